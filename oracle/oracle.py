@@ -1,0 +1,168 @@
+"""ctypes front end of the CPU oracle (TEST INFRASTRUCTURE - not part of the product).
+
+Loads ``dpaps_oracle.c`` compiled for fp32 (``Oracle("f32")``) or fp64
+(``Oracle("f64")``) and exposes the parameter-server primitives (Table
+"Primitives", Sec. 3.1) and the blocked matrix-factorization epoch (Sec. 2.2.2,
+Sec. 4.1) on numpy arrays.  Nothing here is imported by the HIP path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = [os.path.join(_HERE, "dpaps_oracle.c"), os.path.join(_HERE, "kge_oracle.c")]
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-std=c99", "-Wall"]
+
+STAT_NAMES = ["pull_local", "pull_remote", "push_local", "push_remote", "relocated", "localize_keys",
+              "msg_acc_req", "msg_acc_fwd", "msg_acc_reply", "msg_loc_req", "msg_loc_instruct", "msg_loc_transfer"]
+
+OK, EINVAL, EKEY, EWORKER, ECONFLICT, ENOMEM, EREMOTE = 0, -1, -2, -3, -4, -5, -7
+
+
+def lib_path(prec: str) -> str:
+    return os.path.join(_HERE, f"liboracle_{prec}.so")
+
+
+def build(force: bool = False) -> None:
+    """Compile the oracle with gcc for both precisions (a second or two)."""
+    srcs = [s for s in _SRC if os.path.exists(s)]
+    for prec, real in (("f32", "float"), ("f64", "double")):
+        out = lib_path(prec)
+        if not force and os.path.exists(out) and all(os.path.getmtime(out) >= os.path.getmtime(s) for s in srcs):
+            continue
+        subprocess.check_call(["gcc", *CFLAGS, f"-DREAL={real}", "-o", out, *srcs, "-lm"])
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: oracle status {code}")
+        self.code = code
+
+
+class Oracle:
+    """One parameter server (K keys x L values, W workers) on the CPU."""
+
+    def __init__(self, prec: str, num_keys: int, value_len: int, num_workers: int):
+        build()
+        self.prec = prec
+        self.dtype = np.float32 if prec == "f32" else np.float64
+        self._ct = C.c_float if prec == "f32" else C.c_double
+        lib = C.CDLL(lib_path(prec))
+        self.lib = lib
+        lib.orc_ps_create.restype = C.c_void_p
+        lib.orc_ps_create.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        lib.orc_ps_destroy.argtypes = [C.c_void_p]
+        lib.orc_mf_train_sse.restype = C.c_double
+        assert lib.orc_real_bytes() == np.dtype(self.dtype).itemsize
+        self.K, self.L, self.W = int(num_keys), int(value_len), int(num_workers)
+        self.h = lib.orc_ps_create(self.K, self.L, self.W)
+        if not self.h:
+            raise OracleError(EINVAL, "ps_create")
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.orc_ps_destroy(C.c_void_p(self.h))
+            self.h = None
+
+    __del__ = close
+
+    # -- primitives -----------------------------------------------------
+    def _keys(self, keys):
+        return np.ascontiguousarray(keys, dtype=np.int64)
+
+    def pull(self, keys, worker: int = -1) -> np.ndarray:
+        k = self._keys(keys)
+        out = np.empty((k.size, self.L), dtype=self.dtype)
+        rc = self.lib.orc_ps_pull(C.c_void_p(self.h), C.c_int32(worker), _p(k, C.c_int64), C.c_int64(k.size), _p(out, self._ct))
+        if rc:
+            raise OracleError(rc, "pull")
+        return out
+
+    def push(self, keys, deltas, worker: int = -1) -> None:
+        k = self._keys(keys)
+        d = np.ascontiguousarray(deltas, dtype=self.dtype).reshape(k.size, self.L)
+        rc = self.lib.orc_ps_push(C.c_void_p(self.h), C.c_int32(worker), _p(k, C.c_int64), C.c_int64(k.size), _p(d, self._ct))
+        if rc:
+            raise OracleError(rc, "push")
+
+    def localize(self, keys, worker: int) -> None:
+        k = self._keys(keys)
+        rc = self.lib.orc_ps_localize(C.c_void_p(self.h), _p(k, C.c_int64), C.c_int64(k.size), C.c_int32(worker))
+        if rc:
+            raise OracleError(rc, "localize")
+
+    def owner(self, keys=None) -> np.ndarray:
+        k = np.arange(self.K, dtype=np.int64) if keys is None else self._keys(keys)
+        out = np.empty(k.size, dtype=np.int32)
+        rc = self.lib.orc_ps_owner(C.c_void_p(self.h), _p(k, C.c_int64), C.c_int64(k.size), _p(out, C.c_int32))
+        if rc:
+            raise OracleError(rc, "owner")
+        return out
+
+    def home(self, keys=None) -> np.ndarray:
+        k = np.arange(self.K, dtype=np.int64) if keys is None else self._keys(keys)
+        out = np.empty(k.size, dtype=np.int32)
+        rc = self.lib.orc_ps_home(C.c_void_p(self.h), _p(k, C.c_int64), C.c_int64(k.size), _p(out, C.c_int32))
+        if rc:
+            raise OracleError(rc, "home")
+        return out
+
+    def stats(self) -> dict:
+        out = np.zeros(self.lib.orc_stats_count(), dtype=np.int64)
+        self.lib.orc_ps_stats(C.c_void_p(self.h), _p(out, C.c_int64))
+        return dict(zip(STAT_NAMES, (int(x) for x in out)))
+
+    # -- matrix factorization -----------------------------------------------
+    def mf_sgd_epoch(self, m, n, rows, cols, vals, row_bounds, col_bounds, block_ptr, schedule, lr, lam) -> None:
+        """schedule: int32 [S, T, 3] array or list of [T_s, 3] arrays of (worker, row block, col block)."""
+        strata = [np.ascontiguousarray(s, dtype=np.int32).reshape(-1, 3) for s in schedule]
+        tasks = np.concatenate(strata) if strata else np.zeros((0, 3), np.int32)
+        sptr = np.concatenate([[0], np.cumsum([s.shape[0] for s in strata])]).astype(np.int32)
+        rb = np.ascontiguousarray(row_bounds, dtype=np.int64)
+        cb = np.ascontiguousarray(col_bounds, dtype=np.int64)
+        bp = np.ascontiguousarray(block_ptr, dtype=np.int64)
+        assert bp.size == (rb.size - 1) * (cb.size - 1) + 1
+        rows = np.ascontiguousarray(rows, dtype=np.int32)
+        cols = np.ascontiguousarray(cols, dtype=np.int32)
+        vals = np.ascontiguousarray(vals, dtype=np.float32)
+        rc = self.lib.orc_mf_sgd_epoch(
+            C.c_void_p(self.h), C.c_int64(m), C.c_int64(n), _p(rows, C.c_int32), _p(cols, C.c_int32), _p(vals, C.c_float),
+            C.c_int32(rb.size - 1), C.c_int32(cb.size - 1), _p(rb, C.c_int64), _p(cb, C.c_int64), _p(bp, C.c_int64),
+            _p(tasks, C.c_int32), _p(sptr, C.c_int32), C.c_int32(len(strata)),
+            C.c_double(float(np.float32(lr))), C.c_double(float(np.float32(lam))))
+        if rc:
+            raise OracleError(rc, "mf_sgd_epoch")
+
+    def mf_train_sse(self, m, rows, cols, vals) -> float:
+        rows = np.ascontiguousarray(rows, dtype=np.int32)
+        cols = np.ascontiguousarray(cols, dtype=np.int32)
+        vals = np.ascontiguousarray(vals, dtype=np.float32)
+        return float(self.lib.orc_mf_train_sse(C.c_void_p(self.h), C.c_int64(m), C.c_int64(rows.size),
+                                               _p(rows, C.c_int32), _p(cols, C.c_int32), _p(vals, C.c_float)))
+
+
+def mf_block_ratings(m, n, rows, cols, vals, row_bounds, col_bounds):
+    """Entries stored block by block for the subepochs (Sec. 2.2.2); returns
+    (rows, cols, vals, block_ptr)."""
+    build()
+    lib = C.CDLL(lib_path("f32"))
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    cols = np.ascontiguousarray(cols, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    rb = np.ascontiguousarray(row_bounds, dtype=np.int64)
+    cb = np.ascontiguousarray(col_bounds, dtype=np.int64)
+    ro, co, vo = np.empty_like(rows), np.empty_like(cols), np.empty_like(vals)
+    bp = np.zeros((rb.size - 1) * (cb.size - 1) + 1, dtype=np.int64)
+    rc = lib.orc_mf_block_ratings(C.c_int64(m), C.c_int64(n), C.c_int64(rows.size), _p(rows, C.c_int32), _p(cols, C.c_int32),
+                                  _p(vals, C.c_float), C.c_int32(rb.size - 1), C.c_int32(cb.size - 1), _p(rb, C.c_int64),
+                                  _p(cb, C.c_int64), _p(ro, C.c_int32), _p(co, C.c_int32), _p(vo, C.c_float), _p(bp, C.c_int64))
+    if rc:
+        raise OracleError(rc, "mf_block_ratings")
+    return ro, co, vo, bp

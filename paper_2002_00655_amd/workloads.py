@@ -1,0 +1,296 @@
+"""Seeded synthetic inputs for the parameter-server / blocked-SGD path.
+
+This module only draws random numbers and lays out arrays.  It contains none
+of the method's arithmetic (no parameter-server semantics, no SGD step, no
+blocking of ratings), so that the CPU oracle and the HIP library can both be
+fed from it without sharing any code of the method.
+
+The matrix-factorization inputs stand in for the datasets of Section 4.1
+(Table "ML tasks, models, and datasets"), none of which is available: a sparse
+m x n matrix with N revealed entries whose row / column degrees are uniform or
+long-tailed, and whose values come from a planted low-rank model plus noise.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+__all__ = [
+    "MFWorkload", "KGEWorkload", "MF_CONFIGS", "make_mf", "mf_config",
+    "zipf_probs", "equal_bounds", "balanced_bounds", "cyclic_schedule",
+    "random_schedule", "make_kge",
+]
+
+
+# --------------------------------------------------------------------------
+# degree distributions
+# --------------------------------------------------------------------------
+def zipf_probs(size: int, s: float, cap: float, rng: np.random.Generator) -> np.ndarray:
+    """Probabilities proportional to rank**(-s), truncated so none exceeds
+    ``cap`` (the excess is spread over the others in proportion, i.e. by
+    water-filling), then assigned to ids through a random permutation."""
+    w = np.arange(1, size + 1, dtype=np.float64) ** (-float(s))
+    w /= w.sum()
+    if cap * size < 1.0:
+        raise ValueError("cap too small for the number of ids")
+    # t = number of leading (largest) entries clamped to cap.
+    tail = np.concatenate([np.cumsum(w[::-1])[::-1], [0.0]])  # tail[t] = sum_{i>=t} w_i
+    t = 0
+    while t < size:
+        rest = tail[t]
+        scale = (1.0 - t * cap) / rest if rest > 0 else 0.0
+        if w[t] * scale <= cap * (1 + 1e-12):
+            break
+        # jump ahead: every entry i with w[i]*scale > cap must be clamped too
+        nxt = int(np.searchsorted(-w * scale, -cap, side="left"))
+        t = max(t + 1, nxt)
+    p = w.copy()
+    if t > 0:
+        rest = tail[t]
+        p[:t] = cap
+        p[t:] = w[t:] * ((1.0 - t * cap) / rest)
+    p /= p.sum()
+    return p[rng.permutation(size)]
+
+
+def _sample(p: Optional[np.ndarray], size: int, count: int, rng: np.random.Generator) -> np.ndarray:
+    if p is None:
+        return rng.integers(0, size, size=count, dtype=np.int64)
+    cdf = np.cumsum(p)
+    cdf[-1] = 1.0
+    out = np.searchsorted(cdf, rng.random(count), side="right")
+    np.minimum(out, size - 1, out=out)
+    return out.astype(np.int64, copy=False)
+
+
+def _unique_positions(m, n, nnz, p_row, p_col, rng):
+    """Draw (row, col) pairs with independent marginals until ``nnz`` distinct
+    cells exist; return them sorted by (row, col)."""
+    if p_row is None and p_col is None and m * n < (1 << 62):
+        flat = rng.choice(m * n, size=nnz, replace=False)
+        flat.sort()
+        return flat // n, flat % n
+    have = np.empty(0, dtype=np.int64)
+    need = nnz
+    over = 1.08
+    for _ in range(64):
+        cnt = int(need * over) + 1024
+        r = _sample(p_row, m, cnt, rng)
+        c = _sample(p_col, n, cnt, rng)
+        have = np.unique(np.concatenate([have, r * n + c]))
+        if have.size >= nnz:
+            break
+        need = nnz - have.size
+        over = min(over * 1.5, 8.0)
+    else:
+        raise RuntimeError("could not reach the requested number of distinct cells")
+    if have.size > nnz:
+        drop = rng.choice(have.size, size=have.size - nnz, replace=False)
+        keep = np.ones(have.size, dtype=bool)
+        keep[drop] = False
+        have = have[keep]
+    return have // n, have % n
+
+
+def _planted_dot(U: np.ndarray, V: np.ndarray, rows: np.ndarray, cols: np.ndarray) -> np.ndarray:
+    """sum_k U[rows,k]*V[cols,k] in float32, in chunks (input preparation only)."""
+    out = np.empty(rows.size, dtype=np.float32)
+    try:
+        import torch
+        Ut, Vt = torch.from_numpy(U), torch.from_numpy(V)
+        dev = torch.device("cuda") if torch.cuda.is_available() else torch.device("cpu")
+        Ut, Vt = Ut.to(dev), Vt.to(dev)
+        step = 1 << 22 if dev.type == "cuda" else 1 << 20
+        for a in range(0, rows.size, step):
+            ri = torch.from_numpy(rows[a:a + step]).to(dev)
+            ci = torch.from_numpy(cols[a:a + step]).to(dev)
+            out[a:a + step] = (Ut[ri] * Vt[ci]).sum(1).cpu().numpy()
+        return out
+    except ImportError:  # numpy only
+        step = 1 << 19
+        for a in range(0, rows.size, step):
+            out[a:a + step] = np.einsum("ij,ij->i", U[rows[a:a + step]], V[cols[a:a + step]])
+        return out
+
+
+# --------------------------------------------------------------------------
+# matrix factorization workloads
+# --------------------------------------------------------------------------
+@dataclass
+class MFWorkload:
+    name: str
+    m: int
+    n: int
+    rank: int
+    d_row: int
+    d_col: int
+    lr: float
+    lam: float
+    epochs: int
+    rows: np.ndarray            # int32 [nnz], sorted by (row, col)
+    cols: np.ndarray            # int32 [nnz]
+    vals: np.ndarray            # float32 [nnz]
+    W0: np.ndarray              # float32 [m, rank]  initial row factors
+    H0: np.ndarray              # float32 [n, rank]  initial column factors
+    row_bounds: np.ndarray = field(default=None)   # int64 [d_row+1]
+    col_bounds: np.ndarray = field(default=None)   # int64 [d_col+1]
+    noise_std: float = 0.1
+
+    @property
+    def nnz(self) -> int:
+        return int(self.rows.size)
+
+    @property
+    def num_keys(self) -> int:
+        return self.m + self.n
+
+
+# name -> recipe.  "cap" is the largest allowed expected degree as a fraction
+# of the other dimension (no row can hold more entries than there are columns).
+MF_CONFIGS = {
+    # 1,000 x 1,000, 100k entries at uniform cells, planted rank 8, rank 16, 4x4
+    "tiny": dict(m=1000, n=1000, nnz=100_000, row=None, col=None, planted=8, rank=16,
+                 d=4, epochs=1, values="real", seed=0),
+    # 100,000 x 10,000, 10M entries, Zipf(1.0) both sides, planted 32, rank 50, 64x64
+    "medium": dict(m=100_000, n=10_000, nnz=10_000_000, row=1.0, col=1.0, planted=32, rank=50,
+                   d=64, epochs=5, values="real", seed=0),
+    # 480,189 x 17,770, ~100M entries, long-tailed both sides, values 1..5, rank 100, 256x256
+    "large": dict(m=480_189, n=17_770, nnz=100_000_000, row=1.0, col=1.0, planted=100, rank=100,
+                  d=256, epochs=1, values="stars", seed=0),
+    # 10M x 1M, 500M entries, uniform rows, Zipf(1.1) columns, rank 100
+    "wide": dict(m=10_000_000, n=1_000_000, nnz=500_000_000, row=None, col=1.1, planted=100,
+                 rank=100, d=256, epochs=1, values="real", seed=0),
+}
+
+
+def mf_config(name: str, scale: float = 1.0) -> dict:
+    """Recipe of a named configuration; ``scale`` < 1 shrinks m, n and nnz by
+    that factor (same degree laws, same rank and blocking) for quick runs."""
+    cfg = dict(MF_CONFIGS[name])
+    if scale != 1.0:
+        cfg["m"] = max(cfg["d"], int(round(cfg["m"] * scale)))
+        cfg["n"] = max(cfg["d"], int(round(cfg["n"] * scale)))
+        cfg["nnz"] = max(1, int(round(cfg["nnz"] * scale)))
+    cfg["name"] = name if scale == 1.0 else f"{name}@{scale:g}"
+    return cfg
+
+
+def make_mf(name: str = "tiny", scale: float = 1.0, seed: Optional[int] = None,
+            lr: float = 0.01, lam: float = 0.05, **override) -> MFWorkload:
+    cfg = mf_config(name, scale)
+    cfg.update(override)
+    if seed is not None:
+        cfg["seed"] = seed
+    m, n, nnz, rank = cfg["m"], cfg["n"], cfg["nnz"], cfg["rank"]
+    nnz = min(nnz, (m * n) // 2)
+    ss = np.random.SeedSequence(cfg["seed"])
+    g_deg_r, g_deg_c, g_pos, g_fac, g_noise, g_init = [np.random.default_rng(s) for s in ss.spawn(6)]
+
+    p_row = None if cfg["row"] is None else zipf_probs(m, cfg["row"], 0.5 * n / nnz, g_deg_r)
+    p_col = None if cfg["col"] is None else zipf_probs(n, cfg["col"], 0.5 * m / nnz, g_deg_c)
+    r64, c64 = _unique_positions(m, n, nnz, p_row, p_col, g_pos)
+
+    kp = cfg["planted"]
+    sf = kp ** -0.5
+    U = (g_fac.standard_normal((m, kp), dtype=np.float32) * np.float32(sf))
+    V = (g_fac.standard_normal((n, kp), dtype=np.float32) * np.float32(sf))
+    dot = _planted_dot(U, V, r64, c64)
+    noise = g_noise.standard_normal(r64.size, dtype=np.float32) * np.float32(0.1)
+    if cfg["values"] == "stars":
+        # unit-variance planted score shifted to the middle of a 1..5 scale
+        vals = np.rint(np.clip(3.6 + dot * np.float32(kp ** 0.5) + noise, 1.0, 5.0)).astype(np.float32)
+    else:
+        vals = (dot + noise).astype(np.float32)
+    del U, V, dot, noise
+
+    a = np.float32(rank ** -0.5)
+    W0 = ((g_init.random((m, rank), dtype=np.float32) - np.float32(0.5)) * a).astype(np.float32)
+    H0 = ((g_init.random((n, rank), dtype=np.float32) - np.float32(0.5)) * a).astype(np.float32)
+    d = cfg["d"]
+    return MFWorkload(name=cfg["name"], m=m, n=n, rank=rank, d_row=d, d_col=d, lr=lr, lam=lam,
+                      epochs=cfg["epochs"], rows=r64.astype(np.int32), cols=c64.astype(np.int32),
+                      vals=vals, W0=W0, H0=H0, row_bounds=equal_bounds(m, d), col_bounds=equal_bounds(n, d))
+
+
+# --------------------------------------------------------------------------
+# block boundaries and stratum schedules (inputs of the method, not part of it)
+# --------------------------------------------------------------------------
+def equal_bounds(size: int, d: int) -> np.ndarray:
+    """Range partition into d blocks of ceil(size/d) ids (the last may be short or empty)."""
+    step = -(-size // d)
+    return np.minimum(np.arange(d + 1, dtype=np.int64) * step, size)
+
+
+def balanced_bounds(ids: np.ndarray, size: int, d: int) -> np.ndarray:
+    """Contiguous ranges holding roughly equal numbers of entries each."""
+    deg = np.bincount(ids, minlength=size).astype(np.int64)
+    cum = np.concatenate([[0], np.cumsum(deg)])
+    targets = np.arange(d + 1, dtype=np.float64) * (cum[-1] / d)
+    b = np.searchsorted(cum, targets, side="left").astype(np.int64)
+    b[0], b[-1] = 0, size
+    return np.maximum.accumulate(b)
+
+
+def cyclic_schedule(d: int) -> np.ndarray:
+    """int32 [d strata, d tasks, 3] of (worker, row block, column block): in
+    stratum s worker b keeps row block b and takes column block (b+s) mod d."""
+    b = np.arange(d, dtype=np.int32)
+    out = np.empty((d, d, 3), dtype=np.int32)
+    for s in range(d):
+        out[s, :, 0] = b
+        out[s, :, 1] = b
+        out[s, :, 2] = (b + s) % d
+    return out
+
+
+def random_schedule(d: int, rng: np.random.Generator) -> np.ndarray:
+    """A random exact cover of the d x d blocks by d strata (a random Latin
+    square built from shuffled cyclic shifts), with shuffled task order and a
+    random worker assignment per stratum."""
+    rp, cp, sp = rng.permutation(d), rng.permutation(d), rng.permutation(d)
+    out = np.empty((d, d, 3), dtype=np.int32)
+    for k, s in enumerate(sp):
+        order = rng.permutation(d)
+        out[k, :, 0] = rng.permutation(d)
+        out[k, :, 1] = rp[order]
+        out[k, :, 2] = cp[(order + s) % d]
+    return out
+
+
+# --------------------------------------------------------------------------
+# knowledge-graph-embedding workload (Appendix A, "Knowledge graph embeddings")
+# --------------------------------------------------------------------------
+@dataclass
+class KGEWorkload:
+    name: str
+    num_entities: int
+    num_relations: int
+    dim: int                    # complex dimension; an embedding holds 2*dim floats
+    subj: np.ndarray            # int32 [T]
+    rel: np.ndarray             # int32 [T]
+    obj: np.ndarray             # int32 [T]
+    neg_subj: np.ndarray        # int32 [T, n_neg_s]  replacement subjects
+    neg_obj: np.ndarray         # int32 [T, n_neg_o]  replacement objects
+    E0: np.ndarray              # float32 [num_entities, 2*dim]
+    R0: np.ndarray              # float32 [num_relations, 2*dim]
+    lr: float = 0.1
+    eps: float = 1e-10
+
+
+def make_kge(num_entities=500_000, num_relations=600, triples=3_000_000, dim=100,
+             n_neg_s=5, n_neg_o=5, s=1.0, seed=0, name="complex") -> KGEWorkload:
+    ss = np.random.SeedSequence(seed)
+    g_p, g_t, g_n, g_i = [np.random.default_rng(x) for x in ss.spawn(4)]
+    p_e = zipf_probs(num_entities, s, min(1.0, 0.02 + 1.0 / num_entities * 4), g_p)
+    p_r = zipf_probs(num_relations, s, min(1.0, 0.2 + 1.0 / num_relations * 4), g_p)
+    subj = _sample(p_e, num_entities, triples, g_t).astype(np.int32)
+    obj = _sample(p_e, num_entities, triples, g_t).astype(np.int32)
+    rel = _sample(p_r, num_relations, triples, g_t).astype(np.int32)
+    neg_s = g_n.integers(0, num_entities, size=(triples, n_neg_s), dtype=np.int64).astype(np.int32)
+    neg_o = g_n.integers(0, num_entities, size=(triples, n_neg_o), dtype=np.int64).astype(np.int32)
+    E0 = (g_i.standard_normal((num_entities, 2 * dim), dtype=np.float32) * np.float32(0.1))
+    R0 = (g_i.standard_normal((num_relations, 2 * dim), dtype=np.float32) * np.float32(0.1))
+    return KGEWorkload(name=name, num_entities=num_entities, num_relations=num_relations, dim=dim,
+                       subj=subj, rel=rel, obj=obj, neg_subj=neg_s, neg_obj=neg_o, E0=E0, R0=R0)
