@@ -1,0 +1,163 @@
+/*
+ * dpaps - a parameter server with dynamic parameter allocation, and the blocked
+ * latent-factor SGD it drives, on one AMD MI355X (gfx950).
+ *
+ * C ABI.  Every function returns a status (0 = PS_OK, negative = error) and
+ * never throws or prints.  Unless a parameter says "host", a pointer is a
+ * device pointer valid on the device that was current at ps_create; the caller
+ * owns every buffer it passes and may reuse it once the stream has passed the
+ * call.  `stream` is a hipStream_t (NULL = the null stream).  Calls are
+ * asynchronous on that stream and take effect in stream order, which is the
+ * program order of one client (Sec. 3.4, "Asynchronous operations"); one
+ * handle must not be driven from two streams at once.
+ *
+ * Keys are 0 .. num_keys-1; each key holds a vector of value_len fp32 values
+ * (Sec. 4.1 "Settings and measures": "each key held a vector of parameter
+ * values"; dense storage, Sec. 3.7).  There are num_workers workers, each its
+ * own node.  Every key has a static home node, home(k) = k / ceil(num_keys /
+ * num_workers) (range partitioning, Sec. 3.5), and a dynamic owner node,
+ * initially its home (Sec. 3.1 "Location management").
+ *
+ * Errors.  Host-visible mistakes (null pointers, sizes, worker ids, a bad
+ * schedule) are reported by the call itself and nothing is changed.  A key
+ * outside [0, num_keys) is found on the device: the offending call and every
+ * later call on the handle then change nothing, and PS_EKEY is returned by the
+ * next ps_status / ps_stats / mf_train_sse, which also re-arms the handle.
+ */
+#ifndef DPAPS_H
+#define DPAPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dpaps_ps *ps_handle;
+
+enum {
+    PS_OK = 0,
+    PS_EINVAL = -1,     /* null pointer, negative size, value_len out of range, call out of sequence */
+    PS_EKEY = -2,       /* a key, row or column index out of range (deferred, see above) */
+    PS_EWORKER = -3,    /* worker id outside [-1, num_workers) (or [0, num_workers) where a worker is required) */
+    PS_ECONFLICT = -4,  /* two tasks of one stratum share a worker, a row block or a column block */
+    PS_ENOMEM = -5,     /* device or host allocation failed */
+    PS_EHIP = -6,       /* a HIP runtime call failed; ps_last_error gives its text */
+    PS_EREMOTE = -7,    /* an access inside a subepoch was not local (cannot happen through mf_sgd_epoch) */
+    PS_ELAYOUT = -8,    /* entries are not stored block by block with each column's entries contiguous */
+    PS_ELIMIT = -9,     /* a documented capacity limit was exceeded (see mf_load_ratings) */
+    PS_ESTALL = -10     /* internal: a bounded wait inside the SGD kernel ran out (deferred like PS_EKEY) */
+};
+
+/* Integer statistics of a handle (ps_stats).  "Local" and "remote" are judged
+ * against the owner map at the time of the access (Table "reloc-stats": local
+ * / non-local reads).  Message counts follow the home-node strategy without
+ * location caches: a remote access is request -> home, forward -> owner, reply
+ * -> requester (Sec. 3.3 "forward"); a relocation is request -> home, instruct
+ * -> old owner, transfer -> requester (Sec. 3.2).  Within one call, messages to
+ * the same node are grouped into one (Sec. 3.7 "Message grouping"), and a hop
+ * whose two ends are the same node sends nothing. */
+enum {
+    PS_STAT_PULL_LOCAL = 0, PS_STAT_PULL_REMOTE, PS_STAT_PUSH_LOCAL, PS_STAT_PUSH_REMOTE,
+    PS_STAT_RELOCATED,          /* keys whose owner changed */
+    PS_STAT_LOCALIZE_KEYS,      /* keys passed to localize, moved or not */
+    PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY,
+    PS_STAT_MSG_LOC_REQ, PS_STAT_MSG_LOC_INSTRUCT, PS_STAT_MSG_LOC_TRANSFER,
+    PS_STAT_COUNT
+};
+
+/* Options for ps_set_option. */
+enum {
+    PS_OPT_MF_EXACT = 1,        /* 1: the SGD kernel sums each inner product in index order with separately
+                                   rounded multiplies and adds (slow; for bit-for-bit checks).  default 0 */
+    PS_OPT_MF_CACHE_ROWS = 2,   /* upper bound on row factors a workgroup keeps in LDS (-1 = as many as fit) */
+    PS_OPT_MF_WAVES = 3         /* wavefronts per workgroup in the SGD kernel: 1..16 (default 16) */
+};
+
+/* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */
+
+/* Create a server of num_keys x value_len zeros, owner[k] = home(k).
+ * 1 <= value_len <= 256, 1 <= num_workers <= 2048.  *out is owned by the
+ * library until ps_destroy. */
+int ps_create(int64_t num_keys, int32_t value_len, int32_t num_workers, ps_handle *out);
+int ps_destroy(ps_handle ps);
+
+/* pull: out[p*value_len + c] = value of keys[p], wherever the key lives (Sec.
+ * 2.3: location transparency).  Duplicate keys are allowed.  worker = -1 is an
+ * outside client: values only, no locality statistics. */
+int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, float *out, void *stream);
+
+/* push: cumulative (Sec. 2.1) - value[keys[p]] += deltas[p*value_len ..], one
+ * fp32 addition per term.  All terms of a call are applied; those of one key
+ * in increasing p, which makes the result independent of how the device
+ * schedules the work (no floating-point atomics). */
+int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, const float *deltas, void *stream);
+
+/* localize: relocate the keys to `worker` (Sec. 3.1 "API", Sec. 3.2).  The
+ * value is untouched, there is no replica, and the last localize of a key in
+ * stream order decides its owner (Sec. 3.2, localization conflicts). */
+int ps_localize(ps_handle ps, const int64_t *keys, int64_t n, int32_t worker, void *stream);
+
+/* owner_out[p] = current owner of keys[p]. */
+int ps_owner(ps_handle ps, const int64_t *keys, int64_t n, int32_t *owner_out, void *stream);
+
+/* Copy the PS_STAT_COUNT counters to host memory.  Synchronizes the stream. */
+int ps_stats(ps_handle ps, int64_t *host_out, void *stream);
+
+/* Synchronize the stream and report (and clear) a deferred error. */
+int ps_status(ps_handle ps, void *stream);
+
+int ps_set_option(ps_handle ps, int32_t option, int64_t value);
+
+/* Text of the last failure on this handle (host string owned by the library). */
+const char *ps_last_error(ps_handle ps);
+
+/* ---- matrix factorization by parameter blocking (Sec. 2.2.2, Sec. 4.1) --- */
+/* Row i of the m x n matrix is key i, column j is key m + j (num_keys = m + n,
+ * as in Table "ML tasks, models, and datasets"), value_len is the rank.       */
+
+/* Store the revealed entries block by block for the subepochs: block (rb, cb)
+ * holds the entries with row_bounds[rb] <= row < row_bounds[rb+1] and
+ * col_bounds[cb] <= col < col_bounds[cb+1]; blocks are laid out row-block
+ * major.  Inside a block: columns by decreasing number of entries in the block
+ * (ties: smaller column first), a column's entries by increasing row, equal
+ * cells in input order.  rows/cols/vals (nnz each, any order) are read,
+ * rows_out/cols_out/vals_out (nnz each) and block_ptr_host_out (d_row*d_col+1,
+ * host) are written.  Synchronizes the stream. */
+int mf_block_ratings(int64_t m, int64_t n, int64_t nnz, const int32_t *rows, const int32_t *cols, const float *vals,
+                     int32_t d_row, int32_t d_col, const int64_t *row_bounds_host, const int64_t *col_bounds_host,
+                     int32_t *rows_out, int32_t *cols_out, float *vals_out, int64_t *block_ptr_host_out,
+                     void *stream);
+
+/* Hand the blocked entries (layout of mf_block_ratings: block by block, and in
+ * a block the entries of one column contiguous; any order of the columns and
+ * of the rows within a column is accepted and is the processing order) to the
+ * server, which keeps its own copy.  ps must have m + n keys.  Limits
+ * (PS_ELIMIT): nnz < 2^32; in one block at most 65534 rows with two or more
+ * entries, and at most 65535 entries in one row.  Synchronizes the stream. */
+int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, const int32_t *rows, const int32_t *cols,
+                    const float *vals, int32_t d_row, int32_t d_col, const int64_t *row_bounds_host,
+                    const int64_t *col_bounds_host, const int64_t *block_ptr_host, void *stream);
+
+/* One pass over the given strata, in order (Sec. 2.2.2).  tasks_host holds
+ * (worker, row block, column block) triples; stratum s consists of tasks
+ * stratum_ptr_host[s] .. stratum_ptr_host[s+1]-1.  For each stratum: every
+ * task localizes the keys of its row block and of its column block (rows
+ * ascending, then columns ascending); then each task visits the entries of its
+ * block in stored order and for entry (i, j, v) pulls w = value(i), h =
+ * value(m+j), forms e = v - <w,h> and pushes lr*(e*h - lambda*w) to key i and
+ * lr*(e*w - lambda*h) to key m+j; then all tasks meet at a barrier (Appendix A
+ * "Matrix factorization").  The tasks of a stratum must not share a worker or
+ * a block (PS_ECONFLICT).  Each access inside a subepoch is local (Sec. 4.1)
+ * and is counted as such: 2 local pulls and 2 local pushes per entry. */
+int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32_t *stratum_ptr_host, int32_t num_strata,
+                 float lr, float lambda, void *stream);
+
+/* Sum over the loaded entries of (v - <w_i, h_j>)^2, accumulated in fp64 from
+ * the fp32 factors; synchronizes the stream.  Also reports a deferred error. */
+int mf_train_sse(ps_handle ps, double *sse_host_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPAPS_H */

@@ -1,0 +1,78 @@
+// Internal declarations shared by the translation units of libdpaps.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "dpaps.h"
+
+typedef unsigned long long u64;
+
+// Device-resident description of the loaded ratings (built by mf_load_ratings).
+struct MfData {
+    int64_t m = 0, n = 0, nnz = 0;
+    int32_t d_row = 0, d_col = 0;
+    int64_t num_blocks = 0, num_runs = 0, num_multi = 0;
+    int32_t max_multi_in_block = 0;   // largest number of rows with >= 2 entries in any block
+    // per entry, in stored order
+    int32_t *row = nullptr;           // global row index
+    float *val = nullptr;
+    uint32_t *info = nullptr;         // low 16 bits: ticket slot of the row in its block (0xFFFF: only entry of
+                                      // that row in the block); high 16 bits: rank among the row's entries
+    int32_t *col = nullptr;           // column of the entry (kept for mf_train_sse)
+    // per column run (maximal group of consecutive entries of one column inside a block)
+    int64_t *run_start = nullptr;     // num_runs + 1
+    int32_t *run_col = nullptr;       // num_runs
+    int64_t *blk_run_ptr = nullptr;   // num_blocks + 1, index into runs
+    // rows with >= 2 entries in a block, per block, most frequent first
+    int32_t *multi_row = nullptr;     // num_multi
+    int64_t *blk_multi_ptr = nullptr; // num_blocks + 1
+    // block geometry
+    int64_t *row_bounds = nullptr;    // device copy, d_row + 1
+    int64_t *col_bounds = nullptr;    // device copy, d_col + 1
+    std::vector<int64_t> h_row_bounds, h_col_bounds, h_block_ptr;
+};
+
+struct dpaps_ps {
+    int device = 0;
+    int64_t K = 0;
+    int32_t L = 0, W = 0;
+    int64_t per_home = 0;
+    float *val = nullptr;             // K x L, row-major, packed
+    int32_t *owner = nullptr;         // K
+    u64 *stats = nullptr;             // PS_STAT_COUNT counters on the device
+    int32_t *err = nullptr;           // sticky device error flag (0 = fine)
+    // stamps for counting the distinct destinations of one call's messages
+    uint32_t *stamp_h = nullptr, *stamp_o = nullptr, *stamp_pair = nullptr;
+    uint32_t call_id = 0;
+    // growable scratch for ps_push
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    // schedule staging for mf_sgd_epoch
+    int32_t *d_tasks = nullptr;
+    int64_t d_tasks_cap = 0;
+    std::vector<int32_t> h_tasks_cached;
+    // options
+    int opt_exact = 0;
+    int64_t opt_cache_rows = -1;
+    int opt_waves = 16;
+    // device limits
+    int lds_bytes = 65536;
+    int num_cu = 0;
+    MfData mf;
+    double *d_sse = nullptr;
+    std::string last_error;
+};
+
+int dpaps_fail_hip(dpaps_ps *ps, hipError_t e, const char *what);
+int dpaps_ws_reserve(dpaps_ps *ps, size_t bytes);
+
+#define PS_HIP(ps, call)                                                   \
+    do {                                                                   \
+        hipError_t e_ = (call);                                            \
+        if (e_ != hipSuccess) return dpaps_fail_hip((ps), e_, #call);      \
+    } while (0)
+
+__host__ __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }

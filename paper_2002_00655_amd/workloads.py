@@ -218,9 +218,8 @@ def make_mf(name: str = "tiny", scale: float = 1.0, seed: Optional[int] = None,
 # block boundaries and stratum schedules (inputs of the method, not part of it)
 # --------------------------------------------------------------------------
 def equal_bounds(size: int, d: int) -> np.ndarray:
-    """Range partition into d blocks of ceil(size/d) ids (the last may be short or empty)."""
-    step = -(-size // d)
-    return np.minimum(np.arange(d + 1, dtype=np.int64) * step, size)
+    """Range partition into d blocks of floor(size/d) or ceil(size/d) ids."""
+    return (np.arange(d + 1, dtype=np.int64) * size) // d
 
 
 def balanced_bounds(ids: np.ndarray, size: int, d: int) -> np.ndarray:
