@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the blocked matrix-factorization SGD path on one MI355X.
+
+A "step" is one epoch: for every stratum, localize the blocks, then pull / SGD
+step / push for every entry of the stratum's blocks, then the barrier.  The
+inputs (entries, factors, schedule) are resident in device memory before the
+timed region starts.  Prints ONE JSON line on stdout; everything else goes to
+stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|medium|tiny|wide] [--scale S]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, rb, cb, d, target_seconds=15.0):
+    """The CPU oracle (fp32, one thread) timed on a bounded sample: the first
+    strata of one epoch, as many as fit the time target."""
+    from oracle.oracle import Oracle, mf_block_ratings
+    from paper_2002_00655_amd import workloads as wl
+    sched = wl.cyclic_schedule(d)
+    rblk = np.searchsorted(rb, w.rows, side="right") - 1
+    cblk = np.searchsorted(cb, w.cols, side="right") - 1
+    shift = (cblk - rblk) % d                     # stratum of each entry under the cyclic schedule
+    per_stratum = np.bincount(shift, minlength=d)
+    assumed_rate = 4e6                            # only used to size the sample
+    ns = 1
+    while ns < d and per_stratum[:ns + 1].sum() <= assumed_rate * target_seconds:
+        ns += 1
+    sel = shift < ns
+    rows, cols, vals = w.rows[sel], w.cols[sel], w.vals[sel]
+    br, bc, bv, bp = mf_block_ratings(w.m, w.n, rows, cols, vals, rb, cb)
+    orc = Oracle("f32", w.m + w.n, w.rank, d)
+    orc.push(np.arange(w.m), w.W0)
+    orc.push(w.m + np.arange(w.n), w.H0)
+    t0 = time.perf_counter()
+    orc.mf_sgd_epoch(w.m, w.n, br, bc, bv, rb, cb, bp, sched[:ns], w.lr, w.lam)
+    dt = time.perf_counter() - t0
+    return {"value": rows.size / dt, "unit": "updates/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {ns} of {d} strata of one epoch ({rows.size} updates, {dt:.1f} s), fp32 oracle, gcc -O2"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "wide"])
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--bounds", default="equal", choices=["equal", "balanced"])
+    ap.add_argument("--waves", type=int, default=16)
+    ap.add_argument("--cache-rows", type=int, default=-1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU; --gpus must be 1 (no multi-GPU figure is produced)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2002_00655_amd import workloads as wl
+    from paper_2002_00655_amd import ps as P
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda")
+    props = torch.cuda.get_device_properties(0)
+    log(f"device: {props.name} {props.gcnArchName}, {props.multi_processor_count} CUs, host cores {os.cpu_count()}")
+
+    t0 = time.perf_counter()
+    w = wl.make_mf(args.workload, scale=args.scale)
+    d = w.d_row
+    if args.bounds == "balanced":
+        rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d)
+    else:
+        rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d)
+    t_gen = time.perf_counter() - t0
+    log(f"workload {w.name}: {w.m} x {w.n}, nnz {w.nnz}, rank {w.rank}, {d} x {d} blocks ({args.bounds}); generated in {t_gen:.1f} s")
+
+    # data layout on the device (set-up, reported but not part of updates/s)
+    rows_d, cols_d, vals_d = (torch.from_numpy(x).to(dev) for x in (w.rows, w.cols, w.vals))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    br, bc, bv, bp = P.mf_block_ratings(w.m, w.n, rows_d, cols_d, vals_d, rb, cb)
+    torch.cuda.synchronize()
+    t_block = time.perf_counter() - t0
+    del rows_d, cols_d, vals_d
+
+    srv = P.ParameterServer(w.m + w.n, w.rank, d)
+    srv.set_option(P.OPT_MF_WAVES, args.waves)
+    srv.set_option(P.OPT_MF_CACHE_ROWS, args.cache_rows)
+    srv.push(torch.arange(w.m, device=dev), torch.from_numpy(w.W0).to(dev))
+    srv.push(w.m + torch.arange(w.n, device=dev), torch.from_numpy(w.H0).to(dev))
+    t0 = time.perf_counter()
+    srv.mf_load_ratings(w.m, w.n, br, bc, bv, rb, cb, bp)
+    torch.cuda.synchronize()
+    t_load = time.perf_counter() - t0
+    del br, bc, bv
+    log(f"set-up on device: block {t_block * 1e3:.1f} ms, load {t_load * 1e3:.1f} ms")
+
+    from paper_2002_00655_amd.ps import _flatten_schedule
+    tasks, sptr, _ = _flatten_schedule(wl.cyclic_schedule(d))
+    rmse0 = float(np.sqrt(srv.mf_train_sse() / w.nnz))
+
+    for _ in range(args.warmup):
+        srv.mf_sgd_epoch_raw(tasks, sptr, w.lr, w.lam)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        srv.mf_sgd_epoch_raw(tasks, sptr, w.lr, w.lam)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    srv.status()
+    ms_per_step = dt / args.steps * 1e3
+    updates_per_s = w.nnz * args.steps / dt
+    rmse1 = float(np.sqrt(srv.mf_train_sse() / w.nnz))
+    log(f"{args.steps} epochs in {dt:.3f} s: {ms_per_step:.2f} ms/epoch, {updates_per_s / 1e9:.3f} G updates/s; "
+        f"train rmse {rmse0:.4f} -> {rmse1:.4f}")
+
+    # duration of the dominant kernel (one launch per stratum), HIP events on the launch stream
+    srv.set_option(P.OPT_MF_PROFILE, 1)
+    prof_epochs = max(1, min(args.steps, 3))
+    for _ in range(prof_epochs):
+        srv.mf_sgd_epoch_raw(tasks, sptr, w.lr, w.lam)
+    sgd_ms, launches = srv.mf_profile_read()
+    srv.set_option(P.OPT_MF_PROFILE, 0)
+    bytes_per_update = 16 * w.rank + 12            # two rank-r fp32 rows read and written + the 12-byte entry
+    units_per_launch = w.nnz * prof_epochs / launches
+    avg_launch_s = sgd_ms * 1e-3 / launches
+    achieved = bytes_per_update * units_per_launch / avg_launch_s / 1e9
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": None, "kernel": "k_mf_sgd", "avg_launch_us": avg_launch_s * 1e6,
+                "bytes_per_update": bytes_per_update, "updates_per_launch": units_per_launch,
+                "note": "algorithmic bytes (model: 16r+12 per update), not bus traffic"}
+    log(f"k_mf_sgd: {launches} launches, avg {avg_launch_s * 1e6:.1f} us, model {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
+
+    # pull + push rows per second through the C ABI (uniform random keys, value_len = rank)
+    n_keys = 1 << 20
+    g = torch.Generator(device=dev); g.manual_seed(0)
+    keys = torch.randint(0, w.m + w.n, (n_keys,), device=dev, generator=g)
+    deltas = torch.zeros((n_keys, w.rank), device=dev)
+    out = torch.empty((n_keys, w.rank), device=dev)
+    for rep in range(2):
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        for _ in range(5):
+            srv.pull(keys, 0, out=out)
+            srv.push(keys, deltas, 0)
+        torch.cuda.synchronize(); t_pp = (time.perf_counter() - t0) / 5
+    rows_per_s = 2 * n_keys / t_pp
+
+    result = {
+        "metric": "SGD updates/sec, MF rank %d" % w.rank, "value": updates_per_s, "unit": "updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}_mf", "m": w.m, "n": w.n, "nnz": w.nnz, "rank": w.rank, "blocks": f"{d}x{d}",
+                   "bounds": args.bounds, "lr": w.lr, "lambda": w.lam, "waves": args.waves},
+        "model_gbs": updates_per_s * bytes_per_update / 1e9,
+        "model_frac_of_hbm_peak": updates_per_s * bytes_per_update / 1e9 / HBM_PEAK_GBS,
+        "pull_push_rows_per_s": rows_per_s,
+        "setup_ms": {"generate_host": t_gen * 1e3, "block_ratings": t_block * 1e3, "load_ratings": t_load * 1e3},
+        "train_rmse": [rmse0, rmse1],
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a sample ...")
+        result["cpu_baseline"] = cpu_baseline(w, rb, cb, d, args.cpu_seconds)
+        log(f"cpu oracle: {result['cpu_baseline']['value'] / 1e6:.2f} M updates/s ({result['cpu_baseline']['sample']})")
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

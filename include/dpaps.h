@@ -71,7 +71,8 @@ enum {
     PS_OPT_MF_EXACT = 1,        /* 1: the SGD kernel sums each inner product in index order with separately
                                    rounded multiplies and adds (slow; for bit-for-bit checks).  default 0 */
     PS_OPT_MF_CACHE_ROWS = 2,   /* upper bound on row factors a workgroup keeps in LDS (-1 = as many as fit) */
-    PS_OPT_MF_WAVES = 3         /* wavefronts per workgroup in the SGD kernel: 1..16 (default 16) */
+    PS_OPT_MF_WAVES = 3,        /* wavefronts per workgroup in the SGD kernel: 1..16 (default 16) */
+    PS_OPT_MF_PROFILE = 4       /* 1: bracket every SGD kernel launch with a pair of events (see mf_profile_read) */
 };
 
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */
@@ -156,6 +157,11 @@ int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32_t *stratum
 /* Sum over the loaded entries of (v - <w_i, h_j>)^2, accumulated in fp64 from
  * the fp32 factors; synchronizes the stream.  Also reports a deferred error. */
 int mf_train_sse(ps_handle ps, double *sse_host_out, void *stream);
+
+/* With PS_OPT_MF_PROFILE on: synchronize the stream, return the summed duration (milliseconds) of the SGD
+ * kernel launches recorded since the last call and their number, and forget them.  Both outputs are host
+ * pointers.  For measurement only: the events cost a few microseconds per launch. */
+int mf_profile_read(ps_handle ps, double *sgd_ms_host_out, int64_t *launches_host_out, void *stream);
 
 #ifdef __cplusplus
 }

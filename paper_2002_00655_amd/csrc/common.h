@@ -58,6 +58,10 @@ struct dpaps_ps {
     int opt_exact = 0;
     int64_t opt_cache_rows = -1;
     int opt_waves = 16;
+    int opt_profile = 0;
+    // event pairs around the SGD kernel launches (only while profiling is on)
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used = 0;
     // device limits
     int lds_bytes = 65536;
     int num_cu = 0;

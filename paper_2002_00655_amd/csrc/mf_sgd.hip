@@ -412,6 +412,17 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
                   f.blk_multi_ptr, f.row_bounds, f.col_bounds, f.m, L, f.d_col, (int32_t)cache_cap, (int32_t)ticket_cap,
                   lr, lambda, ps->stats, ps->err};
         int rc;
+        hipEvent_t ev0 = nullptr, ev1 = nullptr;
+        if (ps->opt_profile) {
+            while (ps->ev_pool.size() < ps->ev_used + 2) {
+                hipEvent_t e;
+                PS_HIP(ps, hipEventCreate(&e));
+                ps->ev_pool.push_back(e);
+            }
+            ev0 = ps->ev_pool[ps->ev_used]; ev1 = ps->ev_pool[ps->ev_used + 1];
+            ps->ev_used += 2;
+            PS_HIP(ps, hipEventRecord(ev0, st));
+        }
         if (ps->opt_exact) {
             switch (NV) {
             case 1: rc = launch_sgd<1, true>(ps, a, ntasks, threads, lds, st); break;
@@ -428,7 +439,23 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
             }
         }
         if (rc) return rc;
+        if (ev1) PS_HIP(ps, hipEventRecord(ev1, st));
     }
+    return PS_OK;
+}
+
+extern "C" int mf_profile_read(ps_handle ps, double *sgd_ms_host_out, int64_t *launches_host_out, void *stream) {
+    if (!ps || !sgd_ms_host_out || !launches_host_out) return PS_EINVAL;
+    PS_HIP(ps, hipStreamSynchronize((hipStream_t)stream));
+    double total = 0.0;
+    for (size_t i = 0; i + 1 < ps->ev_used; i += 2) {
+        float ms = 0.0f;
+        PS_HIP(ps, hipEventElapsedTime(&ms, ps->ev_pool[i], ps->ev_pool[i + 1]));
+        total += (double)ms;
+    }
+    *sgd_ms_host_out = total;
+    *launches_host_out = (int64_t)(ps->ev_used / 2);
+    ps->ev_used = 0;
     return PS_OK;
 }
 

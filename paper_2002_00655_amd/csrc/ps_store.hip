@@ -207,6 +207,7 @@ extern "C" int ps_destroy(ps_handle ps) {
     if (ps->stamp_h) (void)hipFree(ps->stamp_h);
     if (ps->ws) (void)hipFree(ps->ws);
     if (ps->d_tasks) (void)hipFree(ps->d_tasks);
+    for (hipEvent_t e : ps->ev_pool) (void)hipEventDestroy(e);
     delete ps;
     return PS_OK;
 }
@@ -340,6 +341,7 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
     case PS_OPT_MF_EXACT: ps->opt_exact = value != 0; return PS_OK;
     case PS_OPT_MF_CACHE_ROWS: if (value < -1) return PS_EINVAL; ps->opt_cache_rows = value; return PS_OK;
     case PS_OPT_MF_WAVES: if (value < 1 || value > 16) return PS_EINVAL; ps->opt_waves = (int)value; return PS_OK;
+    case PS_OPT_MF_PROFILE: ps->opt_profile = value != 0; return PS_OK;
     default: return PS_EINVAL;
     }
 }

@@ -20,10 +20,11 @@ PS_OK, PS_EINVAL, PS_EKEY, PS_EWORKER, PS_ECONFLICT, PS_ENOMEM, PS_EHIP, PS_EREM
     0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10
 STAT_NAMES = ["pull_local", "pull_remote", "push_local", "push_remote", "relocated", "localize_keys",
               "msg_acc_req", "msg_acc_fwd", "msg_acc_reply", "msg_loc_req", "msg_loc_instruct", "msg_loc_transfer"]
-OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES = 1, 2, 3
+OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES, OPT_MF_PROFILE = 1, 2, 3, 4
 
 EXPORTS = ["ps_create", "ps_destroy", "ps_pull", "ps_push", "ps_localize", "ps_owner", "ps_stats", "ps_status",
-           "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_train_sse"]
+           "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_train_sse",
+           "mf_profile_read"]
 
 
 class PSError(RuntimeError):
@@ -53,6 +54,7 @@ def load_library() -> C.CDLL:
     lib.mf_load_ratings.argtypes = [vp, i64, i64, i64, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.mf_sgd_epoch.argtypes = [vp, vp, vp, i32, f32, f32, vp]
     lib.mf_train_sse.argtypes = [vp, vp, vp]
+    lib.mf_profile_read.argtypes = [vp, vp, vp, vp]
     for name in EXPORTS:
         if name != "ps_last_error":
             getattr(lib, name).restype = C.c_int
@@ -167,6 +169,12 @@ class ParameterServer:
     def mf_sgd_epoch_raw(self, tasks: np.ndarray, sptr: np.ndarray, lr: float, lam: float) -> None:
         self._check(_lib.mf_sgd_epoch(self._h, tasks.ctypes.data, sptr.ctypes.data, sptr.size - 1, float(lr), float(lam),
                                       _stream()), "mf_sgd_epoch")
+
+    def mf_profile_read(self):
+        """(summed SGD kernel time in ms, number of launches) since the last call; needs OPT_MF_PROFILE."""
+        ms, cnt = C.c_double(0.0), C.c_int64(0)
+        self._check(_lib.mf_profile_read(self._h, C.addressof(ms), C.addressof(cnt), _stream()), "mf_profile_read")
+        return float(ms.value), int(cnt.value)
 
     def mf_train_sse(self) -> float:
         out = C.c_double(0.0)

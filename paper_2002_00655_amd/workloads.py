@@ -55,12 +55,29 @@ def zipf_probs(size: int, s: float, cap: float, rng: np.random.Generator) -> np.
     return p[rng.permutation(size)]
 
 
-def _sample(p: Optional[np.ndarray], size: int, count: int, rng: np.random.Generator) -> np.ndarray:
-    if p is None:
-        return rng.integers(0, size, size=count, dtype=np.int64)
+def _cuda():
+    """torch's CUDA device if there is one (only used to speed up sorting and
+    searching of the drawn numbers; results are identical to the numpy path)."""
+    try:
+        import torch
+        if torch.cuda.is_available():
+            return torch
+    except ImportError:
+        pass
+    return None
+
+
+def _cdf(p: np.ndarray) -> np.ndarray:
     cdf = np.cumsum(p)
     cdf[-1] = 1.0
-    out = np.searchsorted(cdf, rng.random(count), side="right")
+    return cdf
+
+
+def _sample(p: Optional[np.ndarray], size: int, count: int, rng: np.random.Generator) -> np.ndarray:
+    """``count`` ids drawn from probabilities ``p`` (uniform if None) by inverting the CDF."""
+    if p is None:
+        return rng.integers(0, size, size=count, dtype=np.int64)
+    out = np.searchsorted(_cdf(p), rng.random(count), side="right")
     np.minimum(out, size - 1, out=out)
     return out.astype(np.int64, copy=False)
 
@@ -72,20 +89,42 @@ def _unique_positions(m, n, nnz, p_row, p_col, rng):
         flat = rng.choice(m * n, size=nnz, replace=False)
         flat.sort()
         return flat // n, flat % n
+    torch = _cuda()
     have = np.empty(0, dtype=np.int64)
+    if torch is not None:
+        have_t = torch.empty(0, dtype=torch.int64, device="cuda")
+        cdf_r = None if p_row is None else torch.from_numpy(_cdf(p_row)).cuda()
+        cdf_c = None if p_col is None else torch.from_numpy(_cdf(p_col)).cuda()
     need = nnz
     over = 1.08
+    size = 0
     for _ in range(64):
         cnt = int(need * over) + 1024
-        r = _sample(p_row, m, cnt, rng)
-        c = _sample(p_col, n, cnt, rng)
-        have = np.unique(np.concatenate([have, r * n + c]))
-        if have.size >= nnz:
+        if torch is None:
+            r = _sample(p_row, m, cnt, rng)
+            c = _sample(p_col, n, cnt, rng)
+            have = np.unique(np.concatenate([have, r * n + c]))
+            size = have.size
+        else:   # same draws, same arithmetic, sorted on the device
+            def draw(cdf, dim):
+                if cdf is None:
+                    return torch.from_numpy(rng.integers(0, dim, size=cnt, dtype=np.int64)).cuda()
+                u = torch.from_numpy(rng.random(cnt)).cuda()
+                return torch.searchsorted(cdf, u, right=True).clamp_(max=dim - 1)
+            r = draw(cdf_r, m)
+            c = draw(cdf_c, n)
+            have_t = torch.unique(torch.cat([have_t, r * n + c]))
+            del r, c
+            size = int(have_t.numel())
+        if size >= nnz:
             break
-        need = nnz - have.size
+        need = nnz - size
         over = min(over * 1.5, 8.0)
     else:
         raise RuntimeError("could not reach the requested number of distinct cells")
+    if torch is not None:
+        have = have_t.cpu().numpy()
+        del have_t
     if have.size > nnz:
         drop = rng.choice(have.size, size=have.size - nnz, replace=False)
         keep = np.ones(have.size, dtype=bool)
