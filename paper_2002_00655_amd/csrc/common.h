@@ -10,6 +10,10 @@
 
 typedef unsigned long long u64;
 
+#define PS_STAT_SLOTS 64
+#define PS_STAT_STRIDE 16             // u64 per slot: one 128-byte line
+__device__ __forceinline__ u64 *stat_slot(u64 *stats) { return stats + (size_t)(blockIdx.x % PS_STAT_SLOTS) * PS_STAT_STRIDE; }
+
 // Device-resident description of the loaded ratings (built by mf_load_ratings).
 struct MfData {
     int64_t m = 0, n = 0, nnz = 0;
@@ -42,7 +46,9 @@ struct dpaps_ps {
     int64_t per_home = 0;
     float *val = nullptr;             // K x L, row-major, packed
     int32_t *owner = nullptr;         // K
-    u64 *stats = nullptr;             // PS_STAT_COUNT counters on the device
+    u64 *stats = nullptr;             // PS_STAT_SLOTS x PS_STAT_COUNT partial counters on the device (a workgroup
+                                      // adds to slot blockIdx.x % PS_STAT_SLOTS, so that the atomics of one launch
+                                      // spread over many cache lines); ps_stats adds the slots up
     int32_t *err = nullptr;           // sticky device error flag (0 = fine)
     // stamps for counting the distinct destinations of one call's messages
     uint32_t *stamp_h = nullptr, *stamp_o = nullptr, *stamp_pair = nullptr;

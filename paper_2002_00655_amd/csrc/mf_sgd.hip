@@ -123,11 +123,12 @@ __global__ __launch_bounds__(256) void k_mf_localize(LocalizeArgs a) {
         for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_all[i]);
         for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
         if (threadIdx.x == 0) {
-            atomicAdd(&a.stats[PS_STAT_LOCALIZE_KEYS], (u64)((r1 - r0) + (c1 - c0)));
-            if (s_reloc) atomicAdd(&a.stats[PS_STAT_RELOCATED], (u64)s_reloc);
-            if (s_req) atomicAdd(&a.stats[PS_STAT_MSG_LOC_REQ], (u64)s_req);
-            if (s_instr) atomicAdd(&a.stats[PS_STAT_MSG_LOC_INSTRUCT], (u64)s_instr);
-            if (cnt) atomicAdd(&a.stats[PS_STAT_MSG_LOC_TRANSFER], (u64)cnt);
+            u64 *st = stat_slot(a.stats);
+            atomicAdd(&st[PS_STAT_LOCALIZE_KEYS], (u64)((r1 - r0) + (c1 - c0)));
+            if (s_reloc) atomicAdd(&st[PS_STAT_RELOCATED], (u64)s_reloc);
+            if (s_req) atomicAdd(&st[PS_STAT_MSG_LOC_REQ], (u64)s_req);
+            if (s_instr) atomicAdd(&st[PS_STAT_MSG_LOC_INSTRUCT], (u64)s_instr);
+            if (cnt) atomicAdd(&st[PS_STAT_MSG_LOC_TRANSFER], (u64)cnt);
         }
     }
 }
@@ -163,29 +164,37 @@ __device__ __forceinline__ void store_row(float *p, int lane, int L, const float
     for (int c = 0; c < NV; ++c) { int k = lane + 64 * c; if (k < L) p[k] = x[c]; }
 }
 
-// One SGD step on registers.  w, h: the two factor rows (lane l holds
-// components l, l+64, ...; components past L are zero).  Both rows are
-// updated from their old values:
+// One SGD step on registers, in two parts so that other work can be issued
+// between them.  w, h: the two factor rows (lane l holds components l, l+64,
+// ...; components past L are zero).  Both rows are updated from their old values:
 //   e = v - <w,h>;  w += lr (e h - lambda w);  h += lr (e w - lambda h).
+// Part 1: the products of the inner product, per lane.
 template <int NV, bool EXACT>
-__device__ __forceinline__ void sgd_step(float (&w)[NV], float (&h)[NV], float v, float lr, float lambda, int L) {
+__device__ __forceinline__ void sgd_products(const float (&w)[NV], const float (&h)[NV], float (&prod)[NV]) {
+    if constexpr (EXACT) {
+#pragma unroll
+        for (int c = 0; c < NV; ++c) prod[c] = w[c] * h[c];          // every product rounded on its own
+    } else {
+        float p = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NV; ++c) p = __builtin_fmaf(w[c], h[c], p);
+        prod[0] = p;
+    }
+}
+// Part 2: the sum, the error and the two updates.
+template <int NV, bool EXACT>
+__device__ __forceinline__ void sgd_finish(float (&w)[NV], float (&h)[NV], const float (&prod)[NV], float v, float lr,
+                                           float lambda, int L) {
     float dot;
     if constexpr (EXACT) {
-        // components summed in index order, every product and sum rounded on its own
-        float prod[NV];
-#pragma unroll
-        for (int c = 0; c < NV; ++c) prod[c] = w[c] * h[c];
-        dot = 0.0f;
+        dot = 0.0f;                                                   // components summed in index order
 #pragma unroll
         for (int c = 0; c < NV; ++c) {
             const int lim = min(64, L - 64 * c);
             for (int l = 0; l < lim; ++l) dot = dot + rl_f(prod[c], l);
         }
     } else {
-        float p = 0.0f;
-#pragma unroll
-        for (int c = 0; c < NV; ++c) p = __builtin_fmaf(w[c], h[c], p);
-        dot = wave_sum(p);
+        dot = wave_sum(prod[0]);
     }
     const float e = v - dot;
 #pragma unroll
@@ -201,15 +210,57 @@ __device__ __forceinline__ void sgd_step(float (&w)[NV], float (&h)[NV], float v
     }
 }
 
-template <int NV, bool EXACT>
+// LDS accesses of one wavefront are executed in program order, so for data that
+// lives in LDS a ticket needs no waiting on counters: the writer issues the
+// row's ds_writes and then the ticket's ds_write; a reader that issues the
+// ticket's ds_read and then the row's ds_read and finds the expected ticket
+// value has read the finished row.  The empty asm statements only keep the
+// compiler from reordering the accesses around the (relaxed) ticket access.
+__device__ __forceinline__ void compiler_fence() { __asm__ volatile("" ::: "memory"); }
+__device__ __forceinline__ uint32_t ticket_read(uint32_t *tk) {
+    return __hip_atomic_load(tk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void ticket_write(uint32_t *tk, uint32_t v) {
+    __hip_atomic_store(tk, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Row access with lane l holding components l, l+64, ...: only the last of the
+// NV slices can reach past the end of the row, and `tail` says whether this
+// lane's component of that slice exists.
+template <int NV>
+__device__ __forceinline__ void load_row_t(const float *p, int lane, bool tail, float (&x)[NV]) {
+#pragma unroll
+    for (int c = 0; c < NV - 1; ++c) x[c] = p[lane + 64 * c];
+    x[NV - 1] = tail ? p[lane + 64 * (NV - 1)] : 0.0f;
+}
+template <int NV>
+__device__ __forceinline__ void store_row_t(float *p, int lane, bool tail, const float (&x)[NV]) {
+#pragma unroll
+    for (int c = 0; c < NV - 1; ++c) p[lane + 64 * c] = x[c];
+    if (tail) p[lane + 64 * (NV - 1)] = x[NV - 1];
+}
+
+#define INFO_SINGLE 0xFFFFu      // low 16 bits of an info word: the row's only entry in the block
+#define INFO_NONE 0xFFFEu        // filler for lanes past the end of a run: neither single nor in LDS
+
+// D = entries per read-ahead group for rows that are updated in place.  A wavefront keeps the
+// per-entry data of 64 consecutive entries of its run in registers, one entry per lane, and
+// consumes 64 - D of them before it moves on, so that the entry after the current one and the
+// rows of the next group are always found in the same registers.
+template <int NV, bool EXACT, int D>
 __global__ __launch_bounds__(1024) void k_mf_sgd(SgdArgs a) {
     extern __shared__ float lds_f[];
-    if (*(volatile const int32_t *)a.err) return;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    constexpr int CONS = 64 - D;
+    static_assert(CONS % D == 0, "a chunk is a whole number of groups");
+    const int lane = threadIdx.x & 63;
     const int L = a.L;
+    const bool tail = lane + 64 * (NV - 1) < L;
     float *cache = lds_f;                                              // cache_cap x L
     uint32_t *ticket = reinterpret_cast<uint32_t *>(lds_f + (size_t)a.cache_cap * L);   // ticket_cap
     __shared__ int next_run;
+    __shared__ unsigned int done_entries;
+    __shared__ uint32_t give_up;          // set when a bounded wait ran out, so that the other waits end at once
 
     const int32_t worker = a.tasks[3 * blockIdx.x], rb = a.tasks[3 * blockIdx.x + 1], cb = a.tasks[3 * blockIdx.x + 2];
     const int64_t b = (int64_t)rb * a.d_col + cb;
@@ -227,17 +278,21 @@ __global__ __launch_bounds__(1024) void k_mf_sgd(SgdArgs a) {
         for (int64_t k = c0 + threadIdx.x; k < c1; k += blockDim.x) bad |= a.owner[k] != worker;
         if (bad) atomicExch(a.err, PS_EREMOTE);
     }
-    // pull the busiest rows into LDS; reset the tickets
+    // pull the busiest rows into LDS (all threads, several loads in flight each); reset the tickets
     for (int t = threadIdx.x; t < nmulti; t += blockDim.x) ticket[t] = 0;
-    for (int s = wave; s < ncached; s += nwaves) {
-        const float *src = a.val + (int64_t)a.multi_row[mp0 + s] * L;
-        for (int k = lane; k < L; k += 64) cache[(size_t)s * L + k] = src[k];
+    {
+        const int total = ncached * L;
+#pragma unroll 4
+        for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+            const int s = idx / L;
+            cache[idx] = a.val[(int64_t)a.multi_row[mp0 + s] * L + (idx - s * L)];
+        }
     }
-    if (threadIdx.x == 0) next_run = 0;
+    if (threadIdx.x == 0) { next_run = 0; done_entries = 0; give_up = 0; }
     __syncthreads();
 
     const float lr = a.lr, lambda = a.lambda;
-    u64 done = 0;
+    unsigned int done = 0;
     for (;;) {
         int run = 0;
         if (lane == 0) run = atomicAdd(&next_run, 1);
@@ -246,65 +301,166 @@ __global__ __launch_bounds__(1024) void k_mf_sgd(SgdArgs a) {
         if (g >= run1) break;
         const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
         float *hrow = a.val + (a.m + a.run_col[g]) * (int64_t)L;
+        // the long runs come first and everything else in the block ends up waiting for them
+        if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
         float h[NV];
-        load_row<NV>(hrow, lane, L, h);
-        for (int64_t base = s0; base < s1; base += 64) {
-            const int cnt = (s1 - base) < 64 ? (int)(s1 - base) : 64;
-            int my_row = 0; float my_val = 0.0f; int my_info = 0;
-            if (lane < cnt) { my_row = a.e_row[base + lane]; my_val = a.e_val[base + lane]; my_info = (int)a.e_info[base + lane]; }
-            for (int u = 0; u < cnt; ++u) {
-                const int row = rl_i(my_row, u);
-                const float v = rl_f(my_val, u);
-                const uint32_t info = (uint32_t)rl_i(my_info, u);
-                const uint32_t slot = info & 0xFFFFu, seq = info >> 16;
-                float *wrow = a.val + (int64_t)row * L;
-                float w[NV];
-                if (slot == 0xFFFFu) {
-                    // the only entry of this row in the block: read and write in place
-                    load_row<NV>(wrow, lane, L, w);
-                    sgd_step<NV, EXACT>(w, h, v, lr, lambda, L);
-                    store_row<NV>(wrow, lane, L, w);
-                } else {
-                    // wait until the row's earlier entries (in stored order) are done
-                    uint32_t *tk = &ticket[slot];
-                    for (uint32_t spins = 0; __hip_atomic_load(tk, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) != seq;) {
-                        __builtin_amdgcn_s_sleep(1);
-                        // every wait ends: the predecessor always makes progress.  Should that ever fail
-                        // (corrupt input tables), give up rather than hang the device.
-                        if ((++spins & 1023u) == 0 && (spins > (1u << 22) || *(volatile const int32_t *)a.err)) {
-                            atomicExch(a.err, PS_ESTALL);
-                            break;
+        load_row_t<NV>(hrow, lane, tail, h);
+
+        int64_t pos = s0;
+        int m_row = 0, m_info = (int)INFO_NONE;
+        float m_val = 0.0f;
+        if (pos + lane < s1) { m_row = a.e_row[pos + lane]; m_val = a.e_val[pos + lane]; m_info = (int)a.e_info[pos + lane]; }
+
+        // Read-ahead for rows that are updated in place: while a group of D entries is processed
+        // from `cur`, the rows of the next group are in flight into `nxt`.  Every slot is loaded
+        // for every entry - from the column's own row when there is nothing to fetch - so that
+        // the number of loads in flight does not depend on the data.
+        float cur[D][NV], nxt[D][NV];
+#pragma unroll
+        for (int q = 0; q < D; ++q) {
+            const uint32_t inf = (uint32_t)rl_i(m_info, q);
+            const int r = rl_i(m_row, q);
+            const float *src = (inf & 0xFFFFu) == INFO_SINGLE ? a.val + (int64_t)r * L : hrow;
+            load_row_t<NV>(src, lane, tail, nxt[q]);
+        }
+        // Look-ahead for rows kept in LDS: ticket and row of the coming entry are read while the
+        // current entry is being computed.
+        uint32_t info_cur = (uint32_t)rl_i(m_info, 0);
+        uint32_t pk_tk = 0;
+        float pk_w[NV];
+#pragma unroll
+        for (int c = 0; c < NV; ++c) pk_w[c] = 0.0f;
+        if ((info_cur & 0xFFFFu) < (uint32_t)ncached) {
+            pk_tk = ticket_read(&ticket[info_cur & 0xFFFFu]);
+            compiler_fence();
+            load_row_t<NV>(cache + (size_t)(info_cur & 0xFFFFu) * L, lane, tail, pk_w);
+        }
+
+        while (pos < s1) {
+            const int64_t left = s1 - pos;
+            const int avail = left < 64 ? (int)left : 64;            // entries held in the chunk registers
+            const int n_here = left < CONS ? (int)left : CONS;       // entries of this chunk to process
+            // per-entry data of the chunk that follows
+            int n_row = 0, n_info = (int)INFO_NONE;
+            float n_val = 0.0f;
+            {
+                const int64_t p = pos + CONS + lane;
+                if (p < s1) { n_row = a.e_row[p]; n_val = a.e_val[p]; n_info = (int)a.e_info[p]; }
+            }
+            for (int gb = 0; gb < n_here; gb += D) {
+#pragma unroll
+                for (int q = 0; q < D; ++q) {
+#pragma unroll
+                    for (int c = 0; c < NV; ++c) cur[q][c] = nxt[q][c];
+                }
+#pragma unroll
+                for (int q = 0; q < D; ++q) {                         // rows of the next group
+                    const uint32_t inf = (uint32_t)rl_i(m_info, gb + D + q);
+                    const int r = rl_i(m_row, gb + D + q);
+                    const float *src = (inf & 0xFFFFu) == INFO_SINGLE ? a.val + (int64_t)r * L : hrow;
+                    load_row_t<NV>(src, lane, tail, nxt[q]);
+                }
+#pragma unroll
+                for (int q = 0; q < D; ++q) {
+                    const int u = gb + q;
+                    if (u >= n_here) continue;
+                    const uint32_t slot = info_cur & 0xFFFFu, seq = info_cur >> 16;
+                    const float v = rl_f(m_val, u);
+                    const uint32_t info_nx = u + 1 < avail ? (uint32_t)rl_i(m_info, u + 1) : INFO_NONE;
+                    const uint32_t slot_nx = info_nx & 0xFFFFu;
+                    float w[NV], prod[NV];
+                    // The three kinds of entry differ in where the row comes from and goes to; the
+                    // step in between is the same: products, then (while they are summed) the reads
+                    // for the coming entry, then the updates.
+#define DPAPS_STEP()                                                                         \
+    sgd_products<NV, EXACT>(w, h, prod);                                                     \
+    __asm__ volatile("" : "+v"(prod[0]) : : "memory");                                       \
+    if (slot_nx < (uint32_t)ncached) {                                                       \
+        pk_tk = ticket_read(&ticket[slot_nx]);                                               \
+        compiler_fence();                                                                    \
+        load_row_t<NV>(cache + (size_t)slot_nx * L, lane, tail, pk_w);                       \
+    }                                                                                        \
+    sgd_finish<NV, EXACT>(w, h, prod, v, lr, lambda, L)
+                    if (slot == INFO_SINGLE) {
+                        // the row's only entry in the block: fetched ahead, updated in place
+#pragma unroll
+                        for (int c = 0; c < NV; ++c) w[c] = cur[q][c];
+                        DPAPS_STEP();
+                        store_row_t<NV>(a.val + (int64_t)rl_i(m_row, u) * L, lane, tail, w);
+                    } else {
+                        uint32_t *tk = &ticket[slot];
+                        const bool cached = slot < (uint32_t)ncached;
+                        bool have = false;
+                        if (cached && (uint32_t)__builtin_amdgcn_readfirstlane((int)pk_tk) == seq) {
+#pragma unroll
+                            for (int c = 0; c < NV; ++c) w[c] = pk_w[c];
+                            have = true;
+                        } else {
+                            // wait until the row's earlier entries (in stored order) are done
+                            __builtin_amdgcn_s_setprio(0);
+                            for (uint32_t spins = 0; ticket_read(tk) != seq;) {
+                                __builtin_amdgcn_s_sleep(2);
+                                // every wait ends: the predecessor always makes progress.  Should that ever
+                                // fail (corrupt input tables), give up rather than hang the device.
+                                if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                                    ticket_write(&give_up, 1u);
+                                    atomicExch(a.err, PS_ESTALL);
+                                    break;
+                                }
+                            }
+                            compiler_fence();
+                            if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
+                        }
+                        if (cached) {
+                            float *lrow = cache + (size_t)slot * L;      // the row lives in LDS for this subepoch
+                            if (!have) load_row_t<NV>(lrow, lane, tail, w);
+                            DPAPS_STEP();
+                            store_row_t<NV>(lrow, lane, tail, w);
+                            compiler_fence();
+                            ticket_write(tk, seq + 1u);
+                        } else {
+                            float *wrow = a.val + (int64_t)rl_i(m_row, u) * L;   // did not fit: handed over through memory
+                            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                            load_row_t<NV>(wrow, lane, tail, w);
+                            // wait for this load here, on the rare path, so that the common paths are
+                            // not made to wait for the read-ahead in flight
+                            __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
+                            DPAPS_STEP();
+                            store_row_t<NV>(wrow, lane, tail, w);
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                            ticket_write(tk, seq + 1u);
                         }
                     }
-                    if (slot < (uint32_t)ncached) {
-                        float *src = cache + (size_t)slot * L;          // the row lives in LDS for this subepoch
-                        load_row<NV>(src, lane, L, w);
-                        sgd_step<NV, EXACT>(w, h, v, lr, lambda, L);
-                        store_row<NV>(src, lane, L, w);
-                    } else {                                             // did not fit: handed over through memory
-                        load_row<NV>(wrow, lane, L, w);
-                        sgd_step<NV, EXACT>(w, h, v, lr, lambda, L);
-                        store_row<NV>(wrow, lane, L, w);
-                    }
-                    __hip_atomic_store(tk, seq + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+#undef DPAPS_STEP
+                    info_cur = info_nx;
                 }
             }
-            done += (u64)cnt;
+            done += (unsigned int)n_here;
+            pos += CONS;
+            m_row = n_row; m_val = n_val; m_info = n_info;
         }
-        store_row<NV>(hrow, lane, L, h);
+        store_row_t<NV>(hrow, lane, tail, h);
     }
+    __builtin_amdgcn_s_setprio(0);
+    if (lane == 0 && done) atomicAdd(&done_entries, done);
     __syncthreads();
     // push the cached rows back
-    for (int s = wave; s < ncached; s += nwaves) {
-        float *dst = a.val + (int64_t)a.multi_row[mp0 + s] * L;
-        for (int k = lane; k < L; k += 64) dst[k] = cache[(size_t)s * L + k];
+    {
+        const int total = ncached * L;
+#pragma unroll 4
+        for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+            const int s = idx / L;
+            a.val[(int64_t)a.multi_row[mp0 + s] * L + (idx - s * L)] = cache[idx];
+        }
     }
     // each entry was one pull and one push of two local keys
-    if (lane == 0 && done) {
-        atomicAdd(&a.stats[PS_STAT_PULL_LOCAL], 2 * done);
-        atomicAdd(&a.stats[PS_STAT_PUSH_LOCAL], 2 * done);
+    if (threadIdx.x == 0 && done_entries) {
+        u64 *st = stat_slot(a.stats);
+        atomicAdd(&st[PS_STAT_PULL_LOCAL], 2 * (u64)done_entries);
+        atomicAdd(&st[PS_STAT_PUSH_LOCAL], 2 * (u64)done_entries);
     }
 }
+
 
 // ---------------------------------------------------------------------------
 // training error
@@ -336,13 +492,14 @@ int dpaps_take_error(dpaps_ps *ps, hipStream_t st);   // ps_store.hip
 
 template <int NV, bool EXACT>
 static int launch_sgd(dpaps_ps *ps, const SgdArgs &a, int ntasks, int threads, size_t lds, hipStream_t st) {
+    constexpr int D = NV <= 2 ? 16 : 8;       // read-ahead depth (D*NV registers per lane)
     static size_t configured = 0;
     if (lds > configured) {
-        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd<NV, EXACT>),
+        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd<NV, EXACT, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    k_mf_sgd<NV, EXACT><<<ntasks, threads, lds, st>>>(a);
+    k_mf_sgd<NV, EXACT, D><<<ntasks, threads, lds, st>>>(a);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
 }

@@ -83,6 +83,7 @@ __global__ void k_route_access(const int64_t *keys, int64_t n, int32_t worker, c
                                int32_t W, uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id,
                                u64 *stats, int stat_local, int stat_remote, const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
+    stats = stat_slot(stats);
     int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     bool active = p < n;
     int64_t k = active ? keys[p] : 0;
@@ -100,6 +101,7 @@ __global__ void k_localize(const int64_t *keys, int64_t n, int32_t worker, int32
                            uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, u64 *stats,
                            const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
+    stats = stat_slot(stats);
     int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     bool active = p < n;
     int64_t k = active ? keys[p] : 0;
@@ -175,8 +177,9 @@ extern "C" int ps_create(int64_t num_keys, int32_t value_len, int32_t num_worker
     CR(hipMalloc(&ps->val, vbytes));
     CR(hipMemset(ps->val, 0, vbytes));
     CR(hipMalloc(&ps->owner, (size_t)num_keys * sizeof(int32_t)));
-    CR(hipMalloc(&ps->stats, PS_STAT_COUNT * sizeof(u64)));
-    CR(hipMemset(ps->stats, 0, PS_STAT_COUNT * sizeof(u64)));
+    static_assert(PS_STAT_COUNT <= PS_STAT_STRIDE, "a slot holds all counters");
+    CR(hipMalloc(&ps->stats, PS_STAT_SLOTS * PS_STAT_STRIDE * sizeof(u64)));
+    CR(hipMemset(ps->stats, 0, PS_STAT_SLOTS * PS_STAT_STRIDE * sizeof(u64)));
     CR(hipMalloc(&ps->err, sizeof(int32_t)));
     CR(hipMemset(ps->err, 0, sizeof(int32_t)));
     CR(hipMalloc(&ps->d_sse, sizeof(double)));
@@ -331,8 +334,15 @@ extern "C" int ps_status(ps_handle ps, void *stream) {
 extern "C" int ps_stats(ps_handle ps, int64_t *host_out, void *stream) {
     if (!ps || !host_out) return PS_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    PS_HIP(ps, hipMemcpyAsync(host_out, ps->stats, PS_STAT_COUNT * sizeof(u64), hipMemcpyDeviceToHost, st));
-    return dpaps_take_error(ps, st);
+    u64 h[PS_STAT_SLOTS * PS_STAT_STRIDE];
+    PS_HIP(ps, hipMemcpyAsync(h, ps->stats, sizeof(h), hipMemcpyDeviceToHost, st));
+    int rc = dpaps_take_error(ps, st);      // synchronizes
+    for (int c = 0; c < PS_STAT_COUNT; ++c) {
+        u64 sum = 0;
+        for (int sl = 0; sl < PS_STAT_SLOTS; ++sl) sum += h[sl * PS_STAT_STRIDE + c];
+        host_out[c] = (int64_t)sum;
+    }
+    return rc;
 }
 
 extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
