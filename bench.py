@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device copy of 1 GiB five times (reference for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU; --gpus must be 1 (no multi-GPU figure is produced)", file=sys.stderr)
@@ -80,6 +82,14 @@ def main() -> int:
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "copies": 5}))
+        return 0
     props = torch.cuda.get_device_properties(0)
     log(f"device: {props.name} {props.gcnArchName}, {props.multi_processor_count} CUs, host cores {os.cpu_count()}")
 
