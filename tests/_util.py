@@ -49,5 +49,6 @@ def compare_state(orc, srv, exact, atol=1e-4):
         assert bad.size == 0, f"{bad.size} keys differ, first {bad[:5]}"
     else:
         err = np.abs(got.astype(np.float64) - want.astype(np.float64)).max()
+        print(f"  max abs difference to the oracle: {err:.3e}", flush=True)
         assert err <= atol, f"max abs difference {err}"
     return got, want

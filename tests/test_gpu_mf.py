@@ -154,6 +154,7 @@ def _config_parity(w, d, epochs, schedule=None, rmse_each_epoch=False):
     srv = gpu_epochs(w, rb, cb, blocked, sched, epochs=1)
     got, _ = compare_state(o32, srv, exact=False, atol=1e-4)           # after one epoch, vs fp32 oracle
     want64 = o64.pull(np.arange(w.m + w.n))
+    print(f"  max abs difference to the fp64 oracle: {np.abs(got - want64).max():.3e}", flush=True)
     assert np.abs(got - want64).max() <= 1e-4                          # ... and vs the fp64 oracle
     br, bc, bv, bp = blocked
     r_gpu, r_32, r_64 = (_rmse(x, w.nnz) for x in (srv.mf_train_sse(), o32.mf_train_sse(w.m, br, bc, bv), o64.mf_train_sse(w.m, br, bc, bv)))
@@ -186,6 +187,32 @@ def test_large_shape_scaled():
     w = wl.make_mf("large", scale=0.05)
     print(f"case large@0.05 nnz={w.nnz}", flush=True)
     _config_parity(w, 256, epochs=1)
+
+
+def test_large_config_full_size():
+    """480,189 x 17,770, 100M entries, rank 100, 256 x 256 blocks - the configuration and launch shape that
+    bench.py times - one epoch against the fp32 oracle (about a minute of host work)."""
+    import time
+    w = wl.make_mf("large")
+    d = 256
+    print(f"case large nnz={w.nnz}", flush=True)
+    rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d)
+    t0 = time.time()
+    blocked = _blocked_oracle(w, rb, cb)
+    print(f"  oracle layout {time.time() - t0:.0f} s", flush=True)
+    sched = wl.cyclic_schedule(d)
+    t0 = time.time()
+    o32 = oracle_epochs("f32", w, rb, cb, blocked, sched[:128])
+    print(f"  oracle first half of the epoch {time.time() - t0:.0f} s", flush=True)
+    t0 = time.time()
+    o32.mf_sgd_epoch(w.m, w.n, *blocked[:3], rb, cb, blocked[3], sched[128:], w.lr, w.lam)
+    print(f"  oracle second half {time.time() - t0:.0f} s", flush=True)
+    srv = gpu_epochs(w, rb, cb, blocked, sched)
+    compare_state(o32, srv, exact=False, atol=1e-4)
+    br, bc, bv, bp = blocked
+    r_gpu, r_32 = _rmse(srv.mf_train_sse(), w.nnz), _rmse(o32.mf_train_sse(w.m, br, bc, bv), w.nnz)
+    print(f"  rmse gpu {r_gpu:.6f} oracle {r_32:.6f}", flush=True)
+    assert abs(r_gpu - r_32) <= 1e-5 * r_32
 
 
 def test_wide_shape_scaled():
