@@ -72,7 +72,9 @@ enum {
                                    rounded multiplies and adds (slow; for bit-for-bit checks).  default 0 */
     PS_OPT_MF_CACHE_ROWS = 2,   /* upper bound on row factors a workgroup keeps in LDS (-1 = as many as fit) */
     PS_OPT_MF_WAVES = 3,        /* wavefronts per workgroup in the SGD kernel: 1..16 (default 16) */
-    PS_OPT_MF_PROFILE = 4       /* 1: bracket every SGD kernel launch with a pair of events (see mf_profile_read) */
+    PS_OPT_MF_PROFILE = 4,      /* 1: bracket every SGD kernel launch with a pair of events (see mf_profile_read) */
+    PS_OPT_MF_GROUPED = 5       /* 1 (default 0): process a column's entries in groups of up to 15 with dense 16x16xr
+                                   products where rank <= 128 and PS_OPT_MF_EXACT is off; 0: entry by entry */
 };
 
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */
@@ -135,7 +137,7 @@ int mf_block_ratings(int64_t m, int64_t n, int64_t nnz, const int32_t *rows, con
  * of the rows within a column is accepted and is the processing order) to the
  * server, which keeps its own copy.  ps must have m + n keys.  Limits
  * (PS_ELIMIT): nnz < 2^32; in one block at most 65534 rows with two or more
- * entries, and at most 65535 entries in one row.  Synchronizes the stream. */
+ * entries, and at most 32767 entries of one row.  Synchronizes the stream. */
 int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, const int32_t *rows, const int32_t *cols,
                     const float *vals, int32_t d_row, int32_t d_col, const int64_t *row_bounds_host,
                     const int64_t *col_bounds_host, const int64_t *block_ptr_host, void *stream);

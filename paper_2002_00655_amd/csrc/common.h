@@ -23,8 +23,9 @@ struct MfData {
     // per entry, in stored order
     int32_t *row = nullptr;           // global row index
     float *val = nullptr;
-    uint32_t *info = nullptr;         // low 16 bits: ticket slot of the row in its block (0xFFFF: only entry of
-                                      // that row in the block); high 16 bits: rank among the row's entries
+    uint32_t *info = nullptr;         // bits 0-15: ticket slot of the row in its block (0xFFFF: only entry of that
+                                      // row in the block); bits 16-30: rank among the row's entries in the block;
+                                      // bit 31: the row's previous entry is in the same column
     int32_t *col = nullptr;           // column of the entry (kept for mf_train_sse)
     // per column run (maximal group of consecutive entries of one column inside a block)
     int64_t *run_start = nullptr;     // num_runs + 1
@@ -65,6 +66,7 @@ struct dpaps_ps {
     int64_t opt_cache_rows = -1;
     int opt_waves = 16;
     int opt_profile = 0;
+    int opt_grouped = 0;              // 1: use the grouped SGD kernel where it applies
     // event pairs around the SGD kernel launches (only while profiling is on)
     std::vector<hipEvent_t> ev_pool;
     size_t ev_used = 0;
@@ -75,6 +77,27 @@ struct dpaps_ps {
     double *d_sse = nullptr;
     std::string last_error;
 };
+
+// Arguments of the SGD kernels (one launch = the tasks of one stratum).
+struct SgdArgs {
+    const int32_t *tasks;
+    float *val;                 // the parameter store, K x L
+    const int32_t *owner;
+    const int32_t *e_row; const float *e_val; const uint32_t *e_info;
+    const int64_t *run_start; const int32_t *run_col; const int64_t *blk_run_ptr;
+    const int32_t *multi_row; const int64_t *blk_multi_ptr;
+    const int64_t *row_bounds, *col_bounds;
+    int64_t m;
+    int32_t L, d_col;
+    int32_t cache_cap;          // row factors that fit in LDS
+    int32_t ticket_cap;         // ticket counters in LDS
+    float lr, lambda;
+    u64 *stats;
+    int32_t *err;
+};
+
+// mf_sgd_chunk.hip: the kernel that processes a column's entries in groups (see there)
+int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st);
 
 int dpaps_fail_hip(dpaps_ps *ps, hipError_t e, const char *what);
 int dpaps_ws_reserve(dpaps_ps *ps, size_t bytes);

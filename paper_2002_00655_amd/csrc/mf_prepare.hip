@@ -282,18 +282,21 @@ __global__ void k_multi_slots(const uint64_t *mkey_sorted, const uint32_t *mseg_
     seg_slot[s] = (uint32_t)slot;
 }
 
-// info word of every entry: ticket slot of its row in the block and rank among that row's entries
+// info word of every entry: bits 0-15 ticket slot of its row in the block (0xFFFF: the row's only entry
+// there), bits 16-30 rank among that row's entries in the block, bit 31 set when the row's previous entry
+// belongs to the same column (a cell revealed twice)
 __global__ void k_entry_info(const uint32_t *spos, const uint32_t *seg_idx, const uint32_t *seg_start,
-                             const uint32_t *is_multi, const uint32_t *seg_slot, int64_t nnz, uint32_t *info,
-                             int32_t *err) {
+                             const uint32_t *is_multi, const uint32_t *seg_slot, const int32_t *cols, int64_t nnz,
+                             uint32_t *info, int32_t *err) {
     int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nnz) return;
     uint32_t s = seg_idx[q];
     uint32_t w = 0xFFFFu;
     if (is_multi[s]) {
         uint32_t seq = (uint32_t)q - seg_start[s];
-        if (seq > 65535u) { atomicExch(err, PS_ELIMIT); seq = 65535u; }
-        w = seg_slot[s] | (seq << 16);
+        if (seq > 32767u) { atomicExch(err, PS_ELIMIT); seq = 32767u; }
+        uint32_t repeat = (seq > 0 && cols[spos[q]] == cols[spos[q - 1]]) ? 1u : 0u;
+        w = seg_slot[s] | (seq << 16) | (repeat << 31);
     }
     info[spos[q]] = w;
 }
@@ -454,7 +457,7 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
         HIPRC(hipMemsetAsync(f.blk_multi_ptr, 0, (nb + 1) * sizeof(int64_t), st));
     }
     if (nnz > 0) {
-        k_entry_info<<<grid_for(nnz, 256), 256, 0, st>>>(pos_b, seg_idx, seg_start, is_multi, seg_slot, nnz, f.info, d_err);
+        k_entry_info<<<grid_for(nnz, 256), 256, 0, st>>>(pos_b, seg_idx, seg_start, is_multi, seg_slot, f.col, nnz, f.info, d_err);
         HIPRC(hipGetLastError());
         HIPRC(hipMemcpyAsync(&h_err, d_err, sizeof(int32_t), hipMemcpyDeviceToHost, st));
         HIPRC(hipStreamSynchronize(st));

@@ -136,23 +136,6 @@ __global__ __launch_bounds__(256) void k_mf_localize(LocalizeArgs a) {
 // ---------------------------------------------------------------------------
 // the SGD kernel
 // ---------------------------------------------------------------------------
-struct SgdArgs {
-    const int32_t *tasks;
-    float *val;                 // the parameter store, K x L
-    const int32_t *owner;
-    const int32_t *e_row; const float *e_val; const uint32_t *e_info;
-    const int64_t *run_start; const int32_t *run_col; const int64_t *blk_run_ptr;
-    const int32_t *multi_row; const int64_t *blk_multi_ptr;
-    const int64_t *row_bounds, *col_bounds;
-    int64_t m;
-    int32_t L, d_col;
-    int32_t cache_cap;          // row factors that fit in LDS
-    int32_t ticket_cap;         // ticket counters in LDS
-    float lr, lambda;
-    u64 *stats;
-    int32_t *err;
-};
-
 template <int NV>
 __device__ __forceinline__ void load_row(const float *p, int lane, int L, float (&x)[NV]) {
 #pragma unroll
@@ -364,7 +347,7 @@ __global__ __launch_bounds__(1024) void k_mf_sgd(SgdArgs a) {
                 for (int q = 0; q < D; ++q) {
                     const int u = gb + q;
                     if (u >= n_here) continue;
-                    const uint32_t slot = info_cur & 0xFFFFu, seq = info_cur >> 16;
+                    const uint32_t slot = info_cur & 0xFFFFu, seq = (info_cur >> 16) & 0x7FFFu;
                     const float v = rl_f(m_val, u);
                     const uint32_t info_nx = u + 1 < avail ? (uint32_t)rl_i(m_info, u + 1) : INFO_NONE;
                     const uint32_t slot_nx = info_nx & 0xFFFFu;
@@ -580,7 +563,9 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
             ps->ev_used += 2;
             PS_HIP(ps, hipEventRecord(ev0, st));
         }
-        if (ps->opt_exact) {
+        if (ps->opt_grouped && !ps->opt_exact && L <= 128) {
+            rc = dpaps_launch_sgd_chunk(ps, a, ntasks, ps->opt_waves, st);
+        } else if (ps->opt_exact) {
             switch (NV) {
             case 1: rc = launch_sgd<1, true>(ps, a, ntasks, threads, lds, st); break;
             case 2: rc = launch_sgd<2, true>(ps, a, ntasks, threads, lds, st); break;

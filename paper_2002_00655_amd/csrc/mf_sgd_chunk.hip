@@ -1,0 +1,348 @@
+// Blocked latent-factor SGD, grouped form of the per-entry step (Sec. 2.2.2, Sec. 4.1,
+// Appendix A "Matrix factorization" of the paper; same schedule, same stored order and
+// same result, up to rounding, as the entry-by-entry kernel in mf_sgd.hip).
+//
+// Why.  All entries of one column update the same factor row h, so a column's entries
+// form a serial chain, and measured on the device the entry-by-entry kernel is bound by
+// the instruction issue of the wavefront that holds the longest chain, not by memory.
+// The per-entry recursion
+//     e_t = v_t - <w_t, h_{t-1}>,   h_t = c h_{t-1} + lr e_t w_t,   w_t' = c w_t + lr e_t h_{t-1}
+// (c = 1 - lr lambda) is affine in h, so for a group of T consecutive entries of a column
+// (distinct rows w_0 .. w_{T-1}, all final when the group starts) it can be regrouped:
+//   1. X = [w_0; ...; w_{T-1}; h]  (16 x r with T = 15),  G = X X^T  - one dense 16x16xr
+//      product (matrix cores); G[s][15] = <w_s, h> are the T inner products with the
+//      incoming h, G[s][t] = <w_s, w_t>;
+//   2. with p_s = <w_s, h_t> kept per lane, the errors follow from a scalar recurrence,
+//      e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t],  three dependent vector
+//      instructions per entry instead of a length-r reduction;
+//   3. all new rows are one more dense product X' = C X with the lower-triangular 16x16
+//      coefficient matrix  C[t][t] = c,  C[t][s<t] = lr^2 e_t e_s c^(t-1-s),
+//      C[t][15] = lr e_t c^t,  C[15][s] = lr e_s c^(T-1-s),  C[15][15] = c^T.
+// c is never rounded to fp32 on its own (that would bias every update of a row the same
+// way): products with c are formed as x - (lr lambda) x, and the dense product is taken
+// as X' = X + (C - I) X with c - 1 and c^T - 1 computed in double.
+// Dependencies between columns are unchanged: a row with several entries in the block is
+// ordered by its ticket, and a group starts when the rows of all its entries are final.
+// Groups are cut by the data alone (15 entries, the end of the column, or just before an
+// entry whose row already occurs earlier in the same column), never by timing, so the
+// arithmetic - and with it every bit of the result - is the same from run to run.  A
+// group only waits for entries of earlier columns or earlier groups, so waiting ends.
+#include "common.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define CH 15                    // entries per group (the 16th row of X is the column's row)
+#define INFO_SINGLE 0xFFFFu      // low 16 bits of an info word: the row's only entry in the block
+#define INFO_NONE 0xFFFEu        // filler for lanes that hold no entry
+
+__device__ __forceinline__ int rl_i(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ float rl_f(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+// value of `v` in lane `src` (any permutation; goes through the LDS crossbar, no memory)
+__device__ __forceinline__ int bperm_i(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }
+__device__ __forceinline__ float bperm_f(float v, int src) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ void compiler_fence() { __asm__ volatile("" ::: "memory"); }
+__device__ __forceinline__ uint32_t ticket_read(uint32_t *tk) {
+    return __hip_atomic_load(tk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void ticket_write(uint32_t *tk, uint32_t v) {
+    __hip_atomic_store(tk, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// NT = number of 16-component tiles of a factor row (rank <= 16 NT); A4: the rank is a multiple of 4,
+// so every row starts on a 16-byte boundary and is read in 16-byte pieces
+template <int NT, bool A4>
+__global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    constexpr int RS = 16 * NT + 4;          // row stride of the staging area in floats (conflict-free for both read patterns)
+    constexpr int NV = (NT + 3) / 4;         // 64-component slices of a row
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int n16 = lane & 15, hi = lane >> 4;
+    const int L = a.L;
+    const bool tail = lane + 64 * (NV - 1) < L;
+    float *stg = lds_f + (size_t)wave * 16 * RS;                       // this wavefront's X: 16 rows
+    float *cpow = lds_f + (size_t)nwaves * 16 * RS;                    // c^0 .. c^16
+    float *cpm1 = cpow + 20;                                           // c^0 - 1 .. c^16 - 1
+    uint32_t *ticket = reinterpret_cast<uint32_t *>(cpow + 40);         // ticket_cap
+    __shared__ int next_run;
+    __shared__ unsigned int done_entries;
+    __shared__ uint32_t give_up;
+
+    const int32_t worker = a.tasks[3 * blockIdx.x], rb = a.tasks[3 * blockIdx.x + 1], cb = a.tasks[3 * blockIdx.x + 2];
+    const int64_t b = (int64_t)rb * a.d_col + cb;
+    const int64_t run0 = a.blk_run_ptr[b], run1 = a.blk_run_ptr[b + 1];
+    const int nmulti = (int)(a.blk_multi_ptr[b + 1] - a.blk_multi_ptr[b]);
+    const float lr = a.lr, lambda = a.lambda;
+    const float delta = (float)((double)lr * (double)lambda);         // c = 1 - delta
+
+    // every parameter this worker will touch must be allocated to it (Sec. 4.1: all access is local)
+    {
+        const int64_t r0 = a.row_bounds[rb], r1 = a.row_bounds[rb + 1];
+        const int64_t c0 = a.m + a.col_bounds[cb], c1 = a.m + a.col_bounds[cb + 1];
+        bool bad = false;
+        for (int64_t k = r0 + threadIdx.x; k < r1; k += blockDim.x) bad |= a.owner[k] != worker;
+        for (int64_t k = c0 + threadIdx.x; k < c1; k += blockDim.x) bad |= a.owner[k] != worker;
+        if (bad) atomicExch(a.err, PS_EREMOTE);
+    }
+    for (int t = threadIdx.x; t < nmulti; t += blockDim.x) ticket[t] = 0;
+    for (int i = threadIdx.x; i < nwaves * 16 * RS; i += blockDim.x) lds_f[i] = 0.0f;
+    if (threadIdx.x == 0) {
+        const double cd = 1.0 - (double)lr * (double)lambda;
+        double x = 1.0;
+        for (int i = 0; i <= 16; ++i) { cpow[i] = (float)x; cpm1[i] = (float)(x - 1.0); x = x * cd; }
+        next_run = 0; done_entries = 0; give_up = 0;
+    }
+    __syncthreads();
+
+    // constant parts of this lane's coefficients C[t = n16][s = 4 hi + v] for t < 15
+    float kc[4], dg[4], k15[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int s = 4 * hi + v, t = n16;
+        kc[v] = (t < 15 && s < t) ? lr * lr * cpow[t - 1 - s] : 0.0f;
+        dg[v] = (t < 15 && s == t) ? -delta : 0.0f;               // C - I on the diagonal
+        k15[v] = (t < 15 && s == 15) ? lr * cpow[t] : 0.0f;
+    }
+
+    unsigned int done = 0;
+    for (;;) {
+        int run = 0;
+        if (lane == 0) run = atomicAdd(&next_run, 1);
+        run = __builtin_amdgcn_readfirstlane(run);
+        const int64_t g = run0 + run;
+        if (g >= run1) break;
+        const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
+        float *hrow = a.val + (a.m + a.run_col[g]) * (int64_t)L;
+        // the long runs come first and everything else in the block ends up waiting for them
+        if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
+        // the column's row is row 15 of X
+#pragma unroll
+        for (int cc = 0; cc < NV; ++cc) {
+            const int k = lane + 64 * cc;
+            if (cc < NV - 1 || tail) stg[15 * RS + k] = hrow[k];
+        }
+
+        // per-entry data of 64 consecutive entries of the run, one per lane, and of the window 32 further on
+        int64_t wb = s0;
+        int w_row = 0, w_info = (int)INFO_NONE, x_row = 0, x_info = (int)INFO_NONE;
+        float w_val = 0.0f, x_val = 0.0f;
+        if (wb + lane < s1) { w_row = a.e_row[wb + lane]; w_val = a.e_val[wb + lane]; w_info = (int)a.e_info[wb + lane]; }
+        if (wb + 32 + lane < s1) { x_row = a.e_row[wb + 32 + lane]; x_val = a.e_val[wb + 32 + lane]; x_info = (int)a.e_info[wb + 32 + lane]; }
+
+        // Read-ahead of one group: per-entry data in lanes 0..14, whether all its rows are final, and
+        // the rows themselves, gathered straight into the layout of the first dense product: lane
+        // (n16, hi) holds components 16 j + 4 hi .. + 3 of row n16 in xp[j].
+        int pf_row = 0, pf_info = (int)INFO_NONE, pf_n = 0;
+        float pf_val = 0.0f;
+        bool pf_ready = false;
+        f32x4 xp[NT];
+        auto prefetch = [&](int64_t pp) {
+            while (pp - wb >= 32) {                       // slide the windows
+                wb += 32;
+                w_row = x_row; w_val = x_val; w_info = x_info;
+                x_row = 0; x_val = 0.0f; x_info = (int)INFO_NONE;
+                if (wb + 32 + lane < s1) { x_row = a.e_row[wb + 32 + lane]; x_val = a.e_val[wb + 32 + lane]; x_info = (int)a.e_info[wb + 32 + lane]; }
+            }
+            const int o = (int)(pp - wb);
+            const bool valid = lane < CH && pp + lane < s1;
+            pf_row = bperm_i(w_row, o + lane);
+            pf_val = bperm_f(w_val, o + lane);
+            const int inf = bperm_i(w_info, o + lane);          // all lanes take part: a disabled lane would read as 0
+            pf_info = valid ? inf : (int)INFO_NONE;
+            const uint32_t slot = (uint32_t)pf_info & 0xFFFFu, seq = ((uint32_t)pf_info >> 16) & 0x7FFFu;
+            // the group ends before an entry whose row occurs earlier in this column
+            const unsigned long long cut = __ballot(valid && lane > 0 && slot != INFO_SINGLE && ((uint32_t)pf_info >> 31) != 0u);
+            int navail = (s1 - pp) < CH ? (int)(s1 - pp) : CH;
+            if (cut != 0ull && __builtin_ctzll(cut) < navail) navail = __builtin_ctzll(cut);
+            pf_n = navail;
+            bool ready = true;
+            if (lane < navail && slot != INFO_SINGLE) ready = ticket_read(&ticket[slot]) == seq;
+            pf_ready = __ballot(ready) == ~0ull;          // all rows final now, before their loads are issued
+            compiler_fence();
+            const int rid = bperm_i(pf_row, n16);
+            const float *src = n16 < navail ? a.val + (int64_t)rid * L : hrow;     // no entry: any valid row
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                if constexpr (A4) {
+                    xp[j] = *reinterpret_cast<const f32x4 *>(src + 16 * j + 4 * hi);   // may run past the row's end, never past the store's
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) xp[j][q] = 16 * j + 4 * hi + q < L ? src[16 * j + 4 * hi + q] : 0.0f;
+                }
+            }
+        };
+
+        int64_t pos = s0;
+        prefetch(pos);
+        while (pos < s1) {
+            int c_row = pf_row, c_info = pf_info;
+            float c_val = pf_val;
+            const int k = pf_n;                            // entries of this group
+            if (!pf_ready) {
+                // some row was not final when it was read ahead: wait for its earlier entries (in stored
+                // order), then read the rows again
+                const uint32_t slot = (uint32_t)c_info & 0xFFFFu, seq = ((uint32_t)c_info >> 16) & 0x7FFFu;
+                const bool waits = lane < k && slot != INFO_SINGLE;
+                __builtin_amdgcn_s_setprio(0);
+                for (uint32_t spins = 0;;) {
+                    bool ready = true;
+                    if (waits) ready = ticket_read(&ticket[slot]) == seq;
+                    if (__ballot(ready) == ~0ull) break;
+                    __builtin_amdgcn_s_sleep(2);
+                    // every wait ends: the predecessor always makes progress.  Should that ever fail
+                    // (corrupt input tables), give up rather than hang the device.
+                    if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                        ticket_write(&give_up, 1u);
+                        atomicExch(a.err, PS_ESTALL);
+                        break;
+                    }
+                }
+                if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                prefetch(pos);                            // same group, rows as they are now
+            }
+            // X: rows 0 .. 14 from the read-ahead (components past the rank are zero), row 15 is the column's row
+            f32x4 xm[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) xm[j] = xp[j];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (16 * (NT - 1) + 4 * hi + q >= L) xm[NT - 1][q] = 0.0f;
+            if (n16 < 15) {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = xm[j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < NT; ++j) xm[j] = *reinterpret_cast<const f32x4 *>(&stg[15 * RS + 16 * j + 4 * hi]);
+            }
+            // where the rows of the result go: lane (n16, hi) holds rows 4 hi + v of every tile
+            float *dst[4];
+            bool live[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int s = 4 * hi + v;
+                const int r = bperm_i(c_row, s);
+                live[v] = s < k || s == 15;
+                dst[v] = (s == 15 ? hrow : a.val + (int64_t)r * L) + n16;
+            }
+            // read ahead for the group after this one
+            const int64_t pos_next = pos + k;
+            if (pos_next < s1) prefetch(pos_next);
+
+            // ---- G = X X^T ------------------------------------------------------------------
+            f32x4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gm2 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][0], xm[j][0], gm, 0, 0, 0);
+                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][1], xm[j][1], gm2, 0, 0, 0);
+                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][2], xm[j][2], gm, 0, 0, 0);
+                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][3], xm[j][3], gm2, 0, 0, 0);
+            }
+            gm = gm + gm2;
+            // lane (n16, hi) holds G[4 hi + v][n16] = <x_{n16}, x_{4 hi + v}> in gm[v]; gather the whole
+            // row n16 of G into every lane: gg[s] = G[n16][s]
+            float gg[16];
+#pragma unroll
+            for (int h2 = 0; h2 < 4; ++h2) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) gg[4 * h2 + v] = bperm_f(gm[v], 16 * h2 + n16);
+            }
+
+            // ---- the errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t] ---------------------
+            float p = gg[15];                              // p_s = <w_s, h>
+            float e_vec = 0.0f;                            // e_t in every lane with n16 == t
+            const float v_lr = lr;
+#pragma unroll
+            for (int t = 0; t < CH; ++t) {
+                if (t < k) {
+                    const float ecand = c_val - p;         // lane t holds v_t and p_t
+                    const float e = rl_f(ecand, t);
+                    e_vec = n16 == t ? e : e_vec;
+                    p = __builtin_fmaf(v_lr * e, gg[t], __builtin_fmaf(-delta, p, p));
+                }
+            }
+
+            // ---- coefficients (C - I)[t = n16][s = 4 hi + v] ------------------------------------
+            float ca[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int s = 4 * hi + v;
+                const float es = bperm_f(e_vec, s);       // lane s (< 16) holds e_s; e_15 = 0
+                const int pw = k - 1 - s;
+                const float last = s < 15 ? lr * es * cpow[pw > 0 ? pw : 0] : cpm1[k];
+                ca[v] = n16 < 15 ? __builtin_fmaf(e_vec * es, kc[v], __builtin_fmaf(e_vec, k15[v], dg[v])) : last;
+            }
+
+            // ---- X' = X + (C - I) X, tile by tile; rows 0 .. k-1 go to the store, row 15 to the column's
+            //      row in the store and in X
+#pragma unroll
+            for (int tile = 0; tile < NT; ++tile) {
+                float xn[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) xn[v] = stg[(4 * hi + v) * RS + 16 * tile + n16];
+                f32x4 acc = {xn[0], xn[1], xn[2], xn[3]};             // the I of X + (C - I) X: same lane layout as the result
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ca[v], xn[v], acc, 0, 0, 0);
+                if (tile < NT - 1 || 16 * tile + n16 < L) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (live[v]) dst[v][16 * tile] = acc[v];
+                    if (hi == 3) stg[15 * RS + 16 * tile + n16] = acc[3];
+                }
+            }
+            // ---- hand the rows on: the stores must have completed before the tickets move ---------
+            {
+                const uint32_t slot = (uint32_t)c_info & 0xFFFFu, seq = ((uint32_t)c_info >> 16) & 0x7FFFu;
+                const bool bump = lane < k && slot != INFO_SINGLE && slot != INFO_NONE;
+                if (__ballot(bump) != 0) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    if (bump) ticket_write(&ticket[slot], seq + 1u);
+                }
+            }
+            done += (unsigned int)k;
+            pos = pos_next;
+        }
+    }
+    __builtin_amdgcn_s_setprio(0);
+    if (lane == 0 && done) atomicAdd(&done_entries, done);
+    __syncthreads();
+    // each entry was one pull and one push of two local keys
+    if (threadIdx.x == 0 && done_entries) {
+        u64 *st = stat_slot(a.stats);
+        atomicAdd(&st[PS_STAT_PULL_LOCAL], 2 * (u64)done_entries);
+        atomicAdd(&st[PS_STAT_PUSH_LOCAL], 2 * (u64)done_entries);
+    }
+}
+
+template <int NT, bool A4>
+static int launch_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st) {
+    const size_t lds = ((size_t)waves * 16 * (16 * NT + 4) + 40) * sizeof(float) + (size_t)a.ticket_cap * sizeof(uint32_t);
+    if (lds + 1024 > (size_t)ps->lds_bytes) { ps->last_error = "not enough LDS for the grouped SGD kernel"; return PS_ELIMIT; }
+    static size_t configured = 0;
+    if (lds > configured) {
+        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_chunk<NT, A4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = lds;
+    }
+    k_mf_sgd_chunk<NT, A4><<<ntasks, 64 * waves, lds, st>>>(a);
+    PS_HIP(ps, hipGetLastError());
+    return PS_OK;
+}
+
+int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st) {
+    switch ((a.L + 15) / 16) {
+    case 1: return a.L % 4 == 0 ? launch_chunk<1, true>(ps, a, ntasks, waves, st) : launch_chunk<1, false>(ps, a, ntasks, waves, st);
+    case 2: return a.L % 4 == 0 ? launch_chunk<2, true>(ps, a, ntasks, waves, st) : launch_chunk<2, false>(ps, a, ntasks, waves, st);
+    case 3: return a.L % 4 == 0 ? launch_chunk<3, true>(ps, a, ntasks, waves, st) : launch_chunk<3, false>(ps, a, ntasks, waves, st);
+    case 4: return a.L % 4 == 0 ? launch_chunk<4, true>(ps, a, ntasks, waves, st) : launch_chunk<4, false>(ps, a, ntasks, waves, st);
+    case 5: return a.L % 4 == 0 ? launch_chunk<5, true>(ps, a, ntasks, waves, st) : launch_chunk<5, false>(ps, a, ntasks, waves, st);
+    case 6: return a.L % 4 == 0 ? launch_chunk<6, true>(ps, a, ntasks, waves, st) : launch_chunk<6, false>(ps, a, ntasks, waves, st);
+    case 7: return a.L % 4 == 0 ? launch_chunk<7, true>(ps, a, ntasks, waves, st) : launch_chunk<7, false>(ps, a, ntasks, waves, st);
+    case 8: return a.L % 4 == 0 ? launch_chunk<8, true>(ps, a, ntasks, waves, st) : launch_chunk<8, false>(ps, a, ntasks, waves, st);
+    default: return PS_ELIMIT;
+    }
+}

@@ -173,7 +173,8 @@ extern "C" int ps_create(int64_t num_keys, int32_t value_len, int32_t num_worker
     ps->lds_bytes = v;
     CR(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, ps->device));
     ps->num_cu = v;
-    size_t vbytes = (size_t)num_keys * value_len * sizeof(float);
+    // 64 floats of slack after the last row: the grouped SGD kernel reads rows in 16-byte pieces up to the next multiple of 16 components
+    size_t vbytes = ((size_t)num_keys * value_len + 64) * sizeof(float);
     CR(hipMalloc(&ps->val, vbytes));
     CR(hipMemset(ps->val, 0, vbytes));
     CR(hipMalloc(&ps->owner, (size_t)num_keys * sizeof(int32_t)));
@@ -352,6 +353,7 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
     case PS_OPT_MF_CACHE_ROWS: if (value < -1) return PS_EINVAL; ps->opt_cache_rows = value; return PS_OK;
     case PS_OPT_MF_WAVES: if (value < 1 || value > 16) return PS_EINVAL; ps->opt_waves = (int)value; return PS_OK;
     case PS_OPT_MF_PROFILE: ps->opt_profile = value != 0; return PS_OK;
+    case PS_OPT_MF_GROUPED: ps->opt_grouped = value != 0; return PS_OK;
     default: return PS_EINVAL;
     }
 }

@@ -14,7 +14,7 @@ from _util import oracle_epochs, gpu_epochs, compare_state, gpu_values
 
 pytestmark = pytest.mark.gpu
 
-OPT_EXACT, OPT_CACHE, OPT_WAVES = 1, 2, 3
+OPT_EXACT, OPT_CACHE, OPT_WAVES, OPT_GROUPED = 1, 2, 3, 5
 
 
 def _blocked_oracle(w, rb, cb):
@@ -222,6 +222,37 @@ def test_wide_shape_scaled():
     _config_parity(w, 256, epochs=1)
 
 
+@pytest.mark.parametrize("rank,waves,grouped", [(1, 16, 1), (16, 3, 1), (50, 16, 1), (64, 8, 1), (100, 16, 1), (100, 1, 1), (128, 16, 1),
+                                                (100, 16, 0), (50, 4, 0), (130, 16, 1)])
+def test_normal_arithmetic_both_kernels(rank, waves, grouped):
+    """The grouped kernel (dense 16 x 16 x r products per group of entries; ranks up to 128) and the
+    entry-by-entry kernel in its normal arithmetic, with duplicate cells, shuffled rows inside the
+    columns, ragged blocks and a random schedule: within the stated tolerance of the fp32 oracle."""
+    rng = np.random.default_rng(1000 + rank)
+    w = wl.make_mf("tiny", scale=0.4, seed=5, rank=rank)
+    extra = rng.integers(0, w.nnz, 300)
+    w.rows = np.concatenate([w.rows, w.rows[extra]]); w.cols = np.concatenate([w.cols, w.cols[extra]])
+    w.vals = np.concatenate([w.vals, rng.standard_normal(300).astype(np.float32)])
+    d = 3
+    rb = np.array([0, 17, 230, w.m], np.int64)
+    cb = np.array([0, 5, 6, w.n], np.int64)
+    br, bc, bv, bp = _blocked_oracle(w, rb, cb)
+    order = np.arange(br.size)
+    for b in range(d * d):                                  # keep columns grouped, shuffle the rows inside each column
+        seg = np.arange(bp[b], bp[b + 1])
+        key = bc[seg].astype(np.int64) * (br.size + 1) + rng.permutation(seg.size)
+        # stable within the original column order: columns keep their positions
+        colpos = {c: i for i, c in enumerate(dict.fromkeys(bc[seg]))}
+        key = np.array([colpos[c] for c in bc[seg]], np.int64) * (br.size + 1) + rng.permutation(seg.size)
+        order[seg] = seg[np.argsort(key, kind="stable")]
+    blocked = (br[order], bc[order], bv[order], bp)
+    sched = wl.random_schedule(d, rng)
+    print(f"case rank={rank} waves={waves} grouped={grouped} nnz={br.size}", flush=True)
+    orc = oracle_epochs("f32", w, rb, cb, blocked, sched, epochs=2)
+    srv = gpu_epochs(w, rb, cb, blocked, sched, epochs=2, options=[(OPT_WAVES, waves), (OPT_GROUPED, grouped)])
+    compare_state(orc, srv, exact=False, atol=1e-5)
+
+
 def test_exact_sums_need_no_tolerance():
     """Small integer factors, power-of-two step sizes, every row and column used
     once: all sums are exact, so tree-shaped and index-order inner products must
@@ -239,7 +270,7 @@ def test_exact_sums_need_no_tolerance():
         blocked = _blocked_oracle(w, rb, cb)
         sched = wl.cyclic_schedule(2)
         orc = oracle_epochs("f32", w, rb, cb, blocked, sched, lr=0.25, lam=0.5)
-        srv = gpu_epochs(w, rb, cb, blocked, sched, lr=0.25, lam=0.5)
+        srv = gpu_epochs(w, rb, cb, blocked, sched, lr=0.25, lam=0.5, options=[(OPT_GROUPED, 0)])
         compare_state(orc, srv, exact=True)
 
 
