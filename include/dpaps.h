@@ -73,8 +73,11 @@ enum {
     PS_OPT_MF_CACHE_ROWS = 2,   /* upper bound on row factors a workgroup keeps in LDS (-1 = as many as fit) */
     PS_OPT_MF_WAVES = 3,        /* wavefronts per workgroup in the SGD kernel: 1..16 (default 16) */
     PS_OPT_MF_PROFILE = 4,      /* 1: bracket every SGD kernel launch with a pair of events (see mf_profile_read) */
-    PS_OPT_MF_GROUPED = 5       /* 1 (default 0): process a column's entries in groups of up to 15 with dense 16x16xr
-                                   products where rank <= 128 and PS_OPT_MF_EXACT is off; 0: entry by entry */
+    PS_OPT_MF_GROUPED = 5,      /* 1 (default): where rank <= 128 and PS_OPT_MF_EXACT is off, process the long column
+                                   runs of a block in groups of up to 15 entries with dense 16x16xr products and
+                                   the other entries row by row; 0: every column run entry by entry */
+    PS_OPT_MF_HEAVY_LEN = 6     /* column runs with at least this many entries count as long (default 48; read by
+                                   mf_load_ratings, so set it before) */
 };
 
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */

@@ -34,6 +34,22 @@ struct MfData {
     // rows with >= 2 entries in a block, per block, most frequent first
     int32_t *multi_row = nullptr;     // num_multi
     int64_t *blk_multi_ptr = nullptr; // num_blocks + 1
+    // Split of every block for the grouped SGD kernel: its leading column runs of at least heavy_len entries
+    // ("heavy" columns) are processed column by column, the entries of the other runs row by row.  That part
+    // is kept a second time, ordered by (block, row, stored position):
+    int32_t heavy_len = 0;            // the threshold this split was made with
+    bool sweep_ok = false;            // rows ascend inside every run of the second part (needed to walk it by rows)
+    int32_t *blk_nheavy = nullptr;    // num_blocks: heavy runs of the block
+    int64_t num_tail = 0, num_truns = 0;
+    int32_t max_tail_cols = 0;        // largest number of non-heavy runs in any block
+    uint32_t *t_cinfo = nullptr;      // num_tail: bits 0-15 index of the entry's run among the block's non-heavy runs,
+                                      // bits 16-31 its rank inside that run
+    float *t_val = nullptr;           // num_tail
+    uint32_t *trun_start = nullptr;   // num_truns + 1: first entry of a row run
+    int32_t *trun_row = nullptr;      // num_truns: global row index
+    uint32_t *trun_wait = nullptr;    // num_truns: bits 0-15 ticket slot of the row, bits 16-31 the row's entries in heavy
+                                      // runs (the ticket value to wait for); 0xFFFFFFFF: none
+    int64_t *blk_trun_ptr = nullptr;  // num_blocks + 1, index into row runs
     // block geometry
     int64_t *row_bounds = nullptr;    // device copy, d_row + 1
     int64_t *col_bounds = nullptr;    // device copy, d_col + 1
@@ -66,7 +82,8 @@ struct dpaps_ps {
     int64_t opt_cache_rows = -1;
     int opt_waves = 16;
     int opt_profile = 0;
-    int opt_grouped = 0;              // 1: use the grouped SGD kernel where it applies
+    int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
+    int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
     // event pairs around the SGD kernel launches (only while profiling is on)
     std::vector<hipEvent_t> ev_pool;
     size_t ev_used = 0;
@@ -91,6 +108,14 @@ struct SgdArgs {
     int32_t L, d_col;
     int32_t cache_cap;          // row factors that fit in LDS
     int32_t ticket_cap;         // ticket counters in LDS
+    // second part of a block (grouped kernel only)
+    const int32_t *blk_nheavy; const int64_t *blk_trun_ptr;
+    const uint32_t *trun_start; const int32_t *trun_row; const uint32_t *trun_wait;
+    const uint32_t *t_cinfo; const float *t_val;
+    int32_t sweep;              // 0: every run is processed as a heavy run
+    int32_t heavy_waves;        // wavefronts that take heavy runs (each has a staging area in LDS)
+    int32_t ctick_cap;          // column ticket counters in LDS
+    int32_t hcache_cap;         // column factors that fit in LDS
     float lr, lambda;
     u64 *stats;
     int32_t *err;

@@ -172,7 +172,8 @@ done:
 void dpaps_mf_free(dpaps_ps *ps) {
     MfData &f = ps->mf;
     void *ptrs[] = {f.row, f.val, f.info, f.col, f.run_start, f.run_col, f.blk_run_ptr, f.multi_row, f.blk_multi_ptr,
-                    f.row_bounds, f.col_bounds};
+                    f.row_bounds, f.col_bounds, f.blk_nheavy, f.t_cinfo, f.t_val, f.trun_start, f.trun_row, f.trun_wait,
+                    f.blk_trun_ptr};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     ps->mf = MfData();
 }
@@ -306,6 +307,67 @@ __global__ void k_incl_to_seg_idx(const uint32_t *incl, int64_t n, uint32_t *idx
     if (q < n) idx[q] = incl[q] - 1u;
 }
 
+// ---- split of a block into heavy column runs and the rest -----------------------------------------------
+// heavy runs of a block: its leading runs of at least heavy_len entries
+__global__ void k_block_nheavy(const int64_t *blk_run_ptr, const int64_t *run_start, int64_t nb, int32_t heavy_len,
+                               int32_t *nheavy, int32_t *max_tail_cols) {
+    int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= nb) return;
+    int64_t g0 = blk_run_ptr[b], g1 = blk_run_ptr[b + 1], g = g0;
+    while (g < g1 && run_start[g + 1] - run_start[g] >= heavy_len) ++g;
+    nheavy[b] = (int32_t)(g - g0);
+    atomicMax(max_tail_cols, (int32_t)(g1 - g));
+}
+
+// per stored position: index of its run; whether it belongs to a non-heavy run; and the check that rows do
+// not descend inside a non-heavy run
+__global__ void k_tail_flags(const uint32_t *head, const uint32_t *run_excl, const uint32_t *blk, const int64_t *blk_run_ptr,
+                             const int32_t *nheavy, const int32_t *rows, int64_t nnz, uint32_t *runidx, uint32_t *tflag,
+                             int32_t *descends) {
+    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= nnz) return;
+    uint32_t g = run_excl[p] + head[p] - 1u;
+    uint32_t b = blk[p];
+    bool tail = (int64_t)g >= blk_run_ptr[b] + nheavy[b];
+    runidx[p] = g;
+    tflag[p] = tail ? 1u : 0u;
+    if (tail && !head[p] && rows[p] < rows[p - 1]) atomicExch(descends, 1);
+}
+
+// in the order sorted by (block, row): is the entry in the second part, and does it start a row run there
+// (inside a row's group the entries of heavy runs come first, because heavy runs lead the block)
+__global__ void k_tail_sorted(const uint32_t *spos, const uint32_t *tflag, const uint32_t *seg_idx, const uint32_t *seg_start,
+                              int64_t nnz, uint32_t *tq, uint32_t *thead) {
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nnz) return;
+    uint32_t t = tflag[spos[q]];
+    tq[q] = t;
+    thead[q] = (t && (q == seg_start[seg_idx[q]] || !tflag[spos[q - 1]])) ? 1u : 0u;
+}
+
+__global__ void k_tail_fill(const uint32_t *spos, const uint32_t *tq, const uint32_t *tpos, const uint32_t *thead,
+                            const uint32_t *tri, const uint32_t *seg_idx, const uint32_t *seg_start, const uint32_t *is_multi,
+                            const uint32_t *seg_slot, const uint32_t *runidx, const uint32_t *blk, const int64_t *blk_run_ptr,
+                            const int32_t *nheavy, const int64_t *run_start, const int32_t *rows, const float *vals,
+                            int64_t nnz, uint32_t *t_cinfo, float *t_val, uint32_t *trun_start, int32_t *trun_row,
+                            uint32_t *trun_wait, int32_t *err) {
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nnz || !tq[q]) return;
+    uint32_t p = spos[q], t = tpos[q], g = runidx[p], b = blk[p];
+    int64_t cslot = (int64_t)g - (blk_run_ptr[b] + nheavy[b]);
+    int64_t cseq = (int64_t)p - run_start[g];
+    if (cslot >= 65535 || cseq > 65535) { atomicExch(err, PS_ELIMIT); cslot = 0; cseq = 0; }
+    t_cinfo[t] = (uint32_t)cslot | ((uint32_t)cseq << 16);
+    t_val[t] = vals[p];
+    if (thead[q]) {
+        uint32_t j = tri[q], s = seg_idx[q];
+        uint32_t before = (uint32_t)q - seg_start[s];       // the row's entries in heavy runs
+        trun_start[j] = t;
+        trun_row[j] = rows[p];
+        trun_wait[j] = (before > 0 && is_multi[s]) ? (seg_slot[s] | (before << 16)) : 0xFFFFFFFFu;
+    }
+}
+
 extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, const int32_t *rows, const int32_t *cols,
                                const float *vals, int32_t d_row, int32_t d_col, const int64_t *row_bounds_host,
                                const int64_t *col_bounds_host, const int64_t *block_ptr_host, void *stream) {
@@ -336,6 +398,11 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     int32_t *d_err = nullptr; uint64_t *key_a = nullptr, *key_b = nullptr; uint32_t *pos_a = nullptr, *pos_b = nullptr;
     uint32_t *seg_idx = nullptr, *seg_start = nullptr, *is_multi = nullptr, *multi_idx = nullptr, *seg_slot = nullptr;
     u64 *bm_hist = nullptr; char *tmp = nullptr;
+    uint32_t *runidx = nullptr, *tflag = nullptr, *tq = nullptr, *tpos = nullptr;
+    int32_t *d_aux = nullptr;          // [0] largest number of non-heavy runs in a block, [1] rows descend in such a run
+    int32_t h_aux[2] = {0, 0};
+    uint32_t h_tail[4] = {0, 0, 0, 0};
+    int64_t nt = 0, ntr = 0;
     const size_t seen_words = (size_t)(((int64_t)d_row * n + 31) / 32);
     for (int pass = 0; pass < 2; ++pass) {
         a.used = 0;
@@ -348,6 +415,9 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
         seg_idx = a.take<uint32_t>(nnz); seg_start = a.take<uint32_t>(nnz + 1);
         is_multi = a.take<uint32_t>(nnz + 1); multi_idx = a.take<uint32_t>(nnz + 1); seg_slot = a.take<uint32_t>(nnz + 1);
         bm_hist = a.take<u64>(nb);
+        runidx = a.take<uint32_t>(nnz + 1); tflag = a.take<uint32_t>(nnz + 1);
+        tq = a.take<uint32_t>(nnz + 1); tpos = a.take<uint32_t>(nnz + 1);
+        d_aux = a.take<int32_t>(2);
         if (pass == 0) {
             HIPRC(rocprim::radix_sort_pairs(nullptr, tmp_sort64, key_a, key_b, pos_a, pos_b, (size_t)std::max<int64_t>(nnz, 1), 0, 64, st));
             HIPRC(rocprim::exclusive_scan(nullptr, tmp_scan, head, scan, 0u, (size_t)std::max<int64_t>(nnz, 1), rocprim::plus<uint32_t>(), st));
@@ -408,6 +478,17 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     }
     k_blk_ptr_from_scan<<<grid_for(nb + 1, 256), 256, 0, st>>>(d_bp, nb, nnz, scan, num_runs, f.blk_run_ptr);
     HIPRC(hipGetLastError());
+    // --- heavy runs and the rest ---------------------------------------------
+    f.heavy_len = ps->opt_heavy_len;
+    HIPRC(hipMalloc(&f.blk_nheavy, nb * sizeof(int32_t)));
+    HIPRC(hipMalloc(&f.blk_trun_ptr, (nb + 1) * sizeof(int64_t)));
+    HIPRC(hipMemsetAsync(d_aux, 0, 2 * sizeof(int32_t), st));
+    k_block_nheavy<<<grid_for(nb, 256), 256, 0, st>>>(f.blk_run_ptr, f.run_start, nb, f.heavy_len, f.blk_nheavy, d_aux);
+    if (nnz > 0) {
+        k_tail_flags<<<grid_for(nnz, 256), 256, 0, st>>>(head, scan, blk, f.blk_run_ptr, f.blk_nheavy, f.row, nnz, runidx, tflag,
+                                                         d_aux + 1);
+    }
+    HIPRC(hipGetLastError());
 
     if (nnz > 0) {
         // --- rows with several entries in a block --------------------------
@@ -463,7 +544,42 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
         HIPRC(hipStreamSynchronize(st));
         if (h_err) { rc = h_err; goto done; }
     }
+    // --- the non-heavy part once more, by (block, row, stored position) --------
+    if (nnz > 0) {
+        k_tail_sorted<<<grid_for(nnz, 256), 256, 0, st>>>(pos_b, tflag, seg_idx, seg_start, nnz, tq, head);
+        HIPRC(rocprim::exclusive_scan(tmp, tmp_scan, tq, tpos, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), st));
+        HIPRC(rocprim::exclusive_scan(tmp, tmp_scan, head, scan, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), st));
+        HIPRC(hipMemcpyAsync(&h_tail[0], tpos + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIPRC(hipMemcpyAsync(&h_tail[1], tq + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIPRC(hipMemcpyAsync(&h_tail[2], scan + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIPRC(hipMemcpyAsync(&h_tail[3], head + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    }
+    HIPRC(hipMemcpyAsync(h_aux, d_aux, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIPRC(hipStreamSynchronize(st));
+    nt = (int64_t)h_tail[0] + h_tail[1];
+    ntr = (int64_t)h_tail[2] + h_tail[3];
+    f.num_tail = nt; f.num_truns = ntr;
+    f.max_tail_cols = h_aux[0];
+    f.sweep_ok = h_aux[1] == 0;
+    HIPRC(hipMalloc(&f.t_cinfo, std::max<int64_t>(nt, 1) * sizeof(uint32_t)));
+    HIPRC(hipMalloc(&f.t_val, std::max<int64_t>(nt, 1) * sizeof(float)));
+    HIPRC(hipMalloc(&f.trun_start, (ntr + 1) * sizeof(uint32_t)));
+    HIPRC(hipMalloc(&f.trun_row, std::max<int64_t>(ntr, 1) * sizeof(int32_t)));
+    HIPRC(hipMalloc(&f.trun_wait, std::max<int64_t>(ntr, 1) * sizeof(uint32_t)));
+    {
+        const uint32_t end = (uint32_t)nt;
+        HIPRC(hipMemcpyAsync(f.trun_start + ntr, &end, sizeof(uint32_t), hipMemcpyHostToDevice, st));
+    }
+    if (nnz > 0) {
+        k_tail_fill<<<grid_for(nnz, 256), 256, 0, st>>>(pos_b, tq, tpos, head, scan, seg_idx, seg_start, is_multi, seg_slot, runidx,
+                                                        blk, f.blk_run_ptr, f.blk_nheavy, f.run_start, f.row, f.val, nnz, f.t_cinfo,
+                                                        f.t_val, f.trun_start, f.trun_row, f.trun_wait, d_err);
+    }
+    k_blk_ptr_from_scan<<<grid_for(nb + 1, 256), 256, 0, st>>>(d_bp, nb, nnz, scan, ntr, f.blk_trun_ptr);
+    HIPRC(hipGetLastError());
+    HIPRC(hipMemcpyAsync(&h_err, d_err, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIPRC(hipStreamSynchronize(st));
+    if (h_err) { rc = h_err; goto done; }
 done:
     if (dev) (void)hipFree(dev);
     if (rc != PS_OK) dpaps_mf_free(ps);

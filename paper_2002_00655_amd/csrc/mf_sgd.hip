@@ -19,36 +19,12 @@
 //     wavefront to wavefront through global memory;
 //   - a row with a single entry in the block is read and written in place.
 #include "common.h"
+#include "mf_device.h"
 
 #include <algorithm>
 #include <cstring>
 
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
-
-// ---------------------------------------------------------------------------
-// wavefront sum over 64 lanes with DPP; the total is returned in every lane as a
-// wave-uniform value.  Fixed reduction tree, so the result is reproducible.
-// ---------------------------------------------------------------------------
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_add(float x) {
-    int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xF, false);
-    return x + __builtin_bit_cast(float, y);
-}
-
-__device__ __forceinline__ float wave_sum(float x) {
-    x = dpp_add<0xB1, 0xF>(x);    // quad_perm [1,0,3,2]: pairs
-    x = dpp_add<0x4E, 0xF>(x);    // quad_perm [2,3,0,1]: quads
-    x = dpp_add<0x141, 0xF>(x);   // row_half_mirror: 8 lanes
-    x = dpp_add<0x140, 0xF>(x);   // row_mirror: 16 lanes (every lane of a row holds the row's sum)
-    x = dpp_add<0x142, 0xA>(x);   // row_bcast15 into rows 1 and 3
-    x = dpp_add<0x143, 0xC>(x);   // row_bcast31 into rows 2 and 3
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
-}
-
-__device__ __forceinline__ int rl_i(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
-__device__ __forceinline__ float rl_f(float v, int lane) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
-}
 
 // ---------------------------------------------------------------------------
 // localize step of a subepoch: every task takes the keys of its row block and
@@ -192,39 +168,6 @@ __device__ __forceinline__ void sgd_finish(float (&w)[NV], float (&h)[NV], const
         }
     }
 }
-
-// LDS accesses of one wavefront are executed in program order, so for data that
-// lives in LDS a ticket needs no waiting on counters: the writer issues the
-// row's ds_writes and then the ticket's ds_write; a reader that issues the
-// ticket's ds_read and then the row's ds_read and finds the expected ticket
-// value has read the finished row.  The empty asm statements only keep the
-// compiler from reordering the accesses around the (relaxed) ticket access.
-__device__ __forceinline__ void compiler_fence() { __asm__ volatile("" ::: "memory"); }
-__device__ __forceinline__ uint32_t ticket_read(uint32_t *tk) {
-    return __hip_atomic_load(tk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-__device__ __forceinline__ void ticket_write(uint32_t *tk, uint32_t v) {
-    __hip_atomic_store(tk, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-
-// Row access with lane l holding components l, l+64, ...: only the last of the
-// NV slices can reach past the end of the row, and `tail` says whether this
-// lane's component of that slice exists.
-template <int NV>
-__device__ __forceinline__ void load_row_t(const float *p, int lane, bool tail, float (&x)[NV]) {
-#pragma unroll
-    for (int c = 0; c < NV - 1; ++c) x[c] = p[lane + 64 * c];
-    x[NV - 1] = tail ? p[lane + 64 * (NV - 1)] : 0.0f;
-}
-template <int NV>
-__device__ __forceinline__ void store_row_t(float *p, int lane, bool tail, const float (&x)[NV]) {
-#pragma unroll
-    for (int c = 0; c < NV - 1; ++c) p[lane + 64 * c] = x[c];
-    if (tail) p[lane + 64 * (NV - 1)] = x[NV - 1];
-}
-
-#define INFO_SINGLE 0xFFFFu      // low 16 bits of an info word: the row's only entry in the block
-#define INFO_NONE 0xFFFEu        // filler for lanes past the end of a run: neither single nor in LDS
 
 // D = entries per read-ahead group for rows that are updated in place.  A wavefront keeps the
 // per-entry data of 64 consecutive entries of its run in registers, one entry per lane, and
@@ -548,9 +491,18 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
         LocalizeArgs la{tasks, ps->owner, f.row_bounds, f.col_bounds, f.m, ps->per_home, ps->W, ps->stats, ps->err};
         k_mf_localize<<<ntasks, 256, loc_lds, st>>>(la);
         PS_HIP(ps, hipGetLastError());
-        SgdArgs a{tasks, ps->val, ps->owner, f.row, f.val, f.info, f.run_start, f.run_col, f.blk_run_ptr, f.multi_row,
-                  f.blk_multi_ptr, f.row_bounds, f.col_bounds, f.m, L, f.d_col, (int32_t)cache_cap, (int32_t)ticket_cap,
-                  lr, lambda, ps->stats, ps->err};
+        SgdArgs a{};
+        a.tasks = tasks; a.val = ps->val; a.owner = ps->owner;
+        a.e_row = f.row; a.e_val = f.val; a.e_info = f.info;
+        a.run_start = f.run_start; a.run_col = f.run_col; a.blk_run_ptr = f.blk_run_ptr;
+        a.multi_row = f.multi_row; a.blk_multi_ptr = f.blk_multi_ptr;
+        a.row_bounds = f.row_bounds; a.col_bounds = f.col_bounds;
+        a.m = f.m; a.L = L; a.d_col = f.d_col;
+        a.cache_cap = (int32_t)cache_cap; a.ticket_cap = (int32_t)ticket_cap;
+        a.blk_nheavy = f.blk_nheavy; a.blk_trun_ptr = f.blk_trun_ptr;
+        a.trun_start = f.trun_start; a.trun_row = f.trun_row; a.trun_wait = f.trun_wait;
+        a.t_cinfo = f.t_cinfo; a.t_val = f.t_val;
+        a.lr = lr; a.lambda = lambda; a.stats = ps->stats; a.err = ps->err;
         int rc;
         hipEvent_t ev0 = nullptr, ev1 = nullptr;
         if (ps->opt_profile) {

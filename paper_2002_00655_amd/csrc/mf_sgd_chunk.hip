@@ -27,29 +27,30 @@
 // entry whose row already occurs earlier in the same column), never by timing, so the
 // arithmetic - and with it every bit of the result - is the same from run to run.  A
 // group only waits for entries of earlier columns or earlier groups, so waiting ends.
+//
+// Two parts.  Grouping pays for long column runs; a short run would still cost a whole
+// group, and because every column is walked by ascending row, each run's last group ends
+// up waiting for the previous run's, one after the other.  So only the leading runs of a
+// block that are long enough ("heavy" columns) are processed in groups, by the first few
+// wavefronts.  The entries of all other runs are walked row by row: a wavefront takes a few
+// consecutive rows, keeps a row's factor in registers for all of that row's entries, and
+// the factors of the non-heavy columns live in LDS for the subepoch, each with a ticket
+// counter that orders the column's entries as stored.  This is the same dependency graph
+// as walking those runs one after the other - every row's entries in stored order, every
+// column's entries in stored order - so the result is the same; it only takes the waiting
+// out.  A row's entries in heavy runs precede its other entries in stored order (heavy
+// runs lead the block), and the row's ticket tells when they are done.
 #include "common.h"
+#include "mf_device.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define CH 15                    // entries per group (the 16th row of X is the column's row)
-#define INFO_SINGLE 0xFFFFu      // low 16 bits of an info word: the row's only entry in the block
-#define INFO_NONE 0xFFFEu        // filler for lanes that hold no entry
 
-__device__ __forceinline__ int rl_i(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
-__device__ __forceinline__ float rl_f(float v, int lane) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
-}
 // value of `v` in lane `src` (any permutation; goes through the LDS crossbar, no memory)
 __device__ __forceinline__ int bperm_i(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }
 __device__ __forceinline__ float bperm_f(float v, int src) {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, v)));
-}
-__device__ __forceinline__ void compiler_fence() { __asm__ volatile("" ::: "memory"); }
-__device__ __forceinline__ uint32_t ticket_read(uint32_t *tk) {
-    return __hip_atomic_load(tk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-__device__ __forceinline__ void ticket_write(uint32_t *tk, uint32_t v) {
-    __hip_atomic_store(tk, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // NT = number of 16-component tiles of a factor row (rank <= 16 NT); A4: the rank is a multiple of 4,
@@ -64,11 +65,15 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     const int n16 = lane & 15, hi = lane >> 4;
     const int L = a.L;
     const bool tail = lane + 64 * (NV - 1) < L;
-    float *stg = lds_f + (size_t)wave * 16 * RS;                       // this wavefront's X: 16 rows
-    float *cpow = lds_f + (size_t)nwaves * 16 * RS;                    // c^0 .. c^16
+    const int hwaves = a.heavy_waves;                                  // wavefronts 0 .. hwaves-1 take the heavy runs
+    float *stg = lds_f + (size_t)wave * 16 * RS;                       // this wavefront's X: 16 rows (heavy wavefronts only)
+    float *cpow = lds_f + (size_t)hwaves * 16 * RS;                    // c^0 .. c^16
     float *cpm1 = cpow + 20;                                           // c^0 - 1 .. c^16 - 1
-    uint32_t *ticket = reinterpret_cast<uint32_t *>(cpow + 40);         // ticket_cap
+    uint32_t *ticket = reinterpret_cast<uint32_t *>(cpow + 40);         // ticket_cap: one per row with several entries
+    uint32_t *ctick = ticket + a.ticket_cap;                           // ctick_cap: one per non-heavy column
+    float *hcache = reinterpret_cast<float *>(ctick + a.ctick_cap);    // hcache_cap x L: factors of non-heavy columns
     __shared__ int next_run;
+    __shared__ int next_trow;
     __shared__ unsigned int done_entries;
     __shared__ uint32_t give_up;
 
@@ -76,6 +81,11 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     const int64_t b = (int64_t)rb * a.d_col + cb;
     const int64_t run0 = a.blk_run_ptr[b], run1 = a.blk_run_ptr[b + 1];
     const int nmulti = (int)(a.blk_multi_ptr[b + 1] - a.blk_multi_ptr[b]);
+    const int nruns = (int)(run1 - run0);
+    const int nheavy = a.sweep ? a.blk_nheavy[b] : nruns;
+    const int ntcols = nruns - nheavy;                                 // non-heavy columns
+    const int ncached = min(ntcols, a.hcache_cap);
+    const int64_t tr0 = a.sweep ? a.blk_trun_ptr[b] : 0, tr1 = a.sweep ? a.blk_trun_ptr[b + 1] : 0;
     const float lr = a.lr, lambda = a.lambda;
     const float delta = (float)((double)lr * (double)lambda);         // c = 1 - delta
 
@@ -89,12 +99,21 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
         if (bad) atomicExch(a.err, PS_EREMOTE);
     }
     for (int t = threadIdx.x; t < nmulti; t += blockDim.x) ticket[t] = 0;
-    for (int i = threadIdx.x; i < nwaves * 16 * RS; i += blockDim.x) lds_f[i] = 0.0f;
+    for (int t = threadIdx.x; t < ntcols; t += blockDim.x) ctick[t] = 0;
+    for (int i = threadIdx.x; i < hwaves * 16 * RS; i += blockDim.x) lds_f[i] = 0.0f;
+    {
+        const int total = ncached * L;
+#pragma unroll 4
+        for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+            const int s = idx / L;
+            hcache[idx] = a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)];
+        }
+    }
     if (threadIdx.x == 0) {
         const double cd = 1.0 - (double)lr * (double)lambda;
         double x = 1.0;
         for (int i = 0; i <= 16; ++i) { cpow[i] = (float)x; cpm1[i] = (float)(x - 1.0); x = x * cd; }
-        next_run = 0; done_entries = 0; give_up = 0;
+        next_run = 0; next_trow = 0; done_entries = 0; give_up = 0;
     }
     __syncthreads();
 
@@ -109,12 +128,13 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     }
 
     unsigned int done = 0;
-    for (;;) {
+    // ---- part 1: the heavy runs, in groups ----------------------------------------------
+    if (wave < hwaves) for (;;) {
         int run = 0;
         if (lane == 0) run = atomicAdd(&next_run, 1);
         run = __builtin_amdgcn_readfirstlane(run);
+        if (run >= nheavy) break;
         const int64_t g = run0 + run;
-        if (g >= run1) break;
         const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
         float *hrow = a.val + (a.m + a.run_col[g]) * (int64_t)L;
         // the long runs come first and everything else in the block ends up waiting for them
@@ -307,9 +327,155 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
             pos = pos_next;
         }
     }
+
+    // ---- part 2: the other runs, row by row ---------------------------------------------
+    // Consecutive rows tend to meet in some column, so they should be worked on by different
+    // wavefronts at the same time.  The row runs are dealt out in batches of D rows that lie P apart:
+    // D P consecutive row runs make P batches, batch p holding runs p, p + P, p + 2 P, ...  A wavefront
+    // takes the next batch, waits until the heavy runs have passed its rows, reads their entries and
+    // factors in one go and then works through them in ascending order.  Batches are taken in order and
+    // P is at most the number of wavefronts, so the batch that holds the lowest unfinished row is either
+    // being worked on or will be taken by a wavefront that finishes (the heavy runs never wait for this
+    // part): every wait ends.  P is the number of wavefronts that are free for this part from the start.
+    __builtin_amdgcn_s_setprio(1);
+    if (tr1 > tr0) {
+        constexpr int D = 8;
+        const int ntrow = (int)(tr1 - tr0);
+        const int P = nwaves > hwaves ? nwaves - hwaves : nwaves;
+        const int nbatch = (ntrow + D * P - 1) / (D * P) * P;
+        for (;;) {
+            int k = 0;
+            if (lane == 0) k = atomicAdd(&next_trow, 1);
+            k = __builtin_amdgcn_readfirstlane(k);
+            if (k >= nbatch) break;
+            const int jb = (k / P) * (D * P) + (k % P);
+            // lane i < D: row run jb + i P
+            int r_row = -1;
+            uint32_t r_e0 = 0, r_e1 = 0, r_wait = 0xFFFFFFFFu;
+            {
+                const int j = jb + lane * P;
+                if (lane < D && j < ntrow) {
+                    r_row = a.trun_row[tr0 + j]; r_e0 = a.trun_start[tr0 + j]; r_e1 = a.trun_start[tr0 + j + 1];
+                    r_wait = a.trun_wait[tr0 + j];
+                }
+            }
+            // entries of every row (one per lane) and, where the row's entries in heavy runs are done, its factor
+            float w[D][NV], ev[D];
+            uint32_t ci[D];
+            uint32_t loaded = 0;
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                const int row = rl_i(r_row, i);
+                const uint32_t e0 = (uint32_t)rl_i((int)r_e0, i), e1 = (uint32_t)rl_i((int)r_e1, i);
+                const uint32_t wt = (uint32_t)rl_i((int)r_wait, i);
+                ci[i] = 0; ev[i] = 0.0f;
+#pragma unroll
+                for (int cc = 0; cc < NV; ++cc) w[i][cc] = 0.0f;
+                if (e0 + lane < e1) { ci[i] = a.t_cinfo[e0 + lane]; ev[i] = a.t_val[e0 + lane]; }
+                if (row >= 0) {
+                    bool ok = true;
+                    if (wt != 0xFFFFFFFFu) {
+                        // the row's entries in heavy runs first
+                        uint32_t *tk = &ticket[wt & 0xFFFFu];
+                        __builtin_amdgcn_s_setprio(0);
+                        for (uint32_t spins = 0; ticket_read(tk) != (wt >> 16);) {
+                            __builtin_amdgcn_s_sleep(4);
+                            if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                                ticket_write(&give_up, 1u);
+                                atomicExch(a.err, PS_ESTALL);
+                                ok = false;
+                                break;
+                            }
+                        }
+                        __builtin_amdgcn_s_setprio(1);
+                    }
+                    if (ok) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                        load_row_t<NV>(a.val + (int64_t)row * L, lane, tail, w[i]);
+                        loaded |= 1u << i;
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                const int row = rl_i(r_row, i);
+                if (row < 0) continue;
+                const uint32_t e0 = (uint32_t)rl_i((int)r_e0, i), e1 = (uint32_t)rl_i((int)r_e1, i);
+                float *wrow = a.val + (int64_t)row * L;
+                if (!((loaded >> i) & 1u)) {
+                    // wait for the row's entries in heavy runs, then read its factor
+                    const uint32_t wt = (uint32_t)rl_i((int)r_wait, i);
+                    uint32_t *tk = &ticket[wt & 0xFFFFu];
+                    __builtin_amdgcn_s_setprio(0);
+                    for (uint32_t spins = 0; ticket_read(tk) != (wt >> 16);) {
+                        __builtin_amdgcn_s_sleep(2);
+                        if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                            ticket_write(&give_up, 1u);
+                            atomicExch(a.err, PS_ESTALL);
+                            break;
+                        }
+                    }
+                    __builtin_amdgcn_s_setprio(1);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                    load_row_t<NV>(wrow, lane, tail, w[i]);
+                }
+                uint32_t wb = e0;
+                for (uint32_t t = e0; t < e1; ++t) {
+                    if (t - wb >= 64u) {                   // a row with more than 64 entries here: next 64
+                        wb = t;
+                        ci[i] = 0; ev[i] = 0.0f;
+                        if (wb + lane < e1) { ci[i] = a.t_cinfo[wb + lane]; ev[i] = a.t_val[wb + lane]; }
+                    }
+                    const uint32_t cinfo = (uint32_t)rl_i((int)ci[i], (int)(t - wb));
+                    const float v = rl_f(ev[i], (int)(t - wb));
+                    const uint32_t slot = cinfo & 0xFFFFu, seq = cinfo >> 16;
+                    uint32_t *tk = &ctick[slot];
+                    // the column's earlier entries (in stored order) first
+                    for (uint32_t spins = 0; ticket_read(tk) != seq;) {
+                        __builtin_amdgcn_s_sleep(1);
+                        if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                            ticket_write(&give_up, 1u);
+                            atomicExch(a.err, PS_ESTALL);
+                            break;
+                        }
+                    }
+                    compiler_fence();
+                    const bool cached = slot < (uint32_t)ncached;
+                    float *hp = cached ? hcache + (size_t)slot * L : a.val + (a.m + a.run_col[run0 + nheavy + slot]) * (int64_t)L;
+                    float h[NV];
+                    if (!cached) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                    load_row_t<NV>(hp, lane, tail, h);
+                    float pr = 0.0f;
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) pr = __builtin_fmaf(w[i][cc], h[cc], pr);
+                    const float e = v - wave_sum(pr);
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) {
+                        const float wo = w[i][cc], ho = h[cc];
+                        w[i][cc] = __builtin_fmaf(lr, __builtin_fmaf(e, ho, -(lambda * wo)), wo);
+                        h[cc] = __builtin_fmaf(lr, __builtin_fmaf(e, wo, -(lambda * ho)), ho);
+                    }
+                    store_row_t<NV>(hp, lane, tail, h);
+                    if (cached) compiler_fence(); else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    ticket_write(tk, seq + 1u);
+                }
+                store_row_t<NV>(wrow, lane, tail, w[i]);
+                done += e1 - e0;
+            }
+        }
+    }
     __builtin_amdgcn_s_setprio(0);
     if (lane == 0 && done) atomicAdd(&done_entries, done);
     __syncthreads();
+    // write the cached column factors back
+    {
+        const int total = ncached * L;
+#pragma unroll 4
+        for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+            const int s = idx / L;
+            a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)] = hcache[idx];
+        }
+    }
     // each entry was one pull and one push of two local keys
     if (threadIdx.x == 0 && done_entries) {
         u64 *st = stat_slot(a.stats);
@@ -319,9 +485,21 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
 }
 
 template <int NT, bool A4>
-static int launch_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st) {
-    const size_t lds = ((size_t)waves * 16 * (16 * NT + 4) + 40) * sizeof(float) + (size_t)a.ticket_cap * sizeof(uint32_t);
-    if (lds + 1024 > (size_t)ps->lds_bytes) { ps->last_error = "not enough LDS for the grouped SGD kernel"; return PS_ELIMIT; }
+static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
+    const MfData &f = ps->mf;
+    const int L = a.L;
+    a.sweep = f.sweep_ok ? 1 : 0;
+    a.heavy_waves = (a.sweep && waves > 8) ? 8 : waves;
+    a.ctick_cap = a.sweep ? (f.max_tail_cols > 1 ? f.max_tail_cols : 1) : 1;
+    // LDS plan: staging areas and tables, the two kinds of ticket counters, then as many column factors as fit
+    const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 40) * 4 + ((int64_t)a.ticket_cap + a.ctick_cap) * 4;
+    const int64_t budget = (int64_t)ps->lds_bytes - 1024;         // static LDS and slack
+    if (fixed > budget) { ps->last_error = "not enough LDS for the grouped SGD kernel"; return PS_ELIMIT; }
+    int64_t hcap = a.sweep ? (budget - fixed) / ((int64_t)L * 4) : 0;
+    if (hcap > f.max_tail_cols) hcap = f.max_tail_cols;
+    if (ps->opt_cache_rows >= 0 && hcap > ps->opt_cache_rows) hcap = ps->opt_cache_rows;
+    a.hcache_cap = (int32_t)hcap;
+    const size_t lds = (size_t)(fixed + hcap * L * 4);
     static size_t configured = 0;
     if (lds > configured) {
         PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_chunk<NT, A4>),

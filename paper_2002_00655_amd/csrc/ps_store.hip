@@ -354,6 +354,9 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
     case PS_OPT_MF_WAVES: if (value < 1 || value > 16) return PS_EINVAL; ps->opt_waves = (int)value; return PS_OK;
     case PS_OPT_MF_PROFILE: ps->opt_profile = value != 0; return PS_OK;
     case PS_OPT_MF_GROUPED: ps->opt_grouped = value != 0; return PS_OK;
+    case PS_OPT_MF_HEAVY_LEN:
+        if (value < 1 || value > (1 << 30)) return PS_EINVAL;
+        ps->opt_heavy_len = (int)value; return PS_OK;
     default: return PS_EINVAL;
     }
 }

@@ -14,7 +14,7 @@ from _util import oracle_epochs, gpu_epochs, compare_state, gpu_values
 
 pytestmark = pytest.mark.gpu
 
-OPT_EXACT, OPT_CACHE, OPT_WAVES, OPT_GROUPED = 1, 2, 3, 5
+OPT_EXACT, OPT_CACHE, OPT_WAVES, OPT_GROUPED, OPT_HEAVY_LEN = 1, 2, 3, 5, 6
 
 
 def _blocked_oracle(w, rb, cb):
@@ -250,6 +250,31 @@ def test_normal_arithmetic_both_kernels(rank, waves, grouped):
     print(f"case rank={rank} waves={waves} grouped={grouped} nnz={br.size}", flush=True)
     orc = oracle_epochs("f32", w, rb, cb, blocked, sched, epochs=2)
     srv = gpu_epochs(w, rb, cb, blocked, sched, epochs=2, options=[(OPT_WAVES, waves), (OPT_GROUPED, grouped)])
+    compare_state(orc, srv, exact=False, atol=1e-5)
+
+
+@pytest.mark.parametrize("rank,waves,heavy_len,cache", [(100, 16, 48, -1), (100, 16, 4, -1), (100, 16, 1, -1), (100, 16, 10 ** 6, -1),
+                                                        (100, 9, 6, 0), (100, 16, 6, 3), (16, 3, 5, -1), (50, 1, 4, -1),
+                                                        (128, 12, 8, 2), (1, 16, 3, -1), (37, 8, 2, -1)])
+def test_long_runs_in_groups_rest_by_rows(rank, waves, heavy_len, cache):
+    """The two parts of the grouped kernel - long column runs in groups, the other entries row by row - for
+    several thresholds between 'every run is long' and 'none is', with all, some and none of the other
+    columns' factors kept in LDS, duplicate cells, ragged blocks and a random schedule: within the stated
+    tolerance of the fp32 oracle, two epochs."""
+    rng = np.random.default_rng(2000 + rank + heavy_len)
+    w = wl.make_mf("tiny", scale=0.6, seed=6, rank=rank)
+    extra = rng.integers(0, w.nnz, 300)
+    w.rows = np.concatenate([w.rows, w.rows[extra]]); w.cols = np.concatenate([w.cols, w.cols[extra]])
+    w.vals = np.concatenate([w.vals, rng.standard_normal(300).astype(np.float32)])
+    d = 3
+    rb = np.array([0, 40, 300, w.m], np.int64)
+    cb = np.array([0, 9, 10, w.n], np.int64)
+    blocked = _blocked_oracle(w, rb, cb)
+    sched = wl.random_schedule(d, rng)
+    print(f"case rank={rank} waves={waves} heavy_len={heavy_len} cache={cache} nnz={blocked[0].size}", flush=True)
+    orc = oracle_epochs("f32", w, rb, cb, blocked, sched, epochs=2)
+    srv = gpu_epochs(w, rb, cb, blocked, sched, epochs=2,
+                     options=[(OPT_WAVES, waves), (OPT_GROUPED, 1), (OPT_HEAVY_LEN, heavy_len), (OPT_CACHE, cache)])
     compare_state(orc, srv, exact=False, atol=1e-5)
 
 
