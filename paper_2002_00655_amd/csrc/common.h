@@ -95,6 +95,10 @@ struct dpaps_ps {
     std::string last_error;
 };
 
+// Wavefronts of a workgroup that process heavy runs in the grouped SGD kernel (when it has more wavefronts than
+// that); also the largest number of heavy runs of a block.
+#define DPAPS_HEAVY_WAVES 8
+
 // Arguments of the SGD kernels (one launch = the tasks of one stratum).
 struct SgdArgs {
     const int32_t *tasks;

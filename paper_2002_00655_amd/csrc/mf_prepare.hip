@@ -308,13 +308,14 @@ __global__ void k_incl_to_seg_idx(const uint32_t *incl, int64_t n, uint32_t *idx
 }
 
 // ---- split of a block into heavy column runs and the rest -----------------------------------------------
-// heavy runs of a block: its leading runs of at least heavy_len entries
+// heavy runs of a block: its leading runs of at least heavy_len entries, at most heavy_max of them (one per
+// wavefront that processes heavy runs, so that all of them advance through the rows together)
 __global__ void k_block_nheavy(const int64_t *blk_run_ptr, const int64_t *run_start, int64_t nb, int32_t heavy_len,
-                               int32_t *nheavy, int32_t *max_tail_cols) {
+                               int32_t heavy_max, int32_t *nheavy, int32_t *max_tail_cols) {
     int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= nb) return;
     int64_t g0 = blk_run_ptr[b], g1 = blk_run_ptr[b + 1], g = g0;
-    while (g < g1 && run_start[g + 1] - run_start[g] >= heavy_len) ++g;
+    while (g < g1 && g - g0 < heavy_max && run_start[g + 1] - run_start[g] >= heavy_len) ++g;
     nheavy[b] = (int32_t)(g - g0);
     atomicMax(max_tail_cols, (int32_t)(g1 - g));
 }
@@ -483,7 +484,7 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     HIPRC(hipMalloc(&f.blk_nheavy, nb * sizeof(int32_t)));
     HIPRC(hipMalloc(&f.blk_trun_ptr, (nb + 1) * sizeof(int64_t)));
     HIPRC(hipMemsetAsync(d_aux, 0, 2 * sizeof(int32_t), st));
-    k_block_nheavy<<<grid_for(nb, 256), 256, 0, st>>>(f.blk_run_ptr, f.run_start, nb, f.heavy_len, f.blk_nheavy, d_aux);
+    k_block_nheavy<<<grid_for(nb, 256), 256, 0, st>>>(f.blk_run_ptr, f.run_start, nb, f.heavy_len, DPAPS_HEAVY_WAVES, f.blk_nheavy, d_aux);
     if (nnz > 0) {
         k_tail_flags<<<grid_for(nnz, 256), 256, 0, st>>>(head, scan, blk, f.blk_run_ptr, f.blk_nheavy, f.row, nnz, runidx, tflag,
                                                          d_aux + 1);

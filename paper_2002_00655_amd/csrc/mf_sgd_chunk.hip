@@ -329,53 +329,44 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     }
 
     // ---- part 2: the other runs, row by row ---------------------------------------------
-    // Consecutive rows tend to meet in some column, so they should be worked on by different
-    // wavefronts at the same time.  The row runs are dealt out in batches of D rows that lie P apart:
-    // D P consecutive row runs make P batches, batch p holding runs p, p + P, p + 2 P, ...  A wavefront
-    // takes the next batch, waits until the heavy runs have passed its rows, reads their entries and
-    // factors in one go and then works through them in ascending order.  Batches are taken in order and
-    // P is at most the number of wavefronts, so the batch that holds the lowest unfinished row is either
-    // being worked on or will be taken by a wavefront that finishes (the heavy runs never wait for this
-    // part): every wait ends.  P is the number of wavefronts that are free for this part from the start.
+    // A wavefront takes the next D consecutive row runs, waits until the heavy runs have passed these
+    // rows, reads their entries and factors in one go, and then keeps going round its rows: whichever
+    // row's next entry is the next of its column (by the column's ticket) is processed, the others are
+    // looked at again in the next round.  Batches are taken in ascending order and no wavefront ever
+    // waits for one particular entry, so the lowest unfinished entry of the block is always processed
+    // in its wavefront's next round: every wait ends.
     __builtin_amdgcn_s_setprio(1);
     if (tr1 > tr0) {
         constexpr int D = 8;
         const int ntrow = (int)(tr1 - tr0);
-        const int P = nwaves > hwaves ? nwaves - hwaves : nwaves;
-        const int nbatch = (ntrow + D * P - 1) / (D * P) * P;
         for (;;) {
-            int k = 0;
-            if (lane == 0) k = atomicAdd(&next_trow, 1);
-            k = __builtin_amdgcn_readfirstlane(k);
-            if (k >= nbatch) break;
-            const int jb = (k / P) * (D * P) + (k % P);
-            // lane i < D: row run jb + i P
+            int jb = 0;
+            if (lane == 0) jb = atomicAdd(&next_trow, D);
+            jb = __builtin_amdgcn_readfirstlane(jb);
+            if (jb >= ntrow) break;
+            // lane i < D: row run jb + i
             int r_row = -1;
             uint32_t r_e0 = 0, r_e1 = 0, r_wait = 0xFFFFFFFFu;
-            {
-                const int j = jb + lane * P;
-                if (lane < D && j < ntrow) {
-                    r_row = a.trun_row[tr0 + j]; r_e0 = a.trun_start[tr0 + j]; r_e1 = a.trun_start[tr0 + j + 1];
-                    r_wait = a.trun_wait[tr0 + j];
-                }
+            if (lane < D && jb + lane < ntrow) {
+                r_row = a.trun_row[tr0 + jb + lane]; r_e0 = a.trun_start[tr0 + jb + lane]; r_e1 = a.trun_start[tr0 + jb + lane + 1];
+                r_wait = a.trun_wait[tr0 + jb + lane];
             }
-            // entries of every row (one per lane) and, where the row's entries in heavy runs are done, its factor
+            // entries of every row (one per lane) and its factor, once the row's entries in heavy runs are done
             float w[D][NV], ev[D];
-            uint32_t ci[D];
-            uint32_t loaded = 0;
+            uint32_t ci[D], pos[D], wb[D];
+            uint32_t pend = 0;
+            bool stalled = false;
 #pragma unroll
             for (int i = 0; i < D; ++i) {
                 const int row = rl_i(r_row, i);
                 const uint32_t e0 = (uint32_t)rl_i((int)r_e0, i), e1 = (uint32_t)rl_i((int)r_e1, i);
                 const uint32_t wt = (uint32_t)rl_i((int)r_wait, i);
-                ci[i] = 0; ev[i] = 0.0f;
+                ci[i] = 0; ev[i] = 0.0f; pos[i] = e0; wb[i] = e0;
 #pragma unroll
                 for (int cc = 0; cc < NV; ++cc) w[i][cc] = 0.0f;
                 if (e0 + lane < e1) { ci[i] = a.t_cinfo[e0 + lane]; ev[i] = a.t_val[e0 + lane]; }
-                if (row >= 0) {
-                    bool ok = true;
+                if (row >= 0 && !stalled) {
                     if (wt != 0xFFFFFFFFu) {
-                        // the row's entries in heavy runs first
                         uint32_t *tk = &ticket[wt & 0xFFFFu];
                         __builtin_amdgcn_s_setprio(0);
                         for (uint32_t spins = 0; ticket_read(tk) != (wt >> 16);) {
@@ -383,85 +374,98 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
                             if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
                                 ticket_write(&give_up, 1u);
                                 atomicExch(a.err, PS_ESTALL);
-                                ok = false;
+                                stalled = true;
                                 break;
                             }
                         }
                         __builtin_amdgcn_s_setprio(1);
                     }
-                    if (ok) {
+                    if (!stalled) {
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                         load_row_t<NV>(a.val + (int64_t)row * L, lane, tail, w[i]);
-                        loaded |= 1u << i;
+                        pend |= 1u << i;
                     }
                 }
             }
+            // rounds over the rows that still have entries; lane i holds the next entry of row i
+            uint32_t cur_ci = 0;
 #pragma unroll
             for (int i = 0; i < D; ++i) {
-                const int row = rl_i(r_row, i);
-                if (row < 0) continue;
-                const uint32_t e0 = (uint32_t)rl_i((int)r_e0, i), e1 = (uint32_t)rl_i((int)r_e1, i);
-                float *wrow = a.val + (int64_t)row * L;
-                if (!((loaded >> i) & 1u)) {
-                    // wait for the row's entries in heavy runs, then read its factor
-                    const uint32_t wt = (uint32_t)rl_i((int)r_wait, i);
-                    uint32_t *tk = &ticket[wt & 0xFFFFu];
-                    __builtin_amdgcn_s_setprio(0);
-                    for (uint32_t spins = 0; ticket_read(tk) != (wt >> 16);) {
-                        __builtin_amdgcn_s_sleep(2);
-                        if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
-                            ticket_write(&give_up, 1u);
-                            atomicExch(a.err, PS_ESTALL);
-                            break;
-                        }
-                    }
-                    __builtin_amdgcn_s_setprio(1);
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                    load_row_t<NV>(wrow, lane, tail, w[i]);
-                }
-                uint32_t wb = e0;
-                for (uint32_t t = e0; t < e1; ++t) {
-                    if (t - wb >= 64u) {                   // a row with more than 64 entries here: next 64
-                        wb = t;
-                        ci[i] = 0; ev[i] = 0.0f;
-                        if (wb + lane < e1) { ci[i] = a.t_cinfo[wb + lane]; ev[i] = a.t_val[wb + lane]; }
-                    }
-                    const uint32_t cinfo = (uint32_t)rl_i((int)ci[i], (int)(t - wb));
-                    const float v = rl_f(ev[i], (int)(t - wb));
-                    const uint32_t slot = cinfo & 0xFFFFu, seq = cinfo >> 16;
-                    uint32_t *tk = &ctick[slot];
-                    // the column's earlier entries (in stored order) first
-                    for (uint32_t spins = 0; ticket_read(tk) != seq;) {
-                        __builtin_amdgcn_s_sleep(1);
-                        if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
-                            ticket_write(&give_up, 1u);
-                            atomicExch(a.err, PS_ESTALL);
-                            break;
-                        }
-                    }
-                    compiler_fence();
-                    const bool cached = slot < (uint32_t)ncached;
-                    float *hp = cached ? hcache + (size_t)slot * L : a.val + (a.m + a.run_col[run0 + nheavy + slot]) * (int64_t)L;
-                    float h[NV];
-                    if (!cached) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                    load_row_t<NV>(hp, lane, tail, h);
-                    float pr = 0.0f;
-#pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) pr = __builtin_fmaf(w[i][cc], h[cc], pr);
-                    const float e = v - wave_sum(pr);
-#pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) {
-                        const float wo = w[i][cc], ho = h[cc];
-                        w[i][cc] = __builtin_fmaf(lr, __builtin_fmaf(e, ho, -(lambda * wo)), wo);
-                        h[cc] = __builtin_fmaf(lr, __builtin_fmaf(e, wo, -(lambda * ho)), ho);
-                    }
-                    store_row_t<NV>(hp, lane, tail, h);
-                    if (cached) compiler_fence(); else __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                    ticket_write(tk, seq + 1u);
-                }
-                store_row_t<NV>(wrow, lane, tail, w[i]);
-                done += e1 - e0;
+                const uint32_t first = (uint32_t)rl_i((int)ci[i], 0);
+                cur_ci = lane == i ? first : cur_ci;
             }
+            uint32_t idle_rounds = 0;
+            while (pend != 0) {
+                // lane i looks at the ticket of the column of row i's next entry
+                uint32_t tkv = 0;
+                if (lane < D) tkv = ticket_read(&ctick[cur_ci & 0xFFFFu]);
+                const uint32_t ready = (uint32_t)__ballot(lane < D && ((pend >> lane) & 1u) != 0u && tkv == (cur_ci >> 16));
+                const bool any = ready != 0u;
+#pragma unroll
+                for (int i = 0; i < D; ++i) {
+                    if (!((ready >> i) & 1u)) continue;         // done, or the column's earlier entries first
+                    const uint32_t cinfo = (uint32_t)rl_i((int)cur_ci, i);
+                    const uint32_t slot = cinfo & 0xFFFFu, seq = cinfo >> 16;
+                    const float v = rl_f(ev[i], (int)(pos[i] - wb[i]));
+                    const uint32_t e1 = (uint32_t)rl_i((int)r_e1, i);
+                    uint32_t *tk = &ctick[slot];
+                    compiler_fence();
+                    // one step on the row's factor (registers) and the column's factor h
+                    auto step = [&](float (&h)[NV]) {
+                        float pr = 0.0f;
+#pragma unroll
+                        for (int cc = 0; cc < NV; ++cc) pr = __builtin_fmaf(w[i][cc], h[cc], pr);
+                        const float e = v - wave_sum(pr);
+#pragma unroll
+                        for (int cc = 0; cc < NV; ++cc) {
+                            const float wo = w[i][cc], ho = h[cc];
+                            w[i][cc] = __builtin_fmaf(lr, __builtin_fmaf(e, ho, -(lambda * wo)), wo);
+                            h[cc] = __builtin_fmaf(lr, __builtin_fmaf(e, wo, -(lambda * ho)), ho);
+                        }
+                    };
+                    float h[NV];
+                    if (slot < (uint32_t)ncached) {            // the column's factor lives in LDS
+                        float *hl = hcache + (size_t)slot * L;
+                        load_row_t<NV>(hl, lane, tail, h);
+                        step(h);
+                        store_row_t<NV>(hl, lane, tail, h);
+                        compiler_fence();
+                    } else {                                   // did not fit: handed over through memory
+                        float *hg = a.val + (a.m + a.run_col[run0 + nheavy + slot]) * (int64_t)L;
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                        load_row_t<NV>(hg, lane, tail, h);
+                        step(h);
+                        store_row_t<NV>(hg, lane, tail, h);
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    }
+                    ticket_write(tk, seq + 1u);
+                    ++pos[i];
+                    ++done;
+                    if (pos[i] == e1) {
+                        store_row_t<NV>(a.val + (int64_t)rl_i(r_row, i) * L, lane, tail, w[i]);
+                        pend &= ~(1u << i);
+                    } else {
+                        if (pos[i] - wb[i] >= 64u) {       // a row with more than 64 entries here: next 64
+                            wb[i] = pos[i];
+                            ci[i] = 0; ev[i] = 0.0f;
+                            if (wb[i] + lane < e1) { ci[i] = a.t_cinfo[wb[i] + lane]; ev[i] = a.t_val[wb[i] + lane]; }
+                        }
+                        const uint32_t nx = (uint32_t)rl_i((int)ci[i], (int)(pos[i] - wb[i]));
+                        cur_ci = lane == i ? nx : cur_ci;
+                    }
+                }
+                if (any) {
+                    idle_rounds = 0;
+                } else {
+                    __builtin_amdgcn_s_sleep(1);
+                    if ((++idle_rounds & 1023u) == 0 && (idle_rounds > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                        ticket_write(&give_up, 1u);
+                        atomicExch(a.err, PS_ESTALL);
+                        break;
+                    }
+                }
+            }
+            if (stalled) break;
         }
     }
     __builtin_amdgcn_s_setprio(0);
@@ -489,7 +493,7 @@ static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStrea
     const MfData &f = ps->mf;
     const int L = a.L;
     a.sweep = f.sweep_ok ? 1 : 0;
-    a.heavy_waves = (a.sweep && waves > 8) ? 8 : waves;
+    a.heavy_waves = (a.sweep && waves > DPAPS_HEAVY_WAVES) ? DPAPS_HEAVY_WAVES : waves;
     a.ctick_cap = a.sweep ? (f.max_tail_cols > 1 ? f.max_tail_cols : 1) : 1;
     // LDS plan: staging areas and tables, the two kinds of ticket counters, then as many column factors as fit
     const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 40) * 4 + ((int64_t)a.ticket_cap + a.ctick_cap) * 4;
