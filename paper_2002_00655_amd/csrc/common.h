@@ -37,6 +37,7 @@ struct MfData {
     // Split of every block for the grouped SGD kernel: its leading column runs of at least heavy_len entries
     // ("heavy" columns) are processed column by column, the entries of the other runs row by row.  That part
     // is kept a second time, ordered by (block, row, stored position):
+    int64_t max_block_rows = 0, max_block_cols = 0;   // largest row block and column block
     int32_t heavy_len = 0;            // the threshold this split was made with
     bool sweep_ok = false;            // rows ascend inside every run of the second part (needed to walk it by rows)
     int32_t *blk_nheavy = nullptr;    // num_blocks: heavy runs of the block

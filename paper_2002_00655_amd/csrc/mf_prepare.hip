@@ -439,6 +439,8 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     f.h_row_bounds.assign(row_bounds_host, row_bounds_host + d_row + 1);
     f.h_col_bounds.assign(col_bounds_host, col_bounds_host + d_col + 1);
     f.h_block_ptr.assign(block_ptr_host, block_ptr_host + nb + 1);
+    for (int32_t i = 0; i < d_row; ++i) f.max_block_rows = std::max(f.max_block_rows, row_bounds_host[i + 1] - row_bounds_host[i]);
+    for (int32_t i = 0; i < d_col; ++i) f.max_block_cols = std::max(f.max_block_cols, col_bounds_host[i + 1] - col_bounds_host[i]);
     HIPRC(hipMalloc(&f.row_bounds, (d_row + 1) * sizeof(int64_t)));
     HIPRC(hipMalloc(&f.col_bounds, (d_col + 1) * sizeof(int64_t)));
     HIPRC(hipMalloc(&f.blk_run_ptr, (nb + 1) * sizeof(int64_t)));

@@ -88,6 +88,14 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     const int64_t tr0 = a.sweep ? a.blk_trun_ptr[b] : 0, tr1 = a.sweep ? a.blk_trun_ptr[b + 1] : 0;
     const float lr = a.lr, lambda = a.lambda;
     const float delta = (float)((double)lr * (double)lambda);         // c = 1 - delta
+    // The factors of the block's rows and of its columns, each as a buffer: an access at an offset past
+    // the end reads as zero and writes nothing, which is how lanes without a row are switched off
+    // without branching.  (The host has checked that both spans are below 2 GiB.)
+    const int64_t blk_r0 = a.row_bounds[rb], blk_c0 = a.col_bounds[cb];
+    const uint32_t wspan = (uint32_t)((a.row_bounds[rb + 1] - blk_r0) * L * 4);
+    const uint32_t hspan = (uint32_t)((a.col_bounds[cb + 1] - blk_c0) * L * 4);
+    const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + blk_r0 * L, 0, (int)wspan, 0x00020000);
+    const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + (a.m + blk_c0) * L, 0, (int)hspan, 0x00020000);
 
     // every parameter this worker will touch must be allocated to it (Sec. 4.1: all access is local)
     {
@@ -137,6 +145,7 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
         const int64_t g = run0 + run;
         const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
         float *hrow = a.val + (a.m + a.run_col[g]) * (int64_t)L;
+        const uint32_t hoff = (uint32_t)((a.run_col[g] - blk_c0) * L * 4);      // the same row inside the column buffer
         // the long runs come first and everything else in the block ends up waiting for them
         if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
         // the column's row is row 15 of X
@@ -184,14 +193,18 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
             pf_ready = __ballot(ready) == ~0ull;          // all rows final now, before their loads are issued
             compiler_fence();
             const int rid = bperm_i(pf_row, n16);
-            const float *src = n16 < navail ? a.val + (int64_t)rid * L : hrow;     // no entry: any valid row
+            // byte offset of this lane's first piece; no entry: past the end, reads as zero
+            const uint32_t goff = n16 < navail ? (uint32_t)((rid - (int)blk_r0) * L + 4 * hi) * 4u : wspan;
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 if constexpr (A4) {
-                    xp[j] = *reinterpret_cast<const f32x4 *>(src + 16 * j + 4 * hi);   // may run past the row's end, never past the store's
+                    // may run past the row's end (into the next row, or past the buffer's end)
+                    xp[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)goff + 64 * j, 0, 0));
                 } else {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) xp[j][q] = 16 * j + 4 * hi + q < L ? src[16 * j + 4 * hi + q] : 0.0f;
+                    for (int q = 0; q < 4; ++q)
+                        xp[j][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                            wbuf, (16 * j + 4 * hi + q < L ? (int)goff : (int)wspan) + 64 * j + 4 * q, 0, 0));
                 }
             }
         };
@@ -239,16 +252,17 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
 #pragma unroll
                 for (int j = 0; j < NT; ++j) xm[j] = *reinterpret_cast<const f32x4 *>(&stg[15 * RS + 16 * j + 4 * hi]);
             }
-            // where the rows of the result go: lane (n16, hi) holds rows 4 hi + v of every tile
-            float *dst[4];
-            bool live[4];
+            // where the rows of the result go: lane (n16, hi) holds rows 4 hi + v of every tile; byte offsets
+            // into the block's row factors (past the end for rows without an entry: nothing is written), and
+            // for row 15 into its column factors
+            uint32_t dst[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int s = 4 * hi + v;
                 const int r = bperm_i(c_row, s);
-                live[v] = s < k || s == 15;
-                dst[v] = (s == 15 ? hrow : a.val + (int64_t)r * L) + n16;
+                dst[v] = s < k ? (uint32_t)((r - (int)blk_r0) * L + n16) * 4u : wspan;
             }
+            const uint32_t dst_h = hi == 3 ? hoff + (uint32_t)n16 * 4u : hspan;
             // read ahead for the group after this one
             const int64_t pos_next = pos + k;
             if (pos_next < s1) prefetch(pos_next);
@@ -277,13 +291,11 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
             float e_vec = 0.0f;                            // e_t in every lane with n16 == t
             const float v_lr = lr;
 #pragma unroll
-            for (int t = 0; t < CH; ++t) {
-                if (t < k) {
-                    const float ecand = c_val - p;         // lane t holds v_t and p_t
-                    const float e = rl_f(ecand, t);
-                    e_vec = n16 == t ? e : e_vec;
-                    p = __builtin_fmaf(v_lr * e, gg[t], __builtin_fmaf(-delta, p, p));
-                }
+            for (int t = 0; t < CH; ++t) {                 // steps past the group's end compute nothing that is used
+                const float ecand = c_val - p;             // lane t holds v_t and p_t
+                const float e = t < k ? rl_f(ecand, t) : 0.0f;
+                e_vec = n16 == t ? e : e_vec;
+                p = __builtin_fmaf(v_lr * e, gg[t], __builtin_fmaf(-delta, p, p));
             }
 
             // ---- coefficients (C - I)[t = n16][s = 4 hi + v] ------------------------------------
@@ -307,12 +319,17 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
                 f32x4 acc = {xn[0], xn[1], xn[2], xn[3]};             // the I of X + (C - I) X: same lane layout as the result
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ca[v], xn[v], acc, 0, 0, 0);
-                if (tile < NT - 1 || 16 * tile + n16 < L) {
+                const bool comp = tile < NT - 1 || 16 * tile + n16 < L;       // the component exists
+                // (element by element into scalars first: a bit cast applied to a vector element directly
+                // has been seen to pick element 0 every time)
+                const float r0 = acc[0], r1 = acc[1], r2 = acc[2], r3 = acc[3];
+                const float rr[4] = {r0, r1, r2, r3};
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (live[v]) dst[v][16 * tile] = acc[v];
-                    if (hi == 3) stg[15 * RS + 16 * tile + n16] = acc[3];
-                }
+                for (int v = 0; v < 4; ++v)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(rr[v]), wbuf, (int)(comp ? dst[v] : wspan) + 64 * tile, 0, 0);
+                // in the last quarter of the lanes element 3 is row 15: the column's factor
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(r3), hbuf, (int)(comp ? dst_h : hspan) + 64 * tile, 0, 0);
+                if (hi == 3 && comp) stg[15 * RS + 16 * tile + n16] = r3;
             }
             // ---- hand the rows on: the stores must have completed before the tickets move ---------
             {
@@ -492,6 +509,11 @@ template <int NT, bool A4>
 static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
     const MfData &f = ps->mf;
     const int L = a.L;
+    // the kernel addresses the factors of a block's rows, and of its columns, with 32-bit byte offsets
+    if ((int64_t)f.max_block_rows * L * 4 >= ((int64_t)1 << 31) - 4096 || (int64_t)f.max_block_cols * L * 4 >= ((int64_t)1 << 31) - 4096) {
+        ps->last_error = "a block's factors span 2 GiB or more: use the entry-by-entry kernel (PS_OPT_MF_GROUPED 0)";
+        return PS_ELIMIT;
+    }
     a.sweep = f.sweep_ok ? 1 : 0;
     a.heavy_waves = (a.sweep && waves > DPAPS_HEAVY_WAVES) ? DPAPS_HEAVY_WAVES : waves;
     a.ctick_cap = a.sweep ? (f.max_tail_cols > 1 ? f.max_tail_cols : 1) : 1;

@@ -173,8 +173,9 @@ extern "C" int ps_create(int64_t num_keys, int32_t value_len, int32_t num_worker
     ps->lds_bytes = v;
     CR(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, ps->device));
     ps->num_cu = v;
-    // 64 floats of slack after the last row: the grouped SGD kernel reads rows in 16-byte pieces up to the next multiple of 16 components
-    size_t vbytes = ((size_t)num_keys * value_len + 64) * sizeof(float);
+    // slack after the last row: the grouped SGD kernel reads rows in 16-byte pieces up to the next multiple of 16
+    // components, and parks switched-off lanes just past the end of a block's factors
+    size_t vbytes = ((size_t)num_keys * value_len + 256) * sizeof(float);
     CR(hipMalloc(&ps->val, vbytes));
     CR(hipMemset(ps->val, 0, vbytes));
     CR(hipMalloc(&ps->owner, (size_t)num_keys * sizeof(int32_t)));
