@@ -155,46 +155,29 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
             if (cc < NV - 1 || tail) stg[15 * RS + k] = hrow[k];
         }
 
-        // per-entry data of 64 consecutive entries of the run, one per lane, and of the window 32 further on
-        int64_t wb = s0;
-        int w_row = 0, w_info = (int)INFO_NONE, x_row = 0, x_info = (int)INFO_NONE;
-        float w_val = 0.0f, x_val = 0.0f;
-        if (wb + lane < s1) { w_row = a.e_row[wb + lane]; w_val = a.e_val[wb + lane]; w_info = (int)a.e_info[wb + lane]; }
-        if (wb + 32 + lane < s1) { x_row = a.e_row[wb + 32 + lane]; x_val = a.e_val[wb + 32 + lane]; x_info = (int)a.e_info[wb + 32 + lane]; }
-
-        // Read-ahead of one group: per-entry data in lanes 0..14, whether all its rows are final, and
-        // the rows themselves, gathered straight into the layout of the first dense product: lane
-        // (n16, hi) holds components 16 j + 4 hi .. + 3 of row n16 in xp[j].
+        // Read-ahead in two stages.  meta_load: the per-entry data of a group, entry pp + l into lane l.
+        // plan: from that data, where the group ends and whether all its rows are final; gather: the rows
+        // themselves, straight into the layout of the first dense product - lane (n16, hi) holds
+        // components 16 j + 4 hi .. + 3 of row n16 in xp[j].  While a group is computed, the rows of the
+        // next group and the per-entry data of the one after are in flight.
+        int mq_row = 0, mq_info = (int)INFO_NONE;
+        float mq_val = 0.0f;
+        // (always executed, with the position clamped into the run, and the lanes past the run's end masked
+        // where the data is used: a load that is only issued on some paths makes the compiler copy its
+        // result into the loop's registers right away, which waits for it)
+        auto meta_load = [&](int64_t pp) {
+            int64_t q = pp + lane;
+            q = q < s1 ? q : s1 - 1;
+            mq_row = a.e_row[q]; mq_val = a.e_val[q]; mq_info = (int)a.e_info[q];
+        };
         int pf_row = 0, pf_info = (int)INFO_NONE, pf_n = 0;
         float pf_val = 0.0f;
         bool pf_ready = false;
         f32x4 xp[NT];
-        auto prefetch = [&](int64_t pp) {
-            while (pp - wb >= 32) {                       // slide the windows
-                wb += 32;
-                w_row = x_row; w_val = x_val; w_info = x_info;
-                x_row = 0; x_val = 0.0f; x_info = (int)INFO_NONE;
-                if (wb + 32 + lane < s1) { x_row = a.e_row[wb + 32 + lane]; x_val = a.e_val[wb + 32 + lane]; x_info = (int)a.e_info[wb + 32 + lane]; }
-            }
-            const int o = (int)(pp - wb);
-            const bool valid = lane < CH && pp + lane < s1;
-            pf_row = bperm_i(w_row, o + lane);
-            pf_val = bperm_f(w_val, o + lane);
-            const int inf = bperm_i(w_info, o + lane);          // all lanes take part: a disabled lane would read as 0
-            pf_info = valid ? inf : (int)INFO_NONE;
-            const uint32_t slot = (uint32_t)pf_info & 0xFFFFu, seq = ((uint32_t)pf_info >> 16) & 0x7FFFu;
-            // the group ends before an entry whose row occurs earlier in this column
-            const unsigned long long cut = __ballot(valid && lane > 0 && slot != INFO_SINGLE && ((uint32_t)pf_info >> 31) != 0u);
-            int navail = (s1 - pp) < CH ? (int)(s1 - pp) : CH;
-            if (cut != 0ull && __builtin_ctzll(cut) < navail) navail = __builtin_ctzll(cut);
-            pf_n = navail;
-            bool ready = true;
-            if (lane < navail && slot != INFO_SINGLE) ready = ticket_read(&ticket[slot]) == seq;
-            pf_ready = __ballot(ready) == ~0ull;          // all rows final now, before their loads are issued
-            compiler_fence();
+        auto gather = [&]() {
             const int rid = bperm_i(pf_row, n16);
             // byte offset of this lane's first piece; no entry: past the end, reads as zero
-            const uint32_t goff = n16 < navail ? (uint32_t)((rid - (int)blk_r0) * L + 4 * hi) * 4u : wspan;
+            const uint32_t goff = n16 < pf_n ? (uint32_t)((rid - (int)blk_r0) * L + 4 * hi) * 4u : wspan;
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 if constexpr (A4) {
@@ -208,9 +191,30 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
                 }
             }
         };
+        auto plan = [&](int64_t pp) {                     // the group that starts at pp, whose data meta_load has fetched
+            pf_row = mq_row; pf_val = mq_val;
+            pf_info = (lane < CH && pp + lane < s1) ? mq_info : (int)INFO_NONE;
+            const uint32_t slot = (uint32_t)pf_info & 0xFFFFu, seq = ((uint32_t)pf_info >> 16) & 0x7FFFu;
+            // the group ends before an entry whose row occurs earlier in this column
+            const unsigned long long cut = __ballot(lane > 0 && slot != INFO_SINGLE && slot != INFO_NONE && ((uint32_t)pf_info >> 31) != 0u);
+            int navail = (s1 - pp) < CH ? (int)(s1 - pp) : CH;
+            if (navail < 0) navail = 0;                   // past the run's end: an empty group, nothing is read
+            if (cut != 0ull && __builtin_ctzll(cut) < navail) navail = __builtin_ctzll(cut);
+            pf_n = navail;
+            bool ready = true;
+            if (lane < navail && slot != INFO_SINGLE) ready = ticket_read(&ticket[slot]) == seq;
+            pf_ready = __ballot(ready) == ~0ull;          // all rows final now, before their loads are issued
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            gather();
+        };
 
         int64_t pos = s0;
-        prefetch(pos);
+        meta_load(pos);
+        plan(pos);
+        meta_load(pos + pf_n);
+        // everything asked for so far has arrived before the loop is entered, so that inside the loop the
+        // read-ahead only ever has to wait for loads that were issued a whole group earlier
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         while (pos < s1) {
             int c_row = pf_row, c_info = pf_info;
             float c_val = pf_val;
@@ -236,7 +240,7 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
                 }
                 if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                prefetch(pos);                            // same group, rows as they are now
+                gather();                                 // same group, rows as they are now
             }
             // X: rows 0 .. 14 from the read-ahead (components past the rank are zero), row 15 is the column's row
             f32x4 xm[NT];
@@ -263,9 +267,10 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
                 dst[v] = s < k ? (uint32_t)((r - (int)blk_r0) * L + n16) * 4u : wspan;
             }
             const uint32_t dst_h = hi == 3 ? hoff + (uint32_t)n16 * 4u : hspan;
-            // read ahead for the group after this one
+            // read ahead: the rows of the next group, the per-entry data of the one after
             const int64_t pos_next = pos + k;
-            if (pos_next < s1) prefetch(pos_next);
+            plan(pos_next);
+            meta_load(pos_next + pf_n);
 
             // ---- G = X X^T ------------------------------------------------------------------
             f32x4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gm2 = {0.0f, 0.0f, 0.0f, 0.0f};
