@@ -241,20 +241,25 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
                 if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                 gather();                                 // same group, rows as they are now
+                // waited for here, on the rare path, so that where the paths join the common one is not
+                // made to wait for everything it has in flight
+                __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
             }
-            // X: rows 0 .. 14 from the read-ahead (components past the rank are zero), row 15 is the column's row
-            f32x4 xm[NT];
-#pragma unroll
-            for (int j = 0; j < NT; ++j) xm[j] = xp[j];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (16 * (NT - 1) + 4 * hi + q >= L) xm[NT - 1][q] = 0.0f;
+            // X: rows 0 .. 14 from the read-ahead (components past the rank are zero) go to the staging area;
+            // row 15 there is the column's row.  Both dense products read X from the staging area, so the
+            // registers of the read-ahead are free again at once and the next group's rows can be asked for
+            // before this group's arithmetic starts.
             if (n16 < 15) {
 #pragma unroll
-                for (int j = 0; j < NT; ++j) *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = xm[j];
-            } else {
+                for (int j = 0; j < NT; ++j) {
+                    f32x4 x = xp[j];
+                    if (j == NT - 1) {
 #pragma unroll
-                for (int j = 0; j < NT; ++j) xm[j] = *reinterpret_cast<const f32x4 *>(&stg[15 * RS + 16 * j + 4 * hi]);
+                        for (int q = 0; q < 4; ++q)
+                            if (16 * (NT - 1) + 4 * hi + q >= L) x[q] = 0.0f;
+                    }
+                    *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = x;
+                }
             }
             // where the rows of the result go: lane (n16, hi) holds rows 4 hi + v of every tile; byte offsets
             // into the block's row factors (past the end for rows without an entry: nothing is written), and
@@ -276,10 +281,11 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
             f32x4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gm2 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
-                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][0], xm[j][0], gm, 0, 0, 0);
-                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][1], xm[j][1], gm2, 0, 0, 0);
-                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][2], xm[j][2], gm, 0, 0, 0);
-                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[j][3], xm[j][3], gm2, 0, 0, 0);
+                const f32x4 xm = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
+                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[0], xm[0], gm, 0, 0, 0);
+                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[1], xm[1], gm2, 0, 0, 0);
+                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[2], xm[2], gm, 0, 0, 0);
+                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[3], xm[3], gm2, 0, 0, 0);
             }
             gm = gm + gm2;
             // lane (n16, hi) holds G[4 hi + v][n16] = <x_{n16}, x_{4 hi + v}> in gm[v]; gather the whole
