@@ -79,7 +79,7 @@ def main() -> int:
     ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "wide"])
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--bounds", default="equal", choices=["equal", "balanced"])
-    ap.add_argument("--waves", type=int, default=16)
+    ap.add_argument("--waves", type=int, default=12)
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)

@@ -51,6 +51,11 @@ struct MfData {
     uint32_t *trun_wait = nullptr;    // num_truns: bits 0-15 ticket slot of the row, bits 16-31 the row's entries in heavy
                                       // runs (the ticket value to wait for); 0xFFFFFFFF: none
     int64_t *blk_trun_ptr = nullptr;  // num_blocks + 1, index into row runs
+    // where the groups of the heavy runs start: run r has run_gptr[r+1] - run_gptr[r] - 1 groups (none if it is not
+    // heavy); gstart[run_gptr[r] + g] is the start of group g relative to the run's first entry, one more entry = length
+    int64_t *run_gptr = nullptr;      // num_runs + 1
+    int32_t *gstart = nullptr;        // num_gstart
+    int64_t num_gstart = 0;
     // block geometry
     int64_t *row_bounds = nullptr;    // device copy, d_row + 1
     int64_t *col_bounds = nullptr;    // device copy, d_col + 1
@@ -81,7 +86,7 @@ struct dpaps_ps {
     // options
     int opt_exact = 0;
     int64_t opt_cache_rows = -1;
-    int opt_waves = 16;
+    int opt_waves = 12;
     int opt_profile = 0;
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
@@ -99,6 +104,8 @@ struct dpaps_ps {
 // Wavefronts of a workgroup that process heavy runs in the grouped SGD kernel (when it has more wavefronts than
 // that); also the largest number of heavy runs of a block.
 #define DPAPS_HEAVY_WAVES 8
+// Heavy runs of a block at most.
+#define DPAPS_HEAVY_MAX 8
 
 // Arguments of the SGD kernels (one launch = the tasks of one stratum).
 struct SgdArgs {
@@ -117,8 +124,10 @@ struct SgdArgs {
     const int32_t *blk_nheavy; const int64_t *blk_trun_ptr;
     const uint32_t *trun_start; const int32_t *trun_row; const uint32_t *trun_wait;
     const uint32_t *t_cinfo; const float *t_val;
+    const int64_t *run_gptr; const int32_t *gstart;
     int32_t sweep;              // 0: every run is processed as a heavy run
     int32_t heavy_waves;        // wavefronts that take heavy runs (each has a staging area in LDS)
+    int32_t team;               // wavefronts that share one heavy run
     int32_t ctick_cap;          // column ticket counters in LDS
     int32_t hcache_cap;         // column factors that fit in LDS
     float lr, lambda;

@@ -173,7 +173,7 @@ void dpaps_mf_free(dpaps_ps *ps) {
     MfData &f = ps->mf;
     void *ptrs[] = {f.row, f.val, f.info, f.col, f.run_start, f.run_col, f.blk_run_ptr, f.multi_row, f.blk_multi_ptr,
                     f.row_bounds, f.col_bounds, f.blk_nheavy, f.t_cinfo, f.t_val, f.trun_start, f.trun_row, f.trun_wait,
-                    f.blk_trun_ptr};
+                    f.blk_trun_ptr, f.run_gptr, f.gstart};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     ps->mf = MfData();
 }
@@ -369,6 +369,37 @@ __global__ void k_tail_fill(const uint32_t *spos, const uint32_t *tq, const uint
     }
 }
 
+// ---- groups of a heavy run ------------------------------------------------------------------------------
+// A heavy run is processed in groups of at most 15 consecutive entries; a group also ends before an entry
+// whose row's previous entry lies in the same column (so that the rows of a group are distinct).  Where the
+// groups start depends on the data only, so it is worked out once: one thread per run walks its entries.
+// fill == 0: cnt[r] = number of table entries of run r (groups + 1 for a heavy run, else 0);
+// fill == 1: gstart[gptr[r] + g] = start of group g relative to the run's first entry, the last one = its length.
+__global__ void k_run_groups(const int64_t *run_start, const uint32_t *blk, const int64_t *blk_run_ptr, const int32_t *nheavy,
+                             const uint32_t *info, int64_t num_runs, int fill, uint32_t *cnt, const uint32_t *gptr,
+                             int32_t *gstart) {
+    int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= num_runs) return;
+    const int64_t s0 = run_start[r], s1 = run_start[r + 1];
+    const uint32_t b = blk[s0];
+    if (r - blk_run_ptr[b] >= nheavy[b]) { if (!fill) cnt[r] = 0; return; }
+    uint32_t ng = 0;
+    int64_t p = s0;
+    while (p < s1) {
+        if (fill) gstart[gptr[r] + ng] = (int32_t)(p - s0);
+        ++ng;
+        int64_t q = p + 1;
+        while (q < s1 && q - p < 15 && !((info[q] & 0xFFFFu) != 0xFFFFu && (info[q] >> 31) != 0u)) ++q;
+        p = q;
+    }
+    if (fill) gstart[gptr[r] + ng] = (int32_t)(s1 - s0); else cnt[r] = ng + 1;
+}
+
+__global__ void k_widen_u32(const uint32_t *src, int64_t n, int64_t last, int64_t *dst) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i]; else if (i == n) dst[i] = last;
+}
+
 extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, const int32_t *rows, const int32_t *cols,
                                const float *vals, int32_t d_row, int32_t d_col, const int64_t *row_bounds_host,
                                const int64_t *col_bounds_host, const int64_t *block_ptr_host, void *stream) {
@@ -486,7 +517,7 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     HIPRC(hipMalloc(&f.blk_nheavy, nb * sizeof(int32_t)));
     HIPRC(hipMalloc(&f.blk_trun_ptr, (nb + 1) * sizeof(int64_t)));
     HIPRC(hipMemsetAsync(d_aux, 0, 2 * sizeof(int32_t), st));
-    k_block_nheavy<<<grid_for(nb, 256), 256, 0, st>>>(f.blk_run_ptr, f.run_start, nb, f.heavy_len, DPAPS_HEAVY_WAVES, f.blk_nheavy, d_aux);
+    k_block_nheavy<<<grid_for(nb, 256), 256, 0, st>>>(f.blk_run_ptr, f.run_start, nb, f.heavy_len, DPAPS_HEAVY_MAX, f.blk_nheavy, d_aux);
     if (nnz > 0) {
         k_tail_flags<<<grid_for(nnz, 256), 256, 0, st>>>(head, scan, blk, f.blk_run_ptr, f.blk_nheavy, f.row, nnz, runidx, tflag,
                                                          d_aux + 1);
@@ -583,6 +614,26 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     HIPRC(hipMemcpyAsync(&h_err, d_err, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIPRC(hipStreamSynchronize(st));
     if (h_err) { rc = h_err; goto done; }
+    // --- where the groups of the heavy runs start (head / scan are free again) ----------------------
+    HIPRC(hipMalloc(&f.run_gptr, (num_runs + 1) * sizeof(int64_t)));
+    if (num_runs > 0) {
+        if (num_runs >= ((int64_t)1 << 31)) { rc = PS_ELIMIT; goto done; }
+        k_run_groups<<<grid_for(num_runs, 128), 128, 0, st>>>(f.run_start, blk, f.blk_run_ptr, f.blk_nheavy, f.info, num_runs, 0,
+                                                              head, nullptr, nullptr);
+        HIPRC(rocprim::exclusive_scan(tmp, tmp_scan, head, scan, 0u, (size_t)num_runs, rocprim::plus<uint32_t>(), st));
+        HIPRC(hipMemcpyAsync(&h_tail[0], scan + (num_runs - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIPRC(hipMemcpyAsync(&h_tail[1], head + (num_runs - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIPRC(hipStreamSynchronize(st));
+        f.num_gstart = (int64_t)h_tail[0] + h_tail[1];
+    }
+    HIPRC(hipMalloc(&f.gstart, std::max<int64_t>(f.num_gstart, 1) * sizeof(int32_t)));
+    k_widen_u32<<<grid_for(num_runs + 1, 256), 256, 0, st>>>(scan, num_runs, f.num_gstart, f.run_gptr);
+    if (num_runs > 0) {
+        k_run_groups<<<grid_for(num_runs, 128), 128, 0, st>>>(f.run_start, blk, f.blk_run_ptr, f.blk_nheavy, f.info, num_runs, 1,
+                                                              nullptr, scan, f.gstart);
+    }
+    HIPRC(hipGetLastError());
+    HIPRC(hipStreamSynchronize(st));
 done:
     if (dev) (void)hipFree(dev);
     if (rc != PS_OK) dpaps_mf_free(ps);

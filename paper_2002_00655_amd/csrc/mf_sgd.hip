@@ -502,6 +502,7 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
         a.blk_nheavy = f.blk_nheavy; a.blk_trun_ptr = f.blk_trun_ptr;
         a.trun_start = f.trun_start; a.trun_row = f.trun_row; a.trun_wait = f.trun_wait;
         a.t_cinfo = f.t_cinfo; a.t_val = f.t_val;
+        a.run_gptr = f.run_gptr; a.gstart = f.gstart;
         a.lr = lr; a.lambda = lambda; a.stats = ps->stats; a.err = ps->err;
         int rc;
         hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -515,7 +516,7 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
             ps->ev_used += 2;
             PS_HIP(ps, hipEventRecord(ev0, st));
         }
-        if (ps->opt_grouped && !ps->opt_exact && L <= 128) {
+        if (ps->opt_grouped && !ps->opt_exact && L <= 128 && f.sweep_ok) {
             rc = dpaps_launch_sgd_chunk(ps, a, ntasks, ps->opt_waves, st);
         } else if (ps->opt_exact) {
             switch (NV) {

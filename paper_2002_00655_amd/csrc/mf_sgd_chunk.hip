@@ -55,21 +55,25 @@ __device__ __forceinline__ float bperm_f(float v, int src) {
 
 // NT = number of 16-component tiles of a factor row (rank <= 16 NT); A4: the rank is a multiple of 4,
 // so every row starts on a 16-byte boundary and is read in 16-byte pieces
-template <int NT, bool A4>
-__global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
+// MAXT: the largest workgroup the kernel is compiled for (12 wavefronts leave each of them a third more registers
+// than 16 do, which the first part needs)
+template <int NT, bool A4, int MAXT>
+__global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     constexpr int RS = 16 * NT + 4;          // row stride of the staging area in floats (conflict-free for both read patterns)
     constexpr int NV = (NT + 3) / 4;         // 64-component slices of a row
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int n16 = lane & 15, hi = lane >> 4;
+    const int n16_ = lane & 15, hi_ = lane >> 4;
     const int L = a.L;
     const bool tail = lane + 64 * (NV - 1) < L;
     const int hwaves = a.heavy_waves;                                  // wavefronts 0 .. hwaves-1 take the heavy runs
     float *stg = lds_f + (size_t)wave * 16 * RS;                       // this wavefront's X: 16 rows (heavy wavefronts only)
     float *cpow = lds_f + (size_t)hwaves * 16 * RS;                    // c^0 .. c^16
     float *cpm1 = cpow + 20;                                           // c^0 - 1 .. c^16 - 1
-    uint32_t *ticket = reinterpret_cast<uint32_t *>(cpow + 40);         // ticket_cap: one per row with several entries
+    float *hshare = cpow + 40;                                         // DPAPS_HEAVY_MAX x 16 NT: the heavy columns' factors
+    uint32_t *hseq = reinterpret_cast<uint32_t *>(hshare + DPAPS_HEAVY_MAX * 16 * NT);   // and how many groups each has absorbed
+    uint32_t *ticket = hseq + DPAPS_HEAVY_MAX;                          // ticket_cap: one per row with several entries
     uint32_t *ctick = ticket + a.ticket_cap;                           // ctick_cap: one per non-heavy column
     float *hcache = reinterpret_cast<float *>(ctick + a.ctick_cap);    // hcache_cap x L: factors of non-heavy columns
     __shared__ int next_run;
@@ -82,10 +86,10 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     const int64_t run0 = a.blk_run_ptr[b], run1 = a.blk_run_ptr[b + 1];
     const int nmulti = (int)(a.blk_multi_ptr[b + 1] - a.blk_multi_ptr[b]);
     const int nruns = (int)(run1 - run0);
-    const int nheavy = a.sweep ? a.blk_nheavy[b] : nruns;
+    const int nheavy = a.blk_nheavy[b];
     const int ntcols = nruns - nheavy;                                 // non-heavy columns
     const int ncached = min(ntcols, a.hcache_cap);
-    const int64_t tr0 = a.sweep ? a.blk_trun_ptr[b] : 0, tr1 = a.sweep ? a.blk_trun_ptr[b + 1] : 0;
+    const int64_t tr0 = a.blk_trun_ptr[b], tr1 = a.blk_trun_ptr[b + 1];
     const float lr = a.lr, lambda = a.lambda;
     const float delta = (float)((double)lr * (double)lambda);         // c = 1 - delta
     // The factors of the block's rows and of its columns, each as a buffer: an access at an offset past
@@ -109,6 +113,12 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     for (int t = threadIdx.x; t < nmulti; t += blockDim.x) ticket[t] = 0;
     for (int t = threadIdx.x; t < ntcols; t += blockDim.x) ctick[t] = 0;
     for (int i = threadIdx.x; i < hwaves * 16 * RS; i += blockDim.x) lds_f[i] = 0.0f;
+    // the heavy columns' factors (components past the rank are zero) and their group counters
+    for (int i = threadIdx.x; i < DPAPS_HEAVY_MAX * 16 * NT; i += blockDim.x) {
+        const int r = i / (16 * NT), k = i - r * 16 * NT;
+        hshare[i] = (r < nheavy && k < L) ? a.val[(a.m + a.run_col[run0 + r]) * (int64_t)L + k] : 0.0f;
+    }
+    if (threadIdx.x < DPAPS_HEAVY_MAX) hseq[threadIdx.x] = 0;
     {
         const int total = ncached * L;
 #pragma unroll 4
@@ -125,234 +135,281 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     }
     __syncthreads();
 
-    // constant parts of this lane's coefficients C[t = n16][s = 4 hi + v] for t < 15
-    float kc[4], dg[4], k15[4];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int s = 4 * hi + v, t = n16;
-        kc[v] = (t < 15 && s < t) ? lr * lr * cpow[t - 1 - s] : 0.0f;
-        dg[v] = (t < 15 && s == t) ? -delta : 0.0f;               // C - I on the diagonal
-        k15[v] = (t < 15 && s == 15) ? lr * cpow[t] : 0.0f;
-    }
-
     unsigned int done = 0;
     // ---- part 1: the heavy runs, in groups ----------------------------------------------
-    if (wave < hwaves) for (;;) {
-        int run = 0;
-        if (lane == 0) run = atomicAdd(&next_run, 1);
-        run = __builtin_amdgcn_readfirstlane(run);
-        if (run >= nheavy) break;
-        const int64_t g = run0 + run;
-        const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
-        float *hrow = a.val + (a.m + a.run_col[g]) * (int64_t)L;
-        const uint32_t hoff = (uint32_t)((a.run_col[g] - blk_c0) * L * 4);      // the same row inside the column buffer
-        // the long runs come first and everything else in the block ends up waiting for them
-        if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
-        // the column's row is row 15 of X
-#pragma unroll
-        for (int cc = 0; cc < NV; ++cc) {
-            const int k = lane + 64 * cc;
-            if (cc < NV - 1 || tail) stg[15 * RS + k] = hrow[k];
-        }
+    // A heavy run is processed by a team of T wavefronts that take its groups in turn.  Only a small part
+    // of a group's work depends on the column's factor h as the previous group left it: the inner products
+    // <w_s, h>, the error recurrence and the new h.  That part is done with h in LDS (shared by the team)
+    // and handed from group to group through a counter; the loads, the products <w_s, w_t> before it and
+    // the new rows w_s after it overlap with the other wavefront's turn.
+    if (wave < hwaves) {
+        // With 12 heavy wavefronts: teams of two for the first four runs (the longest, which everything else
+        // ends up waiting for), one wavefront each for the next four.  With fewer: one wavefront per run,
+        // taking runs in turn.
+        const bool mixed = a.team == 2;
+        const int T = (mixed && wave < 8) ? 2 : 1;
+        const int mb = (mixed && wave < 8) ? (wave & 1) : 0;
+        const int run_first = mixed ? (wave < 8 ? wave >> 1 : wave - 4) : wave;
+        const int run_step = mixed ? DPAPS_HEAVY_MAX : hwaves;
+        for (int run = run_first; run < nheavy; run += run_step) {
+            const int64_t g = run0 + run;
+            const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
+            const uint32_t hoff = (uint32_t)((a.run_col[g] - blk_c0) * L * 4);   // the column's row inside the column buffer
+            const int64_t gb = a.run_gptr[g];
+            const int ng = (int)(a.run_gptr[g + 1] - gb) - 1;                   // groups of this run
+            float *hsh = hshare + run * 16 * NT;
+            uint32_t *hsq = &hseq[run];
+            if (run < 2) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(2);
+            // where the groups start: 64 table entries, one per lane, from group gw on
+            int gw = 0;
+            int gs_win = a.gstart[gb + (lane <= ng ? lane : ng)];
+            auto gs = [&](int gi) { return rl_i(gs_win, (gi < ng ? gi : ng) - gw); };   // start of group gi (the run's length past the last)
 
-        // Read-ahead in two stages.  meta_load: the per-entry data of a group, entry pp + l into lane l.
-        // plan: from that data, where the group ends and whether all its rows are final; gather: the rows
-        // themselves, straight into the layout of the first dense product - lane (n16, hi) holds
-        // components 16 j + 4 hi .. + 3 of row n16 in xp[j].  While a group is computed, the rows of the
-        // next group and the per-entry data of the one after are in flight.
-        int mq_row = 0, mq_info = (int)INFO_NONE;
-        float mq_val = 0.0f;
-        // (always executed, with the position clamped into the run, and the lanes past the run's end masked
-        // where the data is used: a load that is only issued on some paths makes the compiler copy its
-        // result into the loop's registers right away, which waits for it)
-        auto meta_load = [&](int64_t pp) {
-            int64_t q = pp + lane;
-            q = q < s1 ? q : s1 - 1;
-            mq_row = a.e_row[q]; mq_val = a.e_val[q]; mq_info = (int)a.e_info[q];
-        };
-        int pf_row = 0, pf_info = (int)INFO_NONE, pf_n = 0;
-        float pf_val = 0.0f;
-        bool pf_ready = false;
-        f32x4 xp[NT];
-        auto gather = [&]() {
-            const int rid = bperm_i(pf_row, n16);
-            // byte offset of this lane's first piece; no entry: past the end, reads as zero
-            const uint32_t goff = n16 < pf_n ? (uint32_t)((rid - (int)blk_r0) * L + 4 * hi) * 4u : wspan;
+            // Read-ahead in two stages.  meta_load: the per-entry data of a group, entry pp + l into lane l.
+            // plan: whether all rows of the group are final, and their gather, straight into the layout of
+            // the dense products - lane (n16, hi) holds components 16 j + 4 hi .. + 3 of row n16 in xp[j].
+            // (Always executed, with positions clamped into the run: a load that is only issued on some
+            // paths makes the compiler copy its result into the loop's registers right away, which waits.)
+            int mq_row = 0, mq_info = (int)INFO_NONE;
+            float mq_val = 0.0f;
+            auto meta_load = [&](int64_t pp) {
+                int64_t q = pp + lane;
+                q = q < s1 ? q : s1 - 1;
+                mq_row = a.e_row[q]; mq_val = a.e_val[q]; mq_info = (int)a.e_info[q];
+            };
+            int pf_row = 0, pf_info = (int)INFO_NONE, pf_n = 0;
+            float pf_val = 0.0f;
+            bool pf_ready = false;
+            f32x4 xp[NT];
+            auto gather = [&](int n16, int hi) {
+                const int rid = bperm_i(pf_row, n16);
+                // byte offset of this lane's first piece; no entry: past the end, reads as zero
+                const uint32_t goff = n16 < pf_n ? (uint32_t)((rid - (int)blk_r0) * L + 4 * hi) * 4u : wspan;
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                if constexpr (A4) {
-                    // may run past the row's end (into the next row, or past the buffer's end)
-                    xp[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)goff + 64 * j, 0, 0));
-                } else {
+                for (int j = 0; j < NT; ++j) {
+                    if constexpr (A4) {
+                        // may run past the row's end (into the next row, or past the buffer's end)
+                        xp[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)goff + 64 * j, 0, 0));
+                    } else {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        xp[j][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                            wbuf, (16 * j + 4 * hi + q < L ? (int)goff : (int)wspan) + 64 * j + 4 * q, 0, 0));
+                        for (int q = 0; q < 4; ++q)
+                            xp[j][q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                wbuf, (16 * j + 4 * hi + q < L ? (int)goff : (int)wspan) + 64 * j + 4 * q, 0, 0));
+                    }
                 }
-            }
-        };
-        auto plan = [&](int64_t pp) {                     // the group that starts at pp, whose data meta_load has fetched
-            pf_row = mq_row; pf_val = mq_val;
-            pf_info = (lane < CH && pp + lane < s1) ? mq_info : (int)INFO_NONE;
-            const uint32_t slot = (uint32_t)pf_info & 0xFFFFu, seq = ((uint32_t)pf_info >> 16) & 0x7FFFu;
-            // the group ends before an entry whose row occurs earlier in this column
-            const unsigned long long cut = __ballot(lane > 0 && slot != INFO_SINGLE && slot != INFO_NONE && ((uint32_t)pf_info >> 31) != 0u);
-            int navail = (s1 - pp) < CH ? (int)(s1 - pp) : CH;
-            if (navail < 0) navail = 0;                   // past the run's end: an empty group, nothing is read
-            if (cut != 0ull && __builtin_ctzll(cut) < navail) navail = __builtin_ctzll(cut);
-            pf_n = navail;
-            bool ready = true;
-            if (lane < navail && slot != INFO_SINGLE) ready = ticket_read(&ticket[slot]) == seq;
-            pf_ready = __ballot(ready) == ~0ull;          // all rows final now, before their loads are issued
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            gather();
-        };
+            };
+            auto plan = [&](int n, int n16, int hi) {     // the group of n entries whose data meta_load has fetched
+                pf_row = mq_row; pf_val = mq_val;
+                pf_info = lane < n ? mq_info : (int)INFO_NONE;
+                pf_n = n;
+                const uint32_t slot = (uint32_t)pf_info & 0xFFFFu, seq = ((uint32_t)pf_info >> 16) & 0x7FFFu;
+                bool ready = true;
+                if (lane < n && slot != INFO_SINGLE) ready = ticket_read(&ticket[slot]) == seq;
+                pf_ready = __ballot(ready) == ~0ull;      // all rows final now, before their loads are issued
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                gather(n16, hi);
+            };
 
-        int64_t pos = s0;
-        meta_load(pos);
-        plan(pos);
-        meta_load(pos + pf_n);
-        // everything asked for so far has arrived before the loop is entered, so that inside the loop the
-        // read-ahead only ever has to wait for loads that were issued a whole group earlier
-        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
-        while (pos < s1) {
-            int c_row = pf_row, c_info = pf_info;
-            float c_val = pf_val;
-            const int k = pf_n;                            // entries of this group
-            if (!pf_ready) {
-                // some row was not final when it was read ahead: wait for its earlier entries (in stored
-                // order), then read the rows again
-                const uint32_t slot = (uint32_t)c_info & 0xFFFFu, seq = ((uint32_t)c_info >> 16) & 0x7FFFu;
-                const bool waits = lane < k && slot != INFO_SINGLE;
-                __builtin_amdgcn_s_setprio(0);
-                for (uint32_t spins = 0;;) {
-                    bool ready = true;
-                    if (waits) ready = ticket_read(&ticket[slot]) == seq;
-                    if (__ballot(ready) == ~0ull) break;
-                    __builtin_amdgcn_s_sleep(2);
-                    // every wait ends: the predecessor always makes progress.  Should that ever fail
-                    // (corrupt input tables), give up rather than hang the device.
+            int gi = mb;                                  // this wavefront's groups: mb, mb + T, ...
+            meta_load(s0 + gs(gi));
+            plan(gs(gi + 1) - gs(gi), n16_, hi_);
+            meta_load(s0 + gs(gi + T));
+            // everything asked for so far has arrived before the loop is entered, so that inside the loop
+            // the read-ahead only ever has to wait for loads that were issued a whole group earlier
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+            for (; gi < ng; gi += T) {
+                if (gi + 2 * T + 1 - gw >= 64) {         // move the table window (runs of more than 60 groups)
+                    gw = gi;
+                    const int q = gw + lane;
+                    gs_win = a.gstart[gb + (q <= ng ? q : ng)];
+                }
+                int c_row = pf_row, c_info = pf_info;
+                float c_val = pf_val;
+                const int k = pf_n;                        // entries of this group
+                // The lane's coordinates once more, opaque to the compiler: everything derived from them
+                // (LDS addresses, offsets) is then recomputed per group with a few instructions instead of
+                // being kept in registers across the loop, of which there are not enough.
+                int n16 = n16_, hi = hi_, ln = lane;
+                __asm__ volatile("" : "+v"(n16), "+v"(hi), "+v"(ln));
+                if (!pf_ready) {
+                    // some row was not final when it was read ahead: wait for its earlier entries (in stored
+                    // order), then read the rows again
+                    const uint32_t slot = (uint32_t)c_info & 0xFFFFu, seq = ((uint32_t)c_info >> 16) & 0x7FFFu;
+                    const bool waits = ln < k && slot != INFO_SINGLE;
+                    __builtin_amdgcn_s_setprio(0);
+                    for (uint32_t spins = 0;;) {
+                        bool ready = true;
+                        if (waits) ready = ticket_read(&ticket[slot]) == seq;
+                        if (__ballot(ready) == ~0ull) break;
+                        __builtin_amdgcn_s_sleep(2);
+                        // every wait ends: the predecessor always makes progress.  Should that ever fail
+                        // (corrupt input tables), give up rather than hang the device.
+                        if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                            ticket_write(&give_up, 1u);
+                            atomicExch(a.err, PS_ESTALL);
+                            break;
+                        }
+                    }
+                    if (run < 2) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(2);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                    gather(n16, hi);                      // same group, rows as they are now
+                    // waited for here, on the rare path, so that where the paths join the common one is not
+                    // made to wait for everything it has in flight
+                    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+                }
+                // X: rows 0 .. 14 from the read-ahead (components past the rank are zero) go to the staging
+                // area; both dense products read X from there, so the registers of the read-ahead are free
+                // again at once
+                if (n16 < 15) {
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) {
+                        f32x4 x = xp[j];
+                        if (j == NT - 1) {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (16 * (NT - 1) + 4 * hi + q >= L) x[q] = 0.0f;
+                        }
+                        *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = x;
+                    }
+                }
+                // read ahead: the rows of this wavefront's next group, the per-entry data of the one after
+                {
+                    const int p1 = gs(gi + T), p2 = gs(gi + T + 1);
+                    plan(p2 - p1, n16, hi);
+                    meta_load(s0 + gs(gi + 2 * T));
+                }
+
+                // ---- <w_s, w_t>: G = X X^T (row 15 of X is an old copy of h here; its products are not used)
+                f32x4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gm2 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const f32x4 xm = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
+                    gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[0], xm[0], gm, 0, 0, 0);
+                    gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[1], xm[1], gm2, 0, 0, 0);
+                    gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[2], xm[2], gm, 0, 0, 0);
+                    gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[3], xm[3], gm2, 0, 0, 0);
+                    if (j & 1) __builtin_amdgcn_sched_barrier(0);   // two tiles in flight at most: registers are scarce
+                }
+                gm = gm + gm2;
+                // ln (n16, hi) holds G[4 hi + v][n16] in gm[v]; the recurrence below needs G[n16][t] in every
+                // ln at step t, fetched from the ln that holds it as the steps go
+
+                // ---- the part that needs h as the previous group left it --------------------------------
+                for (uint32_t spins = 0; ticket_read(hsq) != (uint32_t)gi;) {
+                    __builtin_amdgcn_s_sleep(1);
                     if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
                         ticket_write(&give_up, 1u);
                         atomicExch(a.err, PS_ESTALL);
                         break;
                     }
                 }
-                if (run < 4) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(1);
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                gather();                                 // same group, rows as they are now
-                // waited for here, on the rare path, so that where the paths join the common one is not
-                // made to wait for everything it has in flight
-                __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
-            }
-            // X: rows 0 .. 14 from the read-ahead (components past the rank are zero) go to the staging area;
-            // row 15 there is the column's row.  Both dense products read X from the staging area, so the
-            // registers of the read-ahead are free again at once and the next group's rows can be asked for
-            // before this group's arithmetic starts.
-            if (n16 < 15) {
+                compiler_fence();
+                // p_s = <w_s, h>: every ln its quarter of row n16, then the four quarters together
+                float p = 0.0f;
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
-                    f32x4 x = xp[j];
-                    if (j == NT - 1) {
+                    const f32x4 hq = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
+                    const f32x4 xr = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            if (16 * (NT - 1) + 4 * hi + q >= L) x[q] = 0.0f;
+                    for (int q = 0; q < 4; ++q) p = __builtin_fmaf(xr[q], hq[q], p);
+                    // this wavefront's copy of h as it was (row 15 of X) for the new rows below
+                    if (n16 == 15) *reinterpret_cast<f32x4 *>(&stg[15 * RS + 16 * j + 4 * hi]) = hq;
+                    if (j & 1) __builtin_amdgcn_sched_barrier(0);
+                }
+                p = p + bperm_f(p, ln ^ 16);
+                p = p + bperm_f(p, ln ^ 32);
+                // the errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t]
+                float e_vec = 0.0f;                        // e_t in every ln with n16 == t
+                const float v_lr = lr;
+#pragma unroll
+                for (int t = 0; t < CH; ++t) {             // steps past the group's end compute nothing that is used
+                    const float ecand = c_val - p;         // ln t holds v_t and p_t
+                    const float e = t < k ? rl_f(ecand, t) : 0.0f;
+                    e_vec = n16 == t ? e : e_vec;
+                    const float g_nt = bperm_f(gm[t & 3], 16 * (t >> 2) + n16);   // G[n16][t]
+                    p = __builtin_fmaf(v_lr * e, g_nt, __builtin_fmaf(-delta, p, p));
+                }
+                // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s, ln l its components l, l + 64
+                {
+                    const int pw = k - 1 - n16;
+                    const float a_vec = lr * e_vec * cpow[pw > 0 ? pw : 0];   // ln s < 15: coefficient of w_s (0 past the group)
+                    float hn[NV];
+                    int ck[NV];                            // this ln's components (lanes past the row's 16 NT floats: any)
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) {
+                        ck[cc] = ln + 64 * cc < 16 * NT ? ln + 64 * cc : 0;
+                        const float ho = hsh[ck[cc]];
+                        hn[cc] = __builtin_fmaf(cpm1[k], ho, ho);
                     }
-                    *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = x;
+#pragma unroll
+                    for (int s = 0; s < CH; ++s) {
+                        const float as = rl_f(a_vec, s);
+#pragma unroll
+                        for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(as, stg[s * RS + ck[cc]], hn[cc]);
+                    }
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) {
+                        const bool exists = ln + 64 * cc < L;
+                        if (exists) hsh[ln + 64 * cc] = hn[cc];
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf,
+                                                              (int)(exists ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan), 0, 0);
+                    }
+                    compiler_fence();
+                    ticket_write(hsq, (uint32_t)gi + 1u);
                 }
-            }
-            // where the rows of the result go: lane (n16, hi) holds rows 4 hi + v of every tile; byte offsets
-            // into the block's row factors (past the end for rows without an entry: nothing is written), and
-            // for row 15 into its column factors
-            uint32_t dst[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int s = 4 * hi + v;
-                const int r = bperm_i(c_row, s);
-                dst[v] = s < k ? (uint32_t)((r - (int)blk_r0) * L + n16) * 4u : wspan;
-            }
-            const uint32_t dst_h = hi == 3 ? hoff + (uint32_t)n16 * 4u : hspan;
-            // read ahead: the rows of the next group, the per-entry data of the one after
-            const int64_t pos_next = pos + k;
-            plan(pos_next);
-            meta_load(pos_next + pf_n);
 
-            // ---- G = X X^T ------------------------------------------------------------------
-            f32x4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gm2 = {0.0f, 0.0f, 0.0f, 0.0f};
+                // ---- the new rows: X' = X + (C - I) X, tile by tile; rows 0 .. k-1 go to the store ----------
+                // where the rows of the result go: ln (n16, hi) holds rows 4 hi + v of every tile; byte
+                // offsets into the block's row factors (past the end for rows without an entry)
+                uint32_t dst[4];
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                const f32x4 xm = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
-                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[0], xm[0], gm, 0, 0, 0);
-                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[1], xm[1], gm2, 0, 0, 0);
-                gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[2], xm[2], gm, 0, 0, 0);
-                gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[3], xm[3], gm2, 0, 0, 0);
-            }
-            gm = gm + gm2;
-            // lane (n16, hi) holds G[4 hi + v][n16] = <x_{n16}, x_{4 hi + v}> in gm[v]; gather the whole
-            // row n16 of G into every lane: gg[s] = G[n16][s]
-            float gg[16];
-#pragma unroll
-            for (int h2 = 0; h2 < 4; ++h2) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) gg[4 * h2 + v] = bperm_f(gm[v], 16 * h2 + n16);
-            }
-
-            // ---- the errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t] ---------------------
-            float p = gg[15];                              // p_s = <w_s, h>
-            float e_vec = 0.0f;                            // e_t in every lane with n16 == t
-            const float v_lr = lr;
-#pragma unroll
-            for (int t = 0; t < CH; ++t) {                 // steps past the group's end compute nothing that is used
-                const float ecand = c_val - p;             // lane t holds v_t and p_t
-                const float e = t < k ? rl_f(ecand, t) : 0.0f;
-                e_vec = n16 == t ? e : e_vec;
-                p = __builtin_fmaf(v_lr * e, gg[t], __builtin_fmaf(-delta, p, p));
-            }
-
-            // ---- coefficients (C - I)[t = n16][s = 4 hi + v] ------------------------------------
-            float ca[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int s = 4 * hi + v;
-                const float es = bperm_f(e_vec, s);       // lane s (< 16) holds e_s; e_15 = 0
-                const int pw = k - 1 - s;
-                const float last = s < 15 ? lr * es * cpow[pw > 0 ? pw : 0] : cpm1[k];
-                ca[v] = n16 < 15 ? __builtin_fmaf(e_vec * es, kc[v], __builtin_fmaf(e_vec, k15[v], dg[v])) : last;
-            }
-
-            // ---- X' = X + (C - I) X, tile by tile; rows 0 .. k-1 go to the store, row 15 to the column's
-            //      row in the store and in X
-#pragma unroll
-            for (int tile = 0; tile < NT; ++tile) {
-                float xn[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) xn[v] = stg[(4 * hi + v) * RS + 16 * tile + n16];
-                f32x4 acc = {xn[0], xn[1], xn[2], xn[3]};             // the I of X + (C - I) X: same lane layout as the result
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ca[v], xn[v], acc, 0, 0, 0);
-                const bool comp = tile < NT - 1 || 16 * tile + n16 < L;       // the component exists
-                // (element by element into scalars first: a bit cast applied to a vector element directly
-                // has been seen to pick element 0 every time)
-                const float r0 = acc[0], r1 = acc[1], r2 = acc[2], r3 = acc[3];
-                const float rr[4] = {r0, r1, r2, r3};
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(rr[v]), wbuf, (int)(comp ? dst[v] : wspan) + 64 * tile, 0, 0);
-                // in the last quarter of the lanes element 3 is row 15: the column's factor
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(r3), hbuf, (int)(comp ? dst_h : hspan) + 64 * tile, 0, 0);
-                if (hi == 3 && comp) stg[15 * RS + 16 * tile + n16] = r3;
-            }
-            // ---- hand the rows on: the stores must have completed before the tickets move ---------
-            {
-                const uint32_t slot = (uint32_t)c_info & 0xFFFFu, seq = ((uint32_t)c_info >> 16) & 0x7FFFu;
-                const bool bump = lane < k && slot != INFO_SINGLE && slot != INFO_NONE;
-                if (__ballot(bump) != 0) {
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                    if (bump) ticket_write(&ticket[slot], seq + 1u);
+                for (int v = 0; v < 4; ++v) {
+                    const int s = 4 * hi + v;
+                    const int r = bperm_i(c_row, s);
+                    dst[v] = s < k ? (uint32_t)((r - (int)blk_r0) * L + n16) * 4u : wspan;
                 }
+                float ca[4];                               // (C - I)[t = n16][s = 4 hi + v]; row 15 is not needed any more
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int s = 4 * hi + v;
+                    const float es = bperm_f(e_vec, s);   // ln s (< 16) holds e_s; e_15 = 0
+                    // C[t][s<t] = lr^2 e_t e_s c^(t-1-s),  C[t][t] - 1 = -lr lambda,  C[t][15] = lr e_t c^t
+                    const int t = n16, pw = s == 15 ? t : t - 1 - s;
+                    const float cp = cpow[pw > 0 ? pw : 0];
+                    float x = 0.0f;
+                    if (s < t) x = (lr * e_vec) * (lr * es) * cp;
+                    if (s == t) x = -delta;
+                    if (s == 15) x = lr * e_vec * cp;
+                    ca[v] = t < 15 ? x : 0.0f;
+                }
+#pragma unroll
+                for (int tile = 0; tile < NT; ++tile) {
+                    float xn[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) xn[v] = stg[(4 * hi + v) * RS + 16 * tile + n16];
+                    f32x4 acc = {xn[0], xn[1], xn[2], xn[3]};             // the I of X + (C - I) X: same ln layout as the result
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ca[v], xn[v], acc, 0, 0, 0);
+                    const bool comp = tile < NT - 1 || 16 * tile + n16 < L;       // the component exists
+                    // (element by element into scalars first: a bit cast applied to a vector element directly
+                    // has been seen to pick element 0 every time)
+                    const float r0 = acc[0], r1 = acc[1], r2 = acc[2], r3 = acc[3];
+                    const float rr[4] = {r0, r1, r2, r3};
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(rr[v]), wbuf, (int)(comp ? dst[v] : wspan) + 64 * tile, 0, 0);
+                }
+                // ---- hand the rows on: the stores must have completed before the tickets move ---------
+                {
+                    const uint32_t slot = (uint32_t)c_info & 0xFFFFu, seq = ((uint32_t)c_info >> 16) & 0x7FFFu;
+                    const bool bump = ln < k && slot != INFO_SINGLE && slot != INFO_NONE;
+                    if (__ballot(bump) != 0) {
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                        if (bump) ticket_write(&ticket[slot], seq + 1u);
+                    }
+                }
+                done += (unsigned int)k;
             }
-            done += (unsigned int)k;
-            pos = pos_next;
         }
     }
 
@@ -516,8 +573,8 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_chunk(SgdArgs a) {
     }
 }
 
-template <int NT, bool A4>
-static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
+template <int NT, bool A4, int MAXT>
+static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
     const MfData &f = ps->mf;
     const int L = a.L;
     // the kernel addresses the factors of a block's rows, and of its columns, with 32-bit byte offsets
@@ -525,27 +582,37 @@ static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStrea
         ps->last_error = "a block's factors span 2 GiB or more: use the entry-by-entry kernel (PS_OPT_MF_GROUPED 0)";
         return PS_ELIMIT;
     }
-    a.sweep = f.sweep_ok ? 1 : 0;
-    a.heavy_waves = (a.sweep && waves > DPAPS_HEAVY_WAVES) ? DPAPS_HEAVY_WAVES : waves;
-    a.ctick_cap = a.sweep ? (f.max_tail_cols > 1 ? f.max_tail_cols : 1) : 1;
-    // LDS plan: staging areas and tables, the two kinds of ticket counters, then as many column factors as fit
-    const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 40) * 4 + ((int64_t)a.ticket_cap + a.ctick_cap) * 4;
+    if (!f.sweep_ok) { ps->last_error = "the grouped SGD kernel needs rows in ascending order inside the short column runs"; return PS_ELAYOUT; }
+    a.sweep = 1;
+    // with 12 or more wavefronts, 12 of them take heavy runs (see the kernel); else at most one per heavy run
+    a.team = waves >= 12 ? 2 : 1;
+    a.heavy_waves = waves >= 12 ? 12 : (waves < DPAPS_HEAVY_MAX ? waves : DPAPS_HEAVY_MAX);
+    a.ctick_cap = f.max_tail_cols > 1 ? f.max_tail_cols : 1;
+    // LDS plan: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters, then as
+    // many other column factors as fit
+    const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 40 + DPAPS_HEAVY_MAX * 16 * NT + DPAPS_HEAVY_MAX) * 4 +
+                          ((int64_t)a.ticket_cap + a.ctick_cap) * 4;
     const int64_t budget = (int64_t)ps->lds_bytes - 1024;         // static LDS and slack
     if (fixed > budget) { ps->last_error = "not enough LDS for the grouped SGD kernel"; return PS_ELIMIT; }
-    int64_t hcap = a.sweep ? (budget - fixed) / ((int64_t)L * 4) : 0;
+    int64_t hcap = (budget - fixed) / ((int64_t)L * 4);
     if (hcap > f.max_tail_cols) hcap = f.max_tail_cols;
     if (ps->opt_cache_rows >= 0 && hcap > ps->opt_cache_rows) hcap = ps->opt_cache_rows;
     a.hcache_cap = (int32_t)hcap;
     const size_t lds = (size_t)(fixed + hcap * L * 4);
     static size_t configured = 0;
     if (lds > configured) {
-        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_chunk<NT, A4>),
+        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_chunk<NT, A4, MAXT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    k_mf_sgd_chunk<NT, A4><<<ntasks, 64 * waves, lds, st>>>(a);
+    k_mf_sgd_chunk<NT, A4, MAXT><<<ntasks, 64 * waves, lds, st>>>(a);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
+}
+
+template <int NT, bool A4>
+static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
+    return waves <= 12 ? launch_chunk_t<NT, A4, 768>(ps, a, ntasks, waves, st) : launch_chunk_t<NT, A4, 1024>(ps, a, ntasks, waves, st);
 }
 
 int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st) {
