@@ -25,17 +25,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 
-# HBM bytes per k_mf_sgd launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same counters
-# read for a plain 1 GiB copy; summary under profiles/).  Only valid for the kernel source it was taken with.
-TRAFFIC = {"kernel_sha256_16": "be66ff7b83e8a948", "workload": ("large", 1.0, "equal", 16, -1),
-           "bytes_per_launch": 105.6e6 + 82.4e6}
+# HBM bytes per launch of the SGD kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same
+# counters read for a plain 1 GiB copy; summary under profiles/).  Only valid for the kernel sources it was taken with.
+KERNEL_SOURCES = ("mf_sgd_chunk.hip", "mf_sgd.hip", "mf_device.h", "common.h")
+TRAFFIC = {"kernel_sha256_16": "ec63fff575cd1a9a", "workload": ("large", 1.0, "equal", 12, -1, 0, False),
+           "bytes_per_launch": 136.0e6 + 120.8e6}
+
+
+def kernel_sources_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2002_00655_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def measured_traffic(args):
-    import hashlib
-    src = os.path.join(ROOT, "paper_2002_00655_amd", "csrc", "mf_sgd.hip")
-    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
-    if sha == TRAFFIC["kernel_sha256_16"] and (args.workload, args.scale, args.bounds, args.waves, args.cache_rows) == TRAFFIC["workload"]:
+    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel)
+    if kernel_sources_hash() == TRAFFIC["kernel_sha256_16"] and key == TRAFFIC["workload"]:
         return TRAFFIC["bytes_per_launch"]
     return None     # the kernel (or the workload) is not the one the counters were taken with
 
@@ -81,6 +88,8 @@ def main() -> int:
     ap.add_argument("--bounds", default="equal", choices=["equal", "balanced"])
     ap.add_argument("--waves", type=int, default=12)
     ap.add_argument("--cache-rows", type=int, default=-1)
+    ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
+    ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -129,6 +138,11 @@ def main() -> int:
     srv = P.ParameterServer(w.m + w.n, w.rank, d)
     srv.set_option(P.OPT_MF_WAVES, args.waves)
     srv.set_option(P.OPT_MF_CACHE_ROWS, args.cache_rows)
+    if args.heavy_len > 0:
+        srv.set_option(P.OPT_MF_HEAVY_LEN, args.heavy_len)
+    if args.entry_kernel:
+        srv.set_option(P.OPT_MF_GROUPED, 0)
+    kernel_name = "k_mf_sgd" if (args.entry_kernel or w.rank > 128) else "k_mf_sgd_chunk"
     srv.push(torch.arange(w.m, device=dev), torch.from_numpy(w.W0).to(dev))
     srv.push(w.m + torch.arange(w.n, device=dev), torch.from_numpy(w.H0).to(dev))
     t0 = time.perf_counter()
@@ -169,10 +183,10 @@ def main() -> int:
     avg_launch_s = sgd_ms * 1e-3 / launches
     achieved = bytes_per_update * units_per_launch / avg_launch_s / 1e9
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": measured_traffic(args), "traffic_unit": "bytes per launch", "kernel": "k_mf_sgd", "avg_launch_us": avg_launch_s * 1e6,
+                "traffic": measured_traffic(args), "traffic_unit": "bytes per launch", "kernel": kernel_name, "avg_launch_us": avg_launch_s * 1e6,
                 "bytes_per_update": bytes_per_update, "updates_per_launch": units_per_launch,
                 "note": "algorithmic bytes (model: 16r+12 per update), not bus traffic"}
-    log(f"k_mf_sgd: {launches} launches, avg {avg_launch_s * 1e6:.1f} us, model {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
+    log(f"{kernel_name}: {launches} launches, avg {avg_launch_s * 1e6:.1f} us, model {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
 
     # pull + push rows per second through the C ABI (uniform random keys, value_len = rank)
     n_keys = 1 << 20
@@ -193,7 +207,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}_mf", "m": w.m, "n": w.n, "nnz": w.nnz, "rank": w.rank, "blocks": f"{d}x{d}",
-                   "bounds": args.bounds, "lr": w.lr, "lambda": w.lam, "waves": args.waves},
+                   "bounds": args.bounds, "lr": w.lr, "lambda": w.lam, "waves": args.waves, "kernel": kernel_name},
         "model_gbs": updates_per_s * bytes_per_update / 1e9,
         "model_frac_of_hbm_peak": updates_per_s * bytes_per_update / 1e9 / HBM_PEAK_GBS,
         "pull_push_rows_per_s": rows_per_s,
