@@ -310,10 +310,13 @@ def test_task_order_inside_a_stratum_is_irrelevant():
     sched = wl.cyclic_schedule(d)
     rng = np.random.default_rng(0)
     shuffled = np.stack([s[rng.permutation(d)] for s in sched])
-    a = gpu_epochs(w, rb, cb, blocked, sched)
-    b = gpu_epochs(w, rb, cb, blocked, shuffled)
-    assert np.array_equal(gpu_values(a), gpu_values(b))
-    assert a.stats() == b.stats()
+    # default kernel with the default split, the same with long runs in groups (teams of wavefronts), and the
+    # entry-by-entry kernel: each must give the same bits whatever the order of the tasks
+    for options in ([], [(OPT_HEAVY_LEN, 6)], [(OPT_HEAVY_LEN, 6), (OPT_WAVES, 16)], [(OPT_GROUPED, 0)]):
+        a = gpu_epochs(w, rb, cb, blocked, sched, options=options)
+        b = gpu_epochs(w, rb, cb, blocked, shuffled, options=options)
+        assert np.array_equal(gpu_values(a), gpu_values(b)), options
+        assert a.stats() == b.stats()
     # partial strata (fewer tasks than blocks) are fine too
     part = [sched[0][:2], sched[1][1:]]
     orc = oracle_epochs("f32", w, rb, cb, blocked, part)
