@@ -128,6 +128,8 @@ struct SgdArgs {
     int32_t sweep;              // 0: every run is processed as a heavy run
     int32_t heavy_waves;        // wavefronts that take heavy runs (each has a staging area in LDS)
     int32_t team;               // wavefronts that share one heavy run
+    // the localize step of the subepoch, done by the same workgroup first (grouped kernel only)
+    int32_t fuse_localize; int32_t W; int64_t per_home; int32_t *owner_w;
     int32_t ctick_cap;          // column ticket counters in LDS
     int32_t hcache_cap;         // column factors that fit in LDS
     float lr, lambda;

@@ -62,3 +62,85 @@ __device__ __forceinline__ void store_row_t(float *p, int lane, bool tail, const
 #define INFO_SINGLE 0xFFFFu      // low 16 bits of an info word: the row's only entry in the block
 #define INFO_NONE 0xFFFEu        // filler for lanes past the end of a run: neither single nor in LDS
 
+// ---------------------------------------------------------------------------
+// localize step of a subepoch: every task takes the keys of its row block and
+// of its column block (Sec. 2.3).  One workgroup per task.  Message counts as
+// for ps_localize; because the keys are two ascending ranges, their home nodes
+// come in ascending runs, and the distinct old owners are collected per home
+// node in an LDS bit set.
+// ---------------------------------------------------------------------------
+struct LocalizeArgs {
+    const int32_t *tasks;      // (worker, row block, column block) triples of this stratum
+    int32_t *owner;
+    const int64_t *row_bounds, *col_bounds;
+    int64_t m, per_home;
+    int32_t W;
+    u64 *stats;
+    const int32_t *err;
+};
+
+// All threads of the workgroup call this; bits: 2 * ceil(W / 32) words of LDS scratch.
+__device__ __forceinline__ void mf_localize_task(const LocalizeArgs &a, uint32_t *lds_u32, int32_t worker, int32_t rb, int32_t cb) {
+    const int words = (a.W + 31) / 32;
+    uint32_t *bits_all = lds_u32, *bits_h = lds_u32 + words;
+    __shared__ int s_reloc, s_req, s_instr;
+    const int64_t r0 = a.row_bounds[rb], r1 = a.row_bounds[rb + 1];
+    const int64_t c0 = a.m + a.col_bounds[cb], c1 = a.m + a.col_bounds[cb + 1];
+    for (int i = threadIdx.x; i < 2 * words; i += blockDim.x) lds_u32[i] = 0;
+    if (threadIdx.x == 0) { s_reloc = 0; s_req = 0; s_instr = 0; }
+    __syncthreads();
+    // home nodes touched by the two key ranges (empty range: lo > hi)
+    const int64_t hr_lo = r1 > r0 ? r0 / a.per_home : 1, hr_hi = r1 > r0 ? (r1 - 1) / a.per_home : 0;
+    const int64_t hc_lo = c1 > c0 ? c0 / a.per_home : 1, hc_hi = c1 > c0 ? (c1 - 1) / a.per_home : 0;
+    int reloc = 0;
+    for (int part = 0; part < 2; ++part) {
+        const int64_t lo = part == 0 ? hr_lo : hc_lo, hi = part == 0 ? hr_hi : hc_hi;
+        for (int64_t h = lo; h <= hi; ++h) {
+            if (part == 1 && h >= hr_lo && h <= hr_hi) continue;   // done together with the row range
+            const int64_t k_lo = h * a.per_home, k_hi = k_lo + a.per_home;
+            for (int sub = 0; sub < 2; ++sub) {
+                const int64_t x0 = sub == 0 ? r0 : c0, x1 = sub == 0 ? r1 : c1;
+                const int64_t s0 = x0 > k_lo ? x0 : k_lo, s1 = x1 < k_hi ? x1 : k_hi;
+                for (int64_t k = s0 + threadIdx.x; k < s1; k += blockDim.x) {
+                    int32_t old = a.owner[k];
+                    if (old != worker) {
+                        a.owner[k] = worker;             // the home node updates the location at once
+                        ++reloc;
+                        atomicOr(&bits_h[old >> 5], 1u << (old & 31));
+                        atomicOr(&bits_all[old >> 5], 1u << (old & 31));
+                    }
+                }
+            }
+            __syncthreads();
+            if (threadIdx.x < 64) {
+                int cnt = 0;
+                for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_h[i]);
+                for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
+                if (threadIdx.x == 0 && cnt > 0) {
+                    if (h != worker) s_req += 1;
+                    s_instr += cnt - (int)((bits_h[h >> 5] >> (h & 31)) & 1u);
+                }
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < words; i += blockDim.x) bits_h[i] = 0;
+            __syncthreads();
+        }
+    }
+    if (reloc) atomicAdd(&s_reloc, reloc);
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        int cnt = 0;
+        for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_all[i]);
+        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
+        if (threadIdx.x == 0) {
+            u64 *st = stat_slot(a.stats);
+            atomicAdd(&st[PS_STAT_LOCALIZE_KEYS], (u64)((r1 - r0) + (c1 - c0)));
+            if (s_reloc) atomicAdd(&st[PS_STAT_RELOCATED], (u64)s_reloc);
+            if (s_req) atomicAdd(&st[PS_STAT_MSG_LOC_REQ], (u64)s_req);
+            if (s_instr) atomicAdd(&st[PS_STAT_MSG_LOC_INSTRUCT], (u64)s_instr);
+            if (cnt) atomicAdd(&st[PS_STAT_MSG_LOC_TRANSFER], (u64)cnt);
+        }
+    }
+    __syncthreads();
+}
+

@@ -26,87 +26,10 @@
 
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
 
-// ---------------------------------------------------------------------------
-// localize step of a subepoch: every task takes the keys of its row block and
-// of its column block (Sec. 2.3).  One workgroup per task.  Message counts as
-// for ps_localize; because the keys are two ascending ranges, their home nodes
-// come in ascending runs, and the distinct old owners are collected per home
-// node in an LDS bit set.
-// ---------------------------------------------------------------------------
-struct LocalizeArgs {
-    const int32_t *tasks;      // (worker, row block, column block) triples of this stratum
-    int32_t *owner;
-    const int64_t *row_bounds, *col_bounds;
-    int64_t m, per_home;
-    int32_t W;
-    u64 *stats;
-    const int32_t *err;
-};
-
 __global__ __launch_bounds__(256) void k_mf_localize(LocalizeArgs a) {
-    extern __shared__ uint32_t lds_u32[];
+    extern __shared__ uint32_t lds_loc[];
     if (*(volatile const int32_t *)a.err) return;
-    const int words = (a.W + 31) / 32;
-    uint32_t *bits_all = lds_u32, *bits_h = lds_u32 + words;
-    __shared__ int s_reloc, s_req, s_instr;
-    const int32_t worker = a.tasks[3 * blockIdx.x], rb = a.tasks[3 * blockIdx.x + 1], cb = a.tasks[3 * blockIdx.x + 2];
-    const int64_t r0 = a.row_bounds[rb], r1 = a.row_bounds[rb + 1];
-    const int64_t c0 = a.m + a.col_bounds[cb], c1 = a.m + a.col_bounds[cb + 1];
-    for (int i = threadIdx.x; i < 2 * words; i += blockDim.x) lds_u32[i] = 0;
-    if (threadIdx.x == 0) { s_reloc = 0; s_req = 0; s_instr = 0; }
-    __syncthreads();
-    // home nodes touched by the two key ranges (empty range: lo > hi)
-    const int64_t hr_lo = r1 > r0 ? r0 / a.per_home : 1, hr_hi = r1 > r0 ? (r1 - 1) / a.per_home : 0;
-    const int64_t hc_lo = c1 > c0 ? c0 / a.per_home : 1, hc_hi = c1 > c0 ? (c1 - 1) / a.per_home : 0;
-    int reloc = 0;
-    for (int part = 0; part < 2; ++part) {
-        const int64_t lo = part == 0 ? hr_lo : hc_lo, hi = part == 0 ? hr_hi : hc_hi;
-        for (int64_t h = lo; h <= hi; ++h) {
-            if (part == 1 && h >= hr_lo && h <= hr_hi) continue;   // done together with the row range
-            const int64_t k_lo = h * a.per_home, k_hi = k_lo + a.per_home;
-            for (int sub = 0; sub < 2; ++sub) {
-                const int64_t x0 = sub == 0 ? r0 : c0, x1 = sub == 0 ? r1 : c1;
-                const int64_t s0 = x0 > k_lo ? x0 : k_lo, s1 = x1 < k_hi ? x1 : k_hi;
-                for (int64_t k = s0 + threadIdx.x; k < s1; k += blockDim.x) {
-                    int32_t old = a.owner[k];
-                    if (old != worker) {
-                        a.owner[k] = worker;             // the home node updates the location at once
-                        ++reloc;
-                        atomicOr(&bits_h[old >> 5], 1u << (old & 31));
-                        atomicOr(&bits_all[old >> 5], 1u << (old & 31));
-                    }
-                }
-            }
-            __syncthreads();
-            if (threadIdx.x < 64) {
-                int cnt = 0;
-                for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_h[i]);
-                for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
-                if (threadIdx.x == 0 && cnt > 0) {
-                    if (h != worker) s_req += 1;
-                    s_instr += cnt - (int)((bits_h[h >> 5] >> (h & 31)) & 1u);
-                }
-            }
-            __syncthreads();
-            for (int i = threadIdx.x; i < words; i += blockDim.x) bits_h[i] = 0;
-            __syncthreads();
-        }
-    }
-    if (reloc) atomicAdd(&s_reloc, reloc);
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        int cnt = 0;
-        for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_all[i]);
-        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
-        if (threadIdx.x == 0) {
-            u64 *st = stat_slot(a.stats);
-            atomicAdd(&st[PS_STAT_LOCALIZE_KEYS], (u64)((r1 - r0) + (c1 - c0)));
-            if (s_reloc) atomicAdd(&st[PS_STAT_RELOCATED], (u64)s_reloc);
-            if (s_req) atomicAdd(&st[PS_STAT_MSG_LOC_REQ], (u64)s_req);
-            if (s_instr) atomicAdd(&st[PS_STAT_MSG_LOC_INSTRUCT], (u64)s_instr);
-            if (cnt) atomicAdd(&st[PS_STAT_MSG_LOC_TRANSFER], (u64)cnt);
-        }
-    }
+    mf_localize_task(a, lds_loc, a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1], a.tasks[3 * blockIdx.x + 2]);
 }
 
 // ---------------------------------------------------------------------------
@@ -488,9 +411,12 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
         const int ntasks = stratum_ptr_host[s + 1] - stratum_ptr_host[s];
         if (ntasks == 0) continue;
         const int32_t *tasks = ps->d_tasks + 3 * (int64_t)stratum_ptr_host[s];
-        LocalizeArgs la{tasks, ps->owner, f.row_bounds, f.col_bounds, f.m, ps->per_home, ps->W, ps->stats, ps->err};
-        k_mf_localize<<<ntasks, 256, loc_lds, st>>>(la);
-        PS_HIP(ps, hipGetLastError());
+        const bool grouped = ps->opt_grouped && !ps->opt_exact && L <= 128 && f.sweep_ok;
+        if (!grouped) {      // the grouped kernel does the localize step itself
+            LocalizeArgs la{tasks, ps->owner, f.row_bounds, f.col_bounds, f.m, ps->per_home, ps->W, ps->stats, ps->err};
+            k_mf_localize<<<ntasks, 256, loc_lds, st>>>(la);
+            PS_HIP(ps, hipGetLastError());
+        }
         SgdArgs a{};
         a.tasks = tasks; a.val = ps->val; a.owner = ps->owner;
         a.e_row = f.row; a.e_val = f.val; a.e_info = f.info;
@@ -504,6 +430,7 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
         a.t_cinfo = f.t_cinfo; a.t_val = f.t_val;
         a.run_gptr = f.run_gptr; a.gstart = f.gstart;
         a.lr = lr; a.lambda = lambda; a.stats = ps->stats; a.err = ps->err;
+        a.fuse_localize = grouped ? 1 : 0; a.W = ps->W; a.per_home = ps->per_home; a.owner_w = ps->owner;
         int rc;
         hipEvent_t ev0 = nullptr, ev1 = nullptr;
         if (ps->opt_profile) {
@@ -516,7 +443,7 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
             ps->ev_used += 2;
             PS_HIP(ps, hipEventRecord(ev0, st));
         }
-        if (ps->opt_grouped && !ps->opt_exact && L <= 128 && f.sweep_ok) {
+        if (grouped) {
             rc = dpaps_launch_sgd_chunk(ps, a, ntasks, ps->opt_waves, st);
         } else if (ps->opt_exact) {
             switch (NV) {

@@ -101,8 +101,12 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + blk_r0 * L, 0, (int)wspan, 0x00020000);
     const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + (a.m + blk_c0) * L, 0, (int)hspan, 0x00020000);
 
-    // every parameter this worker will touch must be allocated to it (Sec. 4.1: all access is local)
-    {
+    if (a.fuse_localize) {
+        // the localize step of this task (Sec. 2.3), which makes every parameter the worker will touch its own
+        LocalizeArgs la{a.tasks, a.owner_w, a.row_bounds, a.col_bounds, a.m, a.per_home, a.W, a.stats, a.err};
+        mf_localize_task(la, reinterpret_cast<uint32_t *>(lds_f), worker, rb, cb);
+    } else {
+        // every parameter this worker will touch must be allocated to it (Sec. 4.1: all access is local)
         const int64_t r0 = a.row_bounds[rb], r1 = a.row_bounds[rb + 1];
         const int64_t c0 = a.m + a.col_bounds[cb], c1 = a.m + a.col_bounds[cb + 1];
         bool bad = false;
