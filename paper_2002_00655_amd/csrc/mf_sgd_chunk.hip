@@ -147,13 +147,16 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     // and handed from group to group through a counter; the loads, the products <w_s, w_t> before it and
     // the new rows w_s after it overlap with the other wavefront's turn.
     if (wave < hwaves) {
-        // With 12 heavy wavefronts: teams of two for the first four runs (the longest, which everything else
-        // ends up waiting for), one wavefront each for the next four.  With fewer: one wavefront per run,
-        // taking runs in turn.
+        // With 12 heavy wavefronts: a team of three for the first run (the longest, which everything else
+        // ends up waiting for), teams of two for the next two, one wavefront each for the other five.  With
+        // fewer: one wavefront per run, taking runs in turn.
         const bool mixed = a.team == 2;
-        const int T = (mixed && wave < 8) ? 2 : 1;
-        const int mb = (mixed && wave < 8) ? (wave & 1) : 0;
-        const int run_first = mixed ? (wave < 8 ? wave >> 1 : wave - 4) : wave;
+        int T = 1, mb = 0, run_first = wave;
+        if (mixed) {
+            if (wave < 3) { T = 3; mb = wave; run_first = 0; }
+            else if (wave < 7) { T = 2; mb = (wave - 3) & 1; run_first = 1 + ((wave - 3) >> 1); }
+            else { run_first = wave - 4; }
+        }
         const int run_step = mixed ? DPAPS_HEAVY_MAX : hwaves;
         for (int run = run_first; run < nheavy; run += run_step) {
             const int64_t g = run0 + run;
@@ -295,8 +298,11 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     if (j & 1) __builtin_amdgcn_sched_barrier(0);   // two tiles in flight at most: registers are scarce
                 }
                 gm = gm + gm2;
-                // ln (n16, hi) holds G[4 hi + v][n16] in gm[v]; the recurrence below needs G[n16][t] in every
-                // ln at step t, fetched from the ln that holds it as the steps go
+                // lane (n16, hi) holds G[4 hi + v][n16] in gm[v]; the recurrence below needs lr G[n16][t] in every
+                // lane at step t
+                float gl[CH];
+#pragma unroll
+                for (int t = 0; t < CH; ++t) gl[t] = lr * bperm_f(gm[t & 3], 16 * (t >> 2) + n16);
 
                 // ---- the part that needs h as the previous group left it --------------------------------
                 for (uint32_t spins = 0; ticket_read(hsq) != (uint32_t)gi;) {
@@ -308,43 +314,43 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     }
                 }
                 compiler_fence();
-                // p_s = <w_s, h>: every ln its quarter of row n16, then the four quarters together
-                float p = 0.0f;
+                // h as it is now, lane l its components l, l + 64 (lanes past the row's 16 NT floats: any)
+                float ho[NV];
+                int ck[NV];
+#pragma unroll
+                for (int cc = 0; cc < NV; ++cc) {
+                    ck[cc] = ln + 64 * cc < 16 * NT ? ln + 64 * cc : 0;
+                    ho[cc] = hsh[ck[cc]];
+                }
+                // p_s = <w_s, h>: every lane its quarter of row n16 (four partial sums), then the four quarters together
+                float pq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
                     const f32x4 hq = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
                     const f32x4 xr = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) p = __builtin_fmaf(xr[q], hq[q], p);
-                    // this wavefront's copy of h as it was (row 15 of X) for the new rows below
-                    if (n16 == 15) *reinterpret_cast<f32x4 *>(&stg[15 * RS + 16 * j + 4 * hi]) = hq;
-                    if (j & 1) __builtin_amdgcn_sched_barrier(0);
+                    for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xr[q], hq[q], pq[q]);
                 }
+                float p = (pq[0] + pq[1]) + (pq[2] + pq[3]);
                 p = p + bperm_f(p, ln ^ 16);
                 p = p + bperm_f(p, ln ^ 32);
-                // the errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t]
-                float e_vec = 0.0f;                        // e_t in every ln with n16 == t
-                const float v_lr = lr;
+                // The errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t].  Steps past the group's end work on
+                // rows of X that are zero and on values that are finite, so what they compute changes nothing
+                // that is used; they are not skipped, to keep the chain free of branches.
+                float e_vec = 0.0f;                        // e_t in every lane with n16 == t
 #pragma unroll
-                for (int t = 0; t < CH; ++t) {             // steps past the group's end compute nothing that is used
-                    const float ecand = c_val - p;         // ln t holds v_t and p_t
-                    const float e = t < k ? rl_f(ecand, t) : 0.0f;
+                for (int t = 0; t < CH; ++t) {
+                    const float e = rl_f(c_val - p, t);    // lane t holds v_t and p_t
                     e_vec = n16 == t ? e : e_vec;
-                    const float g_nt = bperm_f(gm[t & 3], 16 * (t >> 2) + n16);   // G[n16][t]
-                    p = __builtin_fmaf(v_lr * e, g_nt, __builtin_fmaf(-delta, p, p));
+                    p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p));
                 }
-                // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s, ln l its components l, l + 64
+                // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s
                 {
                     const int pw = k - 1 - n16;
-                    const float a_vec = lr * e_vec * cpow[pw > 0 ? pw : 0];   // ln s < 15: coefficient of w_s (0 past the group)
+                    const float a_vec = (n16 < k ? lr * e_vec : 0.0f) * cpow[pw > 0 ? pw : 0];   // lane s < 15: coefficient of w_s
                     float hn[NV];
-                    int ck[NV];                            // this ln's components (lanes past the row's 16 NT floats: any)
 #pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) {
-                        ck[cc] = ln + 64 * cc < 16 * NT ? ln + 64 * cc : 0;
-                        const float ho = hsh[ck[cc]];
-                        hn[cc] = __builtin_fmaf(cpm1[k], ho, ho);
-                    }
+                    for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(cpm1[k], ho[cc], ho[cc]);
 #pragma unroll
                     for (int s = 0; s < CH; ++s) {
                         const float as = rl_f(a_vec, s);
@@ -361,9 +367,13 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     compiler_fence();
                     ticket_write(hsq, (uint32_t)gi + 1u);
                 }
+                // this wavefront's copy of h as it was (row 15 of X), for the new rows below
+#pragma unroll
+                for (int cc = 0; cc < NV; ++cc)
+                    if (ln + 64 * cc < 16 * NT) stg[15 * RS + ln + 64 * cc] = ho[cc];
 
                 // ---- the new rows: X' = X + (C - I) X, tile by tile; rows 0 .. k-1 go to the store ----------
-                // where the rows of the result go: ln (n16, hi) holds rows 4 hi + v of every tile; byte
+                // where the rows of the result go: lane (n16, hi) holds rows 4 hi + v of every tile; byte
                 // offsets into the block's row factors (past the end for rows without an entry)
                 uint32_t dst[4];
 #pragma unroll
@@ -376,7 +386,8 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int s = 4 * hi + v;
-                    const float es = bperm_f(e_vec, s);   // ln s (< 16) holds e_s; e_15 = 0
+                    const float es_all = bperm_f(e_vec, s);   // lane s (< 16) holds e_s (all lanes take part in the exchange)
+                    const float es = s < k ? es_all : 0.0f;
                     // C[t][s<t] = lr^2 e_t e_s c^(t-1-s),  C[t][t] - 1 = -lr lambda,  C[t][15] = lr e_t c^t
                     const int t = n16, pw = s == 15 ? t : t - 1 - s;
                     const float cp = cpow[pw > 0 ? pw : 0];
