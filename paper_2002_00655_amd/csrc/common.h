@@ -105,7 +105,7 @@ struct dpaps_ps {
 // that); also the largest number of heavy runs of a block.
 #define DPAPS_HEAVY_WAVES 8
 // Heavy runs of a block at most.
-#define DPAPS_HEAVY_MAX 8
+#define DPAPS_HEAVY_MAX 7
 
 // Arguments of the SGD kernels (one launch = the tasks of one stratum).
 struct SgdArgs {

@@ -147,15 +147,15 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     // and handed from group to group through a counter; the loads, the products <w_s, w_t> before it and
     // the new rows w_s after it overlap with the other wavefront's turn.
     if (wave < hwaves) {
-        // With 12 heavy wavefronts: a team of three for the first run (the longest, which everything else
-        // ends up waiting for), teams of two for the next two, one wavefront each for the other five.  With
+        // With 12 heavy wavefronts: teams of three for the first two runs (the longest, which everything else
+        // ends up waiting for), a team of two for the third, one wavefront each for the other four.  With
         // fewer: one wavefront per run, taking runs in turn.
         const bool mixed = a.team == 2;
         int T = 1, mb = 0, run_first = wave;
         if (mixed) {
-            if (wave < 3) { T = 3; mb = wave; run_first = 0; }
-            else if (wave < 7) { T = 2; mb = (wave - 3) & 1; run_first = 1 + ((wave - 3) >> 1); }
-            else { run_first = wave - 4; }
+            if (wave < 6) { T = 3; mb = wave % 3; run_first = wave / 3; }
+            else if (wave < 8) { T = 2; mb = wave - 6; run_first = 2; }
+            else { run_first = wave - 5; }
         }
         const int run_step = mixed ? DPAPS_HEAVY_MAX : hwaves;
         for (int run = run_first; run < nheavy; run += run_step) {
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     // in its wavefront's next round: every wait ends.
     __builtin_amdgcn_s_setprio(1);
     if (tr1 > tr0) {
-        constexpr int D = 8;
+        constexpr int D = 4;
         const int ntrow = (int)(tr1 - tr0);
         for (;;) {
             int jb = 0;
