@@ -86,7 +86,7 @@ def main() -> int:
     ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "wide"])
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--bounds", default="equal", choices=["equal", "balanced"])
-    ap.add_argument("--waves", type=int, default=12)
+    ap.add_argument("--waves", type=int, default=16)
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
     ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")

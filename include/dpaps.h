@@ -71,7 +71,7 @@ enum {
     PS_OPT_MF_EXACT = 1,        /* 1: the SGD kernel sums each inner product in index order with separately
                                    rounded multiplies and adds (slow; for bit-for-bit checks).  default 0 */
     PS_OPT_MF_CACHE_ROWS = 2,   /* upper bound on row factors a workgroup keeps in LDS (-1 = as many as fit) */
-    PS_OPT_MF_WAVES = 3,        /* wavefronts per workgroup in the SGD kernel: 1..16 (default 12) */
+    PS_OPT_MF_WAVES = 3,        /* wavefronts per workgroup in the SGD kernel: 1..16 (default 16) */
     PS_OPT_MF_PROFILE = 4,      /* 1: bracket every SGD kernel launch with a pair of events (see mf_profile_read) */
     PS_OPT_MF_GROUPED = 5,      /* 1 (default): where rank <= 128 and PS_OPT_MF_EXACT is off, process the long column
                                    runs of a block in groups of up to 15 entries with dense 16x16xr products and

@@ -86,7 +86,7 @@ struct dpaps_ps {
     // options
     int opt_exact = 0;
     int64_t opt_cache_rows = -1;
-    int opt_waves = 12;
+    int opt_waves = 16;
     int opt_profile = 0;
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
@@ -105,7 +105,7 @@ struct dpaps_ps {
 // that); also the largest number of heavy runs of a block.
 #define DPAPS_HEAVY_WAVES 8
 // Heavy runs of a block at most.
-#define DPAPS_HEAVY_MAX 7
+#define DPAPS_HEAVY_MAX 8
 
 // Arguments of the SGD kernels (one launch = the tasks of one stratum).
 struct SgdArgs {

@@ -147,17 +147,17 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     // and handed from group to group through a counter; the loads, the products <w_s, w_t> before it and
     // the new rows w_s after it overlap with the other wavefront's turn.
     if (wave < hwaves) {
-        // With 12 heavy wavefronts: teams of three for the first two runs (the longest, which everything else
-        // ends up waiting for), a team of two for the third, one wavefront each for the other four.  With
-        // fewer: one wavefront per run, taking runs in turn.
-        const bool mixed = a.team == 2;
-        int T = 1, mb = 0, run_first = wave;
-        if (mixed) {
-            if (wave < 6) { T = 3; mb = wave % 3; run_first = wave / 3; }
-            else if (wave < 8) { T = 2; mb = wave - 6; run_first = 2; }
-            else { run_first = wave - 5; }
+        // The longest runs are what everything else ends up waiting for.  With 14 heavy wavefronts (of 16):
+        // teams of three for the first two runs, teams of two for the next two, one wavefront each for the
+        // following four.  With 12 (of 12 to 15): teams of three, three and two, and four single wavefronts
+        // that take the remaining runs in turn.  With fewer: one wavefront per run, taking runs in turn.
+        int T = 1, mb = 0, run_first = wave, run_step = hwaves;
+        if (a.team == 2) {
+            const int pairs_end = hwaves == 14 ? 10 : 8;       // wavefronts 6 .. pairs_end-1 work in pairs
+            if (wave < 6) { T = 3; mb = wave % 3; run_first = wave / 3; run_step = DPAPS_HEAVY_MAX; }
+            else if (wave < pairs_end) { T = 2; mb = (wave - 6) & 1; run_first = 2 + ((wave - 6) >> 1); run_step = DPAPS_HEAVY_MAX; }
+            else { run_first = 2 + ((pairs_end - 6) >> 1) + (wave - pairs_end); run_step = hwaves - pairs_end; }
         }
-        const int run_step = mixed ? DPAPS_HEAVY_MAX : hwaves;
         for (int run = run_first; run < nheavy; run += run_step) {
             const int64_t g = run0 + run;
             const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
@@ -601,7 +601,7 @@ static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStr
     a.sweep = 1;
     // with 12 or more wavefronts, 12 of them take heavy runs (see the kernel); else at most one per heavy run
     a.team = waves >= 12 ? 2 : 1;
-    a.heavy_waves = waves >= 12 ? 12 : (waves < DPAPS_HEAVY_MAX ? waves : DPAPS_HEAVY_MAX);
+    a.heavy_waves = waves >= 16 ? 14 : (waves >= 12 ? 12 : (waves < DPAPS_HEAVY_MAX ? waves : DPAPS_HEAVY_MAX));
     a.ctick_cap = f.max_tail_cols > 1 ? f.max_tail_cols : 1;
     // LDS plan: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters, then as
     // many other column factors as fit
