@@ -2,8 +2,8 @@
 
 Loads ``dpaps_oracle.c`` compiled for fp32 (``Oracle("f32")``) or fp64
 (``Oracle("f64")``) and exposes the parameter-server primitives (Table
-"Primitives", Sec. 3.1) and the blocked matrix-factorization epoch (Sec. 2.2.2,
-Sec. 4.1) on numpy arrays.  Nothing here is imported by the HIP path.
+"Primitives", Sec. 3.1), the blocked matrix-factorization epoch (Sec. 2.2.2,
+Sec. 4.1) and the knowledge-graph-embedding step (``kge_oracle.c``) on numpy arrays.  Nothing here is imported by the HIP path.
 """
 from __future__ import annotations
 
@@ -147,6 +147,29 @@ class Oracle:
         return float(self.lib.orc_mf_train_sse(C.c_void_p(self.h), C.c_int64(m), C.c_int64(rows.size),
                                                _p(rows, C.c_int32), _p(cols, C.c_int32), _p(vals, C.c_float)))
 
+
+    # -- knowledge graph embeddings (ComplEx) ----------------------------------
+    def kge_score(self, D, es, wr, eo) -> float:
+        """Score of one triple; each argument holds 2 D numbers (real parts, then imaginary parts)."""
+        a = [np.ascontiguousarray(x, dtype=self.dtype).reshape(2 * D) for x in (es, wr, eo)]
+        self.lib.orc_kge_score.restype = self._ct
+        return float(self.lib.orc_kge_score(C.c_int32(D), _p(a[0], self._ct), _p(a[1], self._ct), _p(a[2], self._ct)))
+
+    def kge_step(self, num_entities, D, subj, rel, obj, neg_subj, neg_obj, lr, eps, worker: int = -1) -> float:
+        """One mini-batch step (see kge_oracle.c); returns the summed loss of all scored triples."""
+        subj, rel, obj = (np.ascontiguousarray(x, dtype=np.int32) for x in (subj, rel, obj))
+        B = subj.size
+        ns_ = np.ascontiguousarray(neg_subj, dtype=np.int32).reshape(B, -1) if B else np.zeros((0, 0), np.int32)
+        no_ = np.ascontiguousarray(neg_obj, dtype=np.int32).reshape(B, -1) if B else np.zeros((0, 0), np.int32)
+        loss = C.c_double(0.0)
+        real = self._ct
+        rc = self.lib.orc_kge_step(
+            C.c_void_p(self.h), C.c_int32(worker), C.c_int64(num_entities), C.c_int32(D), C.c_int64(B), _p(subj, C.c_int32),
+            _p(rel, C.c_int32), _p(obj, C.c_int32), C.c_int32(ns_.shape[1]), _p(ns_, C.c_int32), C.c_int32(no_.shape[1]),
+            _p(no_, C.c_int32), real(float(np.float32(lr))), real(float(np.float32(eps))), C.byref(loss))
+        if rc:
+            raise OracleError(rc, "kge_step")
+        return loss.value
 
 def mf_block_ratings(m, n, rows, cols, vals, row_bounds, col_bounds):
     """Entries stored block by block for the subepochs (Sec. 2.2.2); returns
