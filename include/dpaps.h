@@ -83,7 +83,7 @@ enum {
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */
 
 /* Create a server of num_keys x value_len zeros, owner[k] = home(k).
- * 1 <= value_len <= 256, 1 <= num_workers <= 2048.  *out is owned by the
+ * 1 <= value_len <= 1024 (matrix factorization: rank <= 256), 1 <= num_workers <= 2048.  *out is owned by the
  * library until ps_destroy. */
 int ps_create(int64_t num_keys, int32_t value_len, int32_t num_workers, ps_handle *out);
 int ps_destroy(ps_handle ps);
@@ -167,6 +167,25 @@ int mf_train_sse(ps_handle ps, double *sse_host_out, void *stream);
  * kernel launches recorded since the last call and their number, and forget them.  Both outputs are host
  * pointers.  For measurement only: the events cost a few microseconds per launch. */
 int mf_profile_read(ps_handle ps, double *sgd_ms_host_out, int64_t *launches_host_out, void *stream);
+
+/* ---- knowledge graph embeddings (Sec. 4.1 "Knowledge graph embeddings", Appendix A) ---- */
+/* One mini-batch step of ComplEx training with AdaGrad and negative sampling, the AdaGrad accumulators stored in
+ * the server next to the embeddings.  Entity e is key e, relation r is key num_entities + r; value_len = 4 * dim:
+ * [0, dim) real parts, [dim, 2 dim) imaginary parts, [2 dim, 4 dim) the accumulators of those 2 dim numbers.
+ * The batch has `batch` positive triples (subj, rel, obj: device arrays of int32 indices); triple b also has
+ * n_neg_subj negatives that replace its subject by neg_subj[b * n_neg_subj + j] and n_neg_obj that replace its
+ * object by neg_obj[b * n_neg_obj + j] (device; the paper perturbs both, 10 times).  The step pulls every key
+ * occurrence (values as they are before the step), computes for every scored triple - label +1 for the positive,
+ * -1 for a negative - score = Re sum_k e_s[k] w_r[k] conj(e_o[k]), loss = log(1 + exp(-label score)), its gradient g
+ * for the 2 dim numbers of each of the three keys, and pushes per occurrence dtheta = -lr g / sqrt(G + g^2 + eps)
+ * and dG = g^2 (G: the pulled accumulator) as cumulative updates, in the order (triple of the batch; positive,
+ * subject negatives, object negatives; subject, relation, object), which fixes the result bit for bit.
+ * worker: as for ps_pull / ps_push (locality statistics).  loss_host_out (may be NULL): sum of the losses of all
+ * scored triples; asking for it synchronizes the stream.  dim <= 256.  Scratch is allocated by the library and
+ * grows with the batch (3 * batch * (1 + n_neg_subj + n_neg_obj) rows). */
+int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, int32_t dim, int64_t batch, const int32_t *subj,
+                 const int32_t *rel, const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj, int32_t n_neg_obj,
+                 const int32_t *neg_obj, float lr, float eps, double *loss_host_out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -98,6 +98,8 @@ struct dpaps_ps {
     int num_cu = 0;
     MfData mf;
     double *d_sse = nullptr;
+    void *kge_ws = nullptr;           // scratch of kge_sgd_step (grows)
+    size_t kge_ws_bytes = 0;
     std::string last_error;
 };
 

@@ -405,6 +405,7 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
                                const int64_t *col_bounds_host, const int64_t *block_ptr_host, void *stream) {
     if (!ps || m <= 0 || n <= 0 || nnz < 0 || d_row <= 0 || d_col <= 0 || !block_ptr_host) return PS_EINVAL;
     if (m + n != ps->K) return PS_EINVAL;
+    if (ps->L > 256) { ps->last_error = "the SGD kernels take ranks up to 256"; return PS_ELIMIT; }
     if (nnz > 0 && (!rows || !cols || !vals)) return PS_EINVAL;
     if (m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31) || nnz >= ((int64_t)1 << 32)) return PS_ELIMIT;
     if ((int64_t)d_row * d_col >= ((int64_t)1 << 31)) return PS_ELIMIT;

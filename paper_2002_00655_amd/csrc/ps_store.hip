@@ -160,7 +160,7 @@ static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + b
 extern "C" int ps_create(int64_t num_keys, int32_t value_len, int32_t num_workers, ps_handle *out) {
     if (!out) return PS_EINVAL;
     *out = nullptr;
-    if (num_keys <= 0 || value_len <= 0 || value_len > 256 || num_workers <= 0 || num_workers > 2048) return PS_EINVAL;
+    if (num_keys <= 0 || value_len <= 0 || value_len > 1024 || num_workers <= 0 || num_workers > 2048) return PS_EINVAL;
     dpaps_ps *ps = new (std::nothrow) dpaps_ps();
     if (!ps) return PS_ENOMEM;
     ps->K = num_keys; ps->L = value_len; ps->W = num_workers;
@@ -211,6 +211,7 @@ extern "C" int ps_destroy(ps_handle ps) {
     if (ps->d_sse) (void)hipFree(ps->d_sse);
     if (ps->stamp_h) (void)hipFree(ps->stamp_h);
     if (ps->ws) (void)hipFree(ps->ws);
+    if (ps->kge_ws) (void)hipFree(ps->kge_ws);
     if (ps->d_tasks) (void)hipFree(ps->d_tasks);
     for (hipEvent_t e : ps->ev_pool) (void)hipEventDestroy(e);
     delete ps;

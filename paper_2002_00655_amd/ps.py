@@ -24,7 +24,7 @@ OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES, OPT_MF_PROFILE, OPT_MF_GROUPED, O
 
 EXPORTS = ["ps_create", "ps_destroy", "ps_pull", "ps_push", "ps_localize", "ps_owner", "ps_stats", "ps_status",
            "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_train_sse",
-           "mf_profile_read"]
+           "mf_profile_read", "kge_sgd_step"]
 
 
 class PSError(RuntimeError):
@@ -55,6 +55,7 @@ def load_library() -> C.CDLL:
     lib.mf_sgd_epoch.argtypes = [vp, vp, vp, i32, f32, f32, vp]
     lib.mf_train_sse.argtypes = [vp, vp, vp]
     lib.mf_profile_read.argtypes = [vp, vp, vp, vp]
+    lib.kge_sgd_step.argtypes = [vp, i32, i64, i32, i64, vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp]
     for name in EXPORTS:
         if name != "ps_last_error":
             getattr(lib, name).restype = C.c_int
@@ -180,6 +181,19 @@ class ParameterServer:
         out = C.c_double(0.0)
         self._check(_lib.mf_train_sse(self._h, C.addressof(out), _stream()), "mf_train_sse")
         return float(out.value)
+
+    def kge_sgd_step(self, num_entities, dim, subj, rel, obj, neg_subj, neg_obj, lr, eps, worker: int = -1,
+                     want_loss: bool = True):
+        """One mini-batch step of ComplEx training (see include/dpaps.h); returns the summed loss or None."""
+        subj, rel, obj = _dev(subj, torch.int32), _dev(rel, torch.int32), _dev(obj, torch.int32)
+        batch = subj.numel()
+        ns_ = _dev(neg_subj, torch.int32).reshape(batch, -1) if batch else torch.zeros((0, 0), dtype=torch.int32)
+        no_ = _dev(neg_obj, torch.int32).reshape(batch, -1) if batch else torch.zeros((0, 0), dtype=torch.int32)
+        loss = C.c_double(0.0)
+        self._check(_lib.kge_sgd_step(self._h, worker, num_entities, dim, batch, subj.data_ptr(), rel.data_ptr(), obj.data_ptr(),
+                                      ns_.shape[1], ns_.data_ptr(), no_.shape[1], no_.data_ptr(), float(lr), float(eps),
+                                      C.addressof(loss) if want_loss else None, _stream()), "kge_sgd_step")
+        return float(loss.value) if want_loss else None
 
 
 def mf_block_ratings(m, n, rows, cols, vals, row_bounds, col_bounds):

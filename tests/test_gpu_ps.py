@@ -19,7 +19,7 @@ def _zipf_keys(rng, K, n, s=1.1):
     return rng.permutation(K)[rng.choice(K, size=n, p=p)].astype(np.int64)
 
 
-@pytest.mark.parametrize("K,L,W,seed", [(5000, 100, 4, 0), (777, 16, 7, 1), (64, 1, 1, 2), (3001, 130, 5, 3), (100000, 50, 256, 4)])
+@pytest.mark.parametrize("K,L,W,seed", [(5000, 100, 4, 0), (777, 16, 7, 1), (64, 1, 1, 2), (3001, 130, 5, 3), (100000, 50, 256, 4), (900, 1024, 3, 5)])
 def test_random_operations_match_oracle(K, L, W, seed):
     torch = _torch()
     from oracle.oracle import Oracle
@@ -125,7 +125,7 @@ def test_errors():
     srv.status()
     assert (srv.owner(good) == 3).all()
     with pytest.raises(P.PSError) as e:
-        P.ParameterServer(10, 257, 2)
+        P.ParameterServer(10, 1025, 2)
     assert e.value.code == P.PS_EINVAL
 
 

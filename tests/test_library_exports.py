@@ -40,7 +40,7 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.ps_create(ctypes.c_int64(10), ctypes.c_int32(4), ctypes.c_int32(2), None) == -1
     h = ctypes.c_void_p()
     assert lib.ps_create(ctypes.c_int64(0), ctypes.c_int32(4), ctypes.c_int32(2), ctypes.byref(h)) == -1
-    assert lib.ps_create(ctypes.c_int64(10), ctypes.c_int32(300), ctypes.c_int32(2), ctypes.byref(h)) == -1
+    assert lib.ps_create(ctypes.c_int64(10), ctypes.c_int32(2000), ctypes.c_int32(2), ctypes.byref(h)) == -1
     assert lib.ps_destroy(None) == -1
     assert lib.ps_pull(None, 0, None, ctypes.c_int64(0), None, None) == -1
     assert lib.ps_status(None, None) == -1
