@@ -7,7 +7,7 @@ inputs (entries, factors, schedule) are resident in device memory before the
 timed region starts.  Prints ONE JSON line on stdout; everything else goes to
 stderr.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|medium|tiny|wide] [--scale S]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|medium|tiny|wide|complex] [--scale S]
 """
 from __future__ import annotations
 
@@ -78,12 +78,96 @@ def cpu_baseline(w, rb, cb, d, target_seconds=15.0):
             "sample": f"first {ns} of {d} strata of one epoch ({rows.size} updates, {dt:.1f} s), fp32 oracle, gcc -O2"}
 
 
+def bench_kge(args, torch, dev) -> int:
+    """One step = one mini-batch of the knowledge-graph-embedding workload: keys of the batch's positive triples
+    and their negatives, pull, per-occurrence AdaGrad updates, push.  Value: scored triples per second."""
+    from paper_2002_00655_amd import workloads as wl
+    from paper_2002_00655_amd import ps as P
+    t0 = time.perf_counter()
+    B = args.batch
+    nsteps = args.warmup + args.steps
+    s = args.scale
+    w = wl.make_kge(num_entities=max(1000, int(500_000 * s)), num_relations=max(10, int(600 * s)), triples=max(B * nsteps, int(3_000_000 * s)))
+    t_gen = time.perf_counter() - t0
+    K, L = w.num_entities + w.num_relations, 4 * w.dim
+    ns, no = w.neg_subj.shape[1], w.neg_obj.shape[1]
+    per = 1 + ns + no
+    log(f"workload {w.name}: {w.num_entities} entities, {w.num_relations} relations, {w.subj.size} triples, dim {w.dim}, "
+        f"{ns}+{no} negatives, batch {B}; generated in {t_gen:.1f} s")
+    srv = P.ParameterServer(K, L, 4)
+    init = torch.zeros((K, L), device=dev)
+    init[:w.num_entities, :2 * w.dim] = torch.from_numpy(w.E0).to(dev)
+    init[w.num_entities:, :2 * w.dim] = torch.from_numpy(w.R0).to(dev)
+    for lo in range(0, K, 1 << 17):
+        hi = min(K, lo + (1 << 17))
+        srv.push(torch.arange(lo, hi, device=dev), init[lo:hi])
+    del init
+    nb = w.subj.size // B
+    subj, rel, obj, negs, nego = (torch.from_numpy(np.ascontiguousarray(x[:nb * B])).to(dev) for x in (w.subj, w.rel, w.obj, w.neg_subj, w.neg_obj))
+
+    def step(i, want_loss=False):
+        sl = slice((i % nb) * B, (i % nb + 1) * B)
+        return srv.kge_sgd_step(w.num_entities, w.dim, subj[sl], rel[sl], obj[sl], negs[sl], nego[sl], 0.1, 1e-10, 0, want_loss=want_loss)
+    loss0 = step(0, True) / (B * per)
+    for i in range(1, max(1, args.warmup)):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    ev1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    srv.status()
+    loss1 = step(args.warmup + args.steps, True) / (B * per)
+    ms_per_step = dt / args.steps * 1e3
+    scored_per_s = B * per * args.steps / dt
+    log(f"{args.steps} steps in {dt:.3f} s: {ms_per_step:.3f} ms/step (stream time {ev0.elapsed_time(ev1) / args.steps:.3f} ms), "
+        f"{scored_per_s / 1e6:.2f} M scored triples/s; mean loss {loss0:.4f} -> {loss1:.4f}")
+    # byte model per key occurrence: its value read once (pull) and the stored value read and written once (push),
+    # plus its 8-byte key: 3 x 4 L + 8
+    bytes_per_occ = 12 * L + 8
+    model = 3 * scored_per_s * bytes_per_occ / 1e9
+    result = {
+        "metric": "scored triples/sec, ComplEx dim %d with AdaGrad through pull/push" % w.dim, "value": scored_per_s, "unit": "triples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "complex_kge", "entities": w.num_entities, "relations": w.num_relations, "dim": w.dim,
+                   "negatives": f"{ns}+{no}", "batch": B, "occurrences_per_step": 3 * B * per, "lr": 0.1, "eps": 1e-10},
+        "positive_triples_per_s": B * args.steps / dt,
+        "roofline": {"bound": "hbm", "achieved": model, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": model / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "whole step (keys, pull, updates, push)", "bytes_per_occurrence": bytes_per_occ,
+                     "note": "algorithmic bytes (model: 12 L + 8 per key occurrence) over the step's wall time"},
+        "mean_loss": [loss0, loss1],
+    }
+    if not args.no_cpu_baseline:
+        from oracle.oracle import Oracle
+        nbc = max(1, min(B, int(args.cpu_seconds * 4000 / per)))          # sized with an assumed 4,000 scored triples/s
+        orc = Oracle("f32", K, L, 4)
+        init_h = np.zeros((K, L), np.float32)
+        init_h[:w.num_entities, :2 * w.dim] = w.E0
+        init_h[w.num_entities:, :2 * w.dim] = w.R0
+        orc.push(np.arange(K), init_h)
+        del init_h
+        t0 = time.perf_counter()
+        orc.kge_step(w.num_entities, w.dim, w.subj[:nbc], w.rel[:nbc], w.obj[:nbc], w.neg_subj[:nbc], w.neg_obj[:nbc], 0.1, 1e-10, 0)
+        dtc = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": nbc * per / dtc, "unit": "triples/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"one step of {nbc} positive triples ({nbc * per} scored, {dtc:.1f} s), fp32 oracle, gcc -O2"}
+        log(f"cpu oracle: {result['cpu_baseline']['value']:.0f} scored triples/s")
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "wide"])
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "wide", "complex"])
+    ap.add_argument("--batch", type=int, default=8192, help="positive triples per step (complex only)")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--bounds", default="equal", choices=["equal", "balanced"])
     ap.add_argument("--waves", type=int, default=16)
@@ -115,6 +199,8 @@ def main() -> int:
         return 0
     props = torch.cuda.get_device_properties(0)
     log(f"device: {props.name} {props.gcnArchName}, {props.multi_processor_count} CUs, host cores {os.cpu_count()}")
+    if args.workload == "complex":
+        return bench_kge(args, torch, dev)
 
     t0 = time.perf_counter()
     w = wl.make_mf(args.workload, scale=args.scale)

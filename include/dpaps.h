@@ -76,8 +76,11 @@ enum {
     PS_OPT_MF_GROUPED = 5,      /* 1 (default): where rank <= 128 and PS_OPT_MF_EXACT is off, process the long column
                                    runs of a block in groups of up to 15 entries with dense 16x16xr products and
                                    the other entries row by row; 0: every column run entry by entry */
-    PS_OPT_MF_HEAVY_LEN = 6     /* column runs with at least this many entries count as long (default 48; read by
+    PS_OPT_MF_HEAVY_LEN = 6,    /* column runs with at least this many entries count as long (default 48; read by
                                    mf_load_ratings, so set it before) */
+    PS_OPT_PUSH_SEQUENTIAL = 7  /* 1: ps_push adds the update terms of a key strictly one after the other in argument
+                                   order, however many there are (one wavefront per key; for bit-for-bit checks
+                                   against a sequential server).  0 (default): see ps_push */
 };
 
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */
@@ -94,9 +97,16 @@ int ps_destroy(ps_handle ps);
 int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, float *out, void *stream);
 
 /* push: cumulative (Sec. 2.1) - value[keys[p]] += deltas[p*value_len ..], one
- * fp32 addition per term.  All terms of a call are applied; those of one key
- * in increasing p, which makes the result independent of how the device
- * schedules the work (no floating-point atomics). */
+ * fp32 addition per term.  All terms of a call are applied, in an order that
+ * depends on the arguments only, never on how the device schedules the work (no
+ * floating-point atomics): the (key, p) pairs are sorted by key, p ascending,
+ * and cut into ranges of 64 pairs.  The terms of a key inside one range are
+ * added one after the other in increasing p - onto the stored value where the
+ * key's terms start in that range, onto zero otherwise - and the sums of a
+ * key's ranges are then added in range order.  A key whose terms lie in one
+ * range (every key mentioned once, most keys mentioned a few times) thus gets
+ * exactly what a sequential server computes; with PS_OPT_PUSH_SEQUENTIAL every
+ * key does, at the price of one wavefront per key. */
 int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, const float *deltas, void *stream);
 
 /* localize: relocate the keys to `worker` (Sec. 3.1 "API", Sec. 3.2).  The

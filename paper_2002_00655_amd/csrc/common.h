@@ -88,6 +88,7 @@ struct dpaps_ps {
     int64_t opt_cache_rows = -1;
     int opt_waves = 16;
     int opt_profile = 0;
+    int opt_push_sequential = 0;      // 1: ps_push adds each key's terms strictly one after the other
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
     // event pairs around the SGD kernel launches (only while profiling is on)

@@ -4,14 +4,18 @@
 // model ComplEx, cited there, whose score Re sum_k e_s[k] w_r[k] conj(e_o[k]) is the
 // standard one).  The step is what a worker does for a batch of data points: pull the
 // parameters of the positive triples and of their negatives, compute the updates, push
-// them - with pull and push being the library's own primitives, so routing statistics
-// and the deterministic order of cumulative updates come for free.
+// them.  The pull is accounted exactly like ps_pull (key check, locality statistics,
+// message counts) but its values are read from the store by the kernel that uses them
+// instead of being copied out first; the push is ps_push, which gives the deterministic
+// order of cumulative updates.
 //
 // Key space: entity e is key e, relation r is key num_entities + r.  A value has 4 D
 // numbers: [0, D) real parts, [D, 2 D) imaginary parts, [2 D, 4 D) the AdaGrad
 // accumulators of those 2 D numbers.
 #include "common.h"
 #include "mf_device.h"
+
+int dpaps_account_pull(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);   // ps_store.hip
 
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
 
@@ -32,19 +36,21 @@ __global__ void k_kge_keys(int64_t num_entities, int64_t batch, const int32_t *s
     keys[3 * t + 2] = o;
 }
 
-// One wavefront per scored triple: score, loss, gradient, and the AdaGrad update of every
-// occurrence, written over the pulled values (lane l handles components l, l + 64, ...).
+// One wavefront per scored triple: its three values as the store holds them, score, loss,
+// gradient, and the AdaGrad update of every occurrence, written to the occurrence's row of
+// the update buffer (lane l handles components l, l + 64, ...).
 //   loss = log(1 + exp(-label score)),  g = dloss/dscore * dscore/dtheta,
 //   dtheta = -lr g / sqrt(G + g^2 + eps),  dG = g^2      (G: the pulled accumulator)
 template <int NC>
-__global__ __launch_bounds__(256) void k_kge_grad(int64_t ntriples, int32_t per, int32_t D, float lr, float eps, float *vals,
-                                                   double *loss, const int32_t *err) {
+__global__ __launch_bounds__(256) void k_kge_grad(int64_t ntriples, int32_t per, int32_t D, float lr, float eps, const int64_t *keys,
+                                                   const float *store, float *upd, double *loss, const int32_t *err) {
     if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     const int lane = threadIdx.x & 63;
     const int64_t t = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     if (t >= ntriples) return;
     const int L = 4 * D;
-    float *vs = vals + (3 * t + 0) * L, *vr = vals + (3 * t + 1) * L, *vo = vals + (3 * t + 2) * L;
+    const float *vs = store + keys[3 * t + 0] * L, *vr = store + keys[3 * t + 1] * L, *vo = store + keys[3 * t + 2] * L;
+    float *us = upd + (3 * t + 0) * L, *ur = upd + (3 * t + 1) * L, *uo = upd + (3 * t + 2) * L;
     float sr[NC], si[NC], rr[NC], ri[NC], orl[NC], oi[NC];
     float part = 0.0f;
 #pragma unroll
@@ -72,14 +78,15 @@ __global__ __launch_bounds__(256) void k_kge_grad(int64_t ntriples, int32_t per,
         const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
                                {dl * (sr[c] * orl[c] + si[c] * oi[c]), dl * (sr[c] * oi[c] - si[c] * orl[c])},
                                {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
-        float *v3[3] = {vs, vr, vo};
+        const float *v3[3] = {vs, vr, vo};
+        float *u3[3] = {us, ur, uo};
 #pragma unroll
         for (int role = 0; role < 3; ++role) {
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
                 const float gg = g[role][p], G = v3[role][2 * D + p * D + k];
-                v3[role][p * D + k] = -lr * gg / sqrtf(G + gg * gg + eps);
-                v3[role][2 * D + p * D + k] = gg * gg;
+                u3[role][p * D + k] = -lr * gg / sqrtf(G + gg * gg + eps);
+                u3[role][2 * D + p * D + k] = gg * gg;
             }
         }
     }
@@ -112,7 +119,7 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     const int64_t ntr = batch * per, nocc = 3 * ntr;
     if (nocc >= ((int64_t)1 << 31)) return PS_ELIMIT;
     hipStream_t st = (hipStream_t)stream;
-    // scratch of the step: keys, pulled values (overwritten by the updates), losses
+    // scratch of the step: keys, update terms, losses
     const size_t off_vals = (size_t)((nocc * 8 + 255) / 256 * 256);
     const size_t off_loss = off_vals + (size_t)((nocc * ps->L * 4 + 255) / 256 * 256);
     const size_t bytes = off_loss + (size_t)(ntr + 1) * 8;
@@ -129,14 +136,14 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     double *loss = (double *)((char *)ps->kge_ws + off_loss);
     k_kge_keys<<<grid_for(ntr, 256), 256, 0, st>>>(num_entities, batch, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, keys);
     PS_HIP(ps, hipGetLastError());
-    int rc = ps_pull(ps, worker, keys, nocc, vals, stream);
+    int rc = dpaps_account_pull(ps, worker, keys, nocc, st);
     if (rc) return rc;
     const unsigned blocks = grid_for(ntr * 64, 256);
     switch ((dim + 63) / 64) {
-    case 1: k_kge_grad<1><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, vals, loss, ps->err); break;
-    case 2: k_kge_grad<2><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, vals, loss, ps->err); break;
-    case 3: k_kge_grad<3><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, vals, loss, ps->err); break;
-    default: k_kge_grad<4><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, vals, loss, ps->err); break;
+    case 1: k_kge_grad<1><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
+    case 2: k_kge_grad<2><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
+    case 3: k_kge_grad<3><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
+    default: k_kge_grad<4><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
     }
     PS_HIP(ps, hipGetLastError());
     rc = ps_push(ps, worker, keys, nocc, vals, stream);

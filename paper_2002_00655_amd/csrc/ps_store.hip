@@ -55,63 +55,116 @@ __global__ void k_check_keys(const int64_t *keys, int64_t n, int64_t K, int32_t 
     }
 }
 
-__device__ __forceinline__ void wave_count_add(bool flag, u64 *counter) {
-    u64 b = __ballot(flag);
-    if (b != 0 && (threadIdx.x & 63) == (unsigned)(__ffsll((long long)__ballot(true)) - 1)) atomicAdd(counter, (u64)__popcll(b));
+// ---- routing statistics ----------------------------------------------------
+// A call's kernels run a fixed number of workgroups that walk over the keys.  Each workgroup counts in LDS
+// and adds its counts to the statistics once, at its end.  The message counts need "first mention of a
+// destination in this call": stamps in device memory carry the id of the last call that mentioned the
+// destination; a workgroup remembers in LDS which destinations it has already settled, so that device-wide
+// operations on the few hot stamp words stay rare.
+constexpr int ROUTE_BLOCKS_PER_CU = 2;
+constexpr int SEEN_H = 256, SEEN_PAIR = 1024;          // direct-mapped: entry holds idx + 1 of a settled destination
+
+struct RouteLds {
+    uint32_t count[8];
+    uint32_t seen_h[SEEN_H], seen_o[SEEN_H], seen_pair[SEEN_PAIR];
+};
+
+__device__ __forceinline__ void route_lds_init(RouteLds &l) {
+    for (int i = threadIdx.x; i < (int)(sizeof(RouteLds) / 4); i += blockDim.x) reinterpret_cast<uint32_t *>(&l)[i] = 0;
+    __syncthreads();
+}
+
+__device__ __forceinline__ void lds_count_add(bool flag, uint32_t *counter) {
+    const u64 b = __ballot(flag);
+    if (b != 0 && (threadIdx.x & 63) == (unsigned)(__ffsll((long long)__ballot(true)) - 1)) atomicAdd(counter, (uint32_t)__popcll(b));
+}
+
+// Marks stamps[idx] with this call's id and tells whether this was the first mark of the call: true in
+// exactly one lane of the whole call per idx.  Lanes of a wavefront that name the same idx are served by
+// one of them; a destination the workgroup has settled before is skipped; the exchange is skipped when
+// the stamp is seen to carry the id already (a stale read only costs an exchange).
+__device__ __forceinline__ bool stamp_first(bool want, uint32_t *stamps, int32_t idx, uint32_t call_id, uint32_t *seen, int seen_mask) {
+    bool first = false;
+    const int lane = threadIdx.x & 63;
+    u64 todo = __ballot(want);
+    while (todo != 0) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int32_t idx0 = __builtin_amdgcn_readlane(idx, leader);
+        const u64 same = __ballot(want && idx == idx0);
+        if (lane == leader && seen[idx0 & seen_mask] != (uint32_t)idx0 + 1u) {
+            if (__hip_atomic_load(&stamps[idx0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != call_id)
+                first = atomicExch(&stamps[idx0], call_id) != call_id;
+            seen[idx0 & seen_mask] = (uint32_t)idx0 + 1u;
+        }
+        todo &= ~same;
+    }
+    return first;
 }
 
 // One key that must travel for requester `worker`: home h, current owner o.
 // Within one call the messages to one destination are grouped (Sec. 3.7); the
 // stamps record which destinations this call has already been charged for.
+// count[2..4]: request, forward, reply (or their localize counterparts).
 __device__ __forceinline__ void route_key(bool travels, int32_t worker, int32_t h, int32_t o, int32_t W,
-                                          uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id,
-                                          u64 *c_req, u64 *c_fwd, u64 *c_back) {
-    bool req = false, fwd = false, back = false;
-    if (travels) {
-        if (h != worker) req = atomicExch(&stamp_h[h], call_id) != call_id;
-        bool fresh = atomicExch(&stamp_pair[(int64_t)h * W + o], call_id) != call_id;
-        fwd = fresh && (h != o);
-        if (o != worker) back = atomicExch(&stamp_o[o], call_id) != call_id;
-    }
-    wave_count_add(req, c_req);
-    wave_count_add(fwd, c_fwd);
-    wave_count_add(back, c_back);
+                                          uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, RouteLds &l) {
+    const bool req = stamp_first(travels && h != worker, stamp_h, h, call_id, l.seen_h, SEEN_H - 1);
+    const bool fresh = stamp_first(travels, stamp_pair, h * W + o, call_id, l.seen_pair, SEEN_PAIR - 1);
+    const bool fwd = fresh && (h != o);
+    const bool back = stamp_first(travels && o != worker, stamp_o, o, call_id, l.seen_o, SEEN_H - 1);
+    lds_count_add(req, &l.count[2]);
+    lds_count_add(fwd, &l.count[3]);
+    lds_count_add(back, &l.count[4]);
+}
+
+// adds count[i] to the statistic which[i] (i < 5), one workgroup's share
+__device__ __forceinline__ void route_lds_flush(RouteLds &l, u64 *stats, int w0, int w1, int w2, int w3, int w4) {
+    __syncthreads();
+    const int which[5] = {w0, w1, w2, w3, w4};
+    if (threadIdx.x < 5 && l.count[threadIdx.x] != 0) atomicAdd(&stat_slot(stats)[which[threadIdx.x]], (u64)l.count[threadIdx.x]);
 }
 
 // Locality statistics and message counts of one pull or push call.
-__global__ void k_route_access(const int64_t *keys, int64_t n, int32_t worker, const int32_t *owner, int64_t per_home,
-                               int32_t W, uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id,
-                               u64 *stats, int stat_local, int stat_remote, const int32_t *err) {
+__global__ __launch_bounds__(256) void k_route_access(const int64_t *keys, int64_t n, int32_t worker, const int32_t *owner, int64_t per_home,
+                                                       int32_t W, uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id,
+                                                       u64 *stats, int stat_local, int stat_remote, const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
-    stats = stat_slot(stats);
-    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    bool active = p < n;
-    int64_t k = active ? keys[p] : 0;
-    int32_t o = active ? owner[k] : 0;
-    bool local = active && o == worker, remote = active && o != worker;
-    wave_count_add(local, &stats[stat_local]);
-    wave_count_add(remote, &stats[stat_remote]);
-    route_key(remote, worker, (int32_t)(k / per_home), o, W, stamp_h, stamp_o, stamp_pair, call_id,
-              &stats[PS_STAT_MSG_ACC_REQ], &stats[PS_STAT_MSG_ACC_FWD], &stats[PS_STAT_MSG_ACC_REPLY]);
+    __shared__ RouteLds l;
+    route_lds_init(l);
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t base = (int64_t)blockIdx.x * blockDim.x; base < n; base += step) {     // whole workgroups walk together
+        const int64_t p = base + threadIdx.x;
+        const bool active = p < n;
+        const int64_t k = active ? keys[p] : 0;
+        const int32_t o = active ? owner[k] : 0;
+        const bool local = active && o == worker, remote = active && o != worker;
+        lds_count_add(local, &l.count[0]);
+        lds_count_add(remote, &l.count[1]);
+        route_key(remote, worker, (int32_t)(k / per_home), o, W, stamp_h, stamp_o, stamp_pair, call_id, l);
+    }
+    route_lds_flush(l, stats, stat_local, stat_remote, PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY);
 }
 
 // localize: the home node updates the location at once (Sec. 3.2, step 1); the
 // exchange makes exactly one of several mentions of a key the one that moves it.
-__global__ void k_localize(const int64_t *keys, int64_t n, int32_t worker, int32_t *owner, int64_t per_home, int32_t W,
-                           uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, u64 *stats,
-                           const int32_t *err) {
+__global__ __launch_bounds__(256) void k_localize(const int64_t *keys, int64_t n, int32_t worker, int32_t *owner, int64_t per_home, int32_t W,
+                                                   uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, u64 *stats,
+                                                   const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
-    stats = stat_slot(stats);
-    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    bool active = p < n;
-    int64_t k = active ? keys[p] : 0;
-    int32_t old = worker;
-    if (active) old = atomicExch(&owner[k], worker);
-    bool moved = active && old != worker;
-    wave_count_add(active, &stats[PS_STAT_LOCALIZE_KEYS]);
-    wave_count_add(moved, &stats[PS_STAT_RELOCATED]);
-    route_key(moved, worker, (int32_t)(k / per_home), old, W, stamp_h, stamp_o, stamp_pair, call_id,
-              &stats[PS_STAT_MSG_LOC_REQ], &stats[PS_STAT_MSG_LOC_INSTRUCT], &stats[PS_STAT_MSG_LOC_TRANSFER]);
+    __shared__ RouteLds l;
+    route_lds_init(l);
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t base = (int64_t)blockIdx.x * blockDim.x; base < n; base += step) {
+        const int64_t p = base + threadIdx.x;
+        const bool active = p < n;
+        const int64_t k = active ? keys[p] : 0;
+        int32_t old = worker;
+        if (active) old = atomicExch(&owner[k], worker);
+        const bool moved = active && old != worker;
+        lds_count_add(active, &l.count[0]);
+        lds_count_add(moved, &l.count[1]);
+        route_key(moved, worker, (int32_t)(k / per_home), old, W, stamp_h, stamp_o, stamp_pair, call_id, l);
+    }
+    route_lds_flush(l, stats, PS_STAT_LOCALIZE_KEYS, PS_STAT_RELOCATED, PS_STAT_MSG_LOC_REQ, PS_STAT_MSG_LOC_INSTRUCT, PS_STAT_MSG_LOC_TRANSFER);
 }
 
 __global__ void k_owner(const int64_t *keys, int64_t n, const int32_t *owner, int32_t *out, const int32_t *err) {
@@ -131,10 +184,21 @@ __global__ void k_pull(const int64_t *keys, int64_t n, int32_t L, const float *v
     out[idx] = val[keys[p] * L + c];
 }
 
+// the same in 16-byte pieces, for rows that start on 16-byte boundaries (value_len a multiple of 4) and fewer
+// than 2^32 pieces in all: P pieces per row
+__global__ void k_pull_v4(const int64_t *keys, uint32_t total, uint32_t P, const float4 *val, float4 *out, const int32_t *err) {
+    if (*(volatile const int32_t *)err) return;
+    const uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const uint32_t p = idx / P, c = idx - p * P;
+    out[idx] = val[keys[p] * (int64_t)P + c];
+}
+
 // push, after the (key, position) pairs have been sorted by key with a stable
 // sort: one wavefront per sorted position; the wavefront at the head of a run
 // of equal keys adds that key's update terms one after the other, in
 // increasing position - the order a sequential server would apply them in.
+// (One wavefront per key however often it is mentioned: the checking mode.)
 __global__ void k_push_apply(const uint64_t *skeys, const uint32_t *spos, int64_t n, int32_t L, const float *deltas,
                              float *val, const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
@@ -152,10 +216,123 @@ __global__ void k_push_apply(const uint64_t *skeys, const uint32_t *spos, int64_
     }
 }
 
+// push, the default: the sorted positions are cut into ranges of PUSH_RANGE, one wavefront each, so that a key
+// mentioned thousands of times is summed by many wavefronts.  Inside a range the terms of a key are added
+// one after the other in argument order, starting from the stored value; a key whose terms fill one range
+// only (any key mentioned once, most keys mentioned a few times) therefore gets the sequential server's
+// bits.  Where a key's terms continue from the previous range they are summed from zero into part[2 r];
+// where they start here and continue into the next range the running value goes to part[2 r + 1]; the
+// second kernel adds a key's partial sums in range order.  The result depends on the arguments only.
+constexpr int PUSH_RANGE = 64;
+
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t x, int l) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), l);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+template <int UN>
+__global__ __launch_bounds__(256) void k_push_ranges(const uint64_t *skeys, const uint32_t *spos, int64_t n, int32_t L,
+                                                      const float *deltas, float *val, float *part, const int32_t *err) {
+    if (*(volatile const int32_t *)err) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t q0 = r * PUSH_RANGE;
+    if (q0 >= n) return;
+    const int cnt = (int)(n - q0 < PUSH_RANGE ? n - q0 : PUSH_RANGE);
+    const uint64_t NOKEY = ~0ull;                                      // no key looks like this
+    const uint64_t mk = lane < cnt ? skeys[q0 + lane] : NOKEY;         // lane t: sorted position q0 + t
+    const int mp = lane < cnt ? (int)spos[q0 + lane] : 0;
+    const uint64_t prevk = q0 > 0 ? skeys[q0 - 1] : NOKEY;
+    const uint64_t nextk = q0 + cnt < n ? skeys[q0 + cnt] : NOKEY;
+    const uint64_t before = lane > 0 && lane < cnt ? skeys[q0 + lane - 1] : NOKEY;
+    const u64 heads = __ballot(lane < cnt && (lane == 0 || before != mk));   // positions where a key's terms start
+    const bool first_open = readlane_u64(mk, 0) == prevk;              // the first key's terms continue from the range before
+    const int c = blockIdx.y * 64 + lane;                              // this wavefront's 64 components
+    const bool in = c < L;
+    // UN positions at a time: all their loads first (update terms, and the stored value where a key's terms
+    // start), then the additions in order
+    float v = 0.0f;
+    uint64_t key = NOKEY;                                              // key of the terms being summed
+    bool key_open = false;                                             // ... which continue from the range before
+    for (int u0 = 0; u0 < cnt; u0 += UN) {
+        float d[UN], b[UN];
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const int u = u0 + i < cnt ? u0 + i : cnt - 1;
+            const bool is_head = u0 + i < cnt && ((heads >> u) & 1) != 0 && !(u == 0 && first_open);
+            d[i] = in && u0 + i < cnt ? deltas[(int64_t)__builtin_amdgcn_readlane(mp, u) * L + c] : 0.0f;
+            b[i] = 0.0f;
+            if (is_head && in) b[i] = val[(int64_t)readlane_u64(mk, u) * L + c];
+        }
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const int u = u0 + i;
+            if (u < cnt) {
+                if ((heads >> u) & 1) {
+                    if (u > 0 && in) {                                 // the previous key's terms end here
+                        if (key_open) part[(2 * r) * L + c] = v;
+                        else val[(int64_t)key * L + c] = v;
+                    }
+                    key = readlane_u64(mk, u);
+                    key_open = u == 0 && first_open;
+                    v = b[i];
+                }
+                v = v + d[i];
+            }
+        }
+    }
+    if (in) {
+        if (key_open) part[(2 * r) * L + c] = v;
+        else if (key == nextk) part[(2 * r + 1) * L + c] = v;
+        else val[(int64_t)key * L + c] = v;
+    }
+}
+
+// Second kernel: the wavefront of the range in which a key's terms start and do not end adds the partial sums
+// of the following ranges, in order, and stores the value.  blockIdx.y: which 64 components.
+__global__ __launch_bounds__(256) void k_push_join(const uint64_t *skeys, int64_t n, int32_t L, const float *part, float *val,
+                                                    const int32_t *err) {
+    if (*(volatile const int32_t *)err) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t q1 = (r + 1) * PUSH_RANGE;
+    if (q1 >= n) return;                                               // nothing follows this range
+    const uint64_t key = skeys[q1 - 1];
+    if (skeys[q1] != key) return;                                      // its last key ends here
+    if (r > 0 && skeys[q1 - PUSH_RANGE] == key && skeys[q1 - PUSH_RANGE - 1] == key) return;   // it started earlier
+    // m: how many of the following ranges begin with this key
+    int64_t m = 0;
+    for (;;) {
+        const int64_t q = (r + 1 + m + lane) * PUSH_RANGE;
+        const u64 b = __ballot(q < n && skeys[q < n ? q : 0] == key);
+        const int run = b == ~0ull ? 64 : __ffsll((long long)~b) - 1;
+        m += run;
+        if (run < 64) break;
+    }
+    const int c = blockIdx.y * 64 + lane;
+    if (c >= L) return;
+    float v = part[(2 * r + 1) * L + c];
+    int64_t j = 1;
+    for (; j + 16 <= m + 1; j += 16) {
+        float d[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) d[i] = part[(2 * (r + j + i)) * L + c];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v = v + d[i];
+    }
+    for (; j <= m; ++j) v = v + part[(2 * (r + j)) * L + c];
+    val[(int64_t)key * L + c] = v;
+}
+
 // ---------------------------------------------------------------------------
 // C ABI
 // ---------------------------------------------------------------------------
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
+static inline unsigned route_grid(const dpaps_ps *ps, int64_t n) {
+    const int64_t need = (n + 255) / 256, cap = (int64_t)ROUTE_BLOCKS_PER_CU * (ps->num_cu > 0 ? ps->num_cu : 1);
+    return (unsigned)(need < cap ? need : cap);
+}
 
 extern "C" int ps_create(int64_t num_keys, int32_t value_len, int32_t num_workers, ps_handle *out) {
     if (!out) return PS_EINVAL;
@@ -235,15 +412,24 @@ static uint32_t next_call_id(dpaps_ps *ps, hipStream_t st) {
     return ps->call_id;
 }
 
+// what ps_pull does before it reads: key check, locality statistics and message counts
+int dpaps_account_pull(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);
+
 static int route_access(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, int st_local, int st_remote,
                         hipStream_t st) {
     if (worker < 0 || n == 0) return PS_OK;
     uint32_t id = next_call_id(ps, st);
-    k_route_access<<<grid_for(n, 256), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
+    k_route_access<<<route_grid(ps, n), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
                                                      ps->stamp_o, ps->stamp_pair, id, ps->stats, st_local, st_remote,
                                                      ps->err);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
+}
+
+int dpaps_account_pull(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st) {
+    int rc = launch_check(ps, keys, n, st);
+    if (rc) return rc;
+    return route_access(ps, worker, keys, n, PS_STAT_PULL_LOCAL, PS_STAT_PULL_REMOTE, st);
 }
 
 extern "C" int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, float *out, void *stream) {
@@ -251,11 +437,14 @@ extern "C" int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     if (worker < -1 || worker >= ps->W) return PS_EWORKER;
     if (n == 0) return PS_OK;
     hipStream_t st = (hipStream_t)stream;
-    int rc = launch_check(ps, keys, n, st);
+    int rc = dpaps_account_pull(ps, worker, keys, n, st);
     if (rc) return rc;
-    rc = route_access(ps, worker, keys, n, PS_STAT_PULL_LOCAL, PS_STAT_PULL_REMOTE, st);
-    if (rc) return rc;
-    k_pull<<<grid_for(n * ps->L, 256), 256, 0, st>>>(keys, n, ps->L, ps->val, out, ps->err);
+    const int64_t pieces = n * (ps->L / 4);
+    if (ps->L % 4 == 0 && pieces < ((int64_t)1 << 32) - 256 && ((uintptr_t)out & 15) == 0)
+        k_pull_v4<<<grid_for(pieces, 256), 256, 0, st>>>(keys, (uint32_t)pieces, (uint32_t)(ps->L / 4),
+                                                          reinterpret_cast<const float4 *>(ps->val), reinterpret_cast<float4 *>(out), ps->err);
+    else
+        k_pull<<<grid_for(n * ps->L, 256), 256, 0, st>>>(keys, n, ps->L, ps->val, out, ps->err);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
 }
@@ -279,15 +468,27 @@ extern "C" int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     rocprim::counting_iterator<uint32_t> iota(0);
     PS_HIP(ps, rocprim::radix_sort_pairs(nullptr, temp_bytes, kin, (uint64_t *)nullptr, iota, (uint32_t *)nullptr,
                                          (size_t)n, 0, key_bits, st));
-    size_t off_keys = 0, off_pos = align_up((size_t)n * 8), off_tmp = off_pos + align_up((size_t)n * 4);
+    const int64_t nranges = (n + PUSH_RANGE - 1) / PUSH_RANGE;
+    const size_t part_bytes = ps->opt_push_sequential ? 0 : align_up((size_t)nranges * 2 * ps->L * sizeof(float));
+    size_t off_keys = 0, off_pos = align_up((size_t)n * 8), off_part = off_pos + align_up((size_t)n * 4), off_tmp = off_part + part_bytes;
     rc = dpaps_ws_reserve(ps, off_tmp + temp_bytes);
     if (rc) return rc;
     uint64_t *skeys = (uint64_t *)((char *)ps->ws + off_keys);
     uint32_t *spos = (uint32_t *)((char *)ps->ws + off_pos);
+    float *part = (float *)((char *)ps->ws + off_part);
     void *tmp = (char *)ps->ws + off_tmp;
     PS_HIP(ps, rocprim::radix_sort_pairs(tmp, temp_bytes, kin, skeys, iota, spos, (size_t)n, 0, key_bits, st));
-    k_push_apply<<<grid_for(n * 64, 256), 256, 0, st>>>(skeys, spos, n, ps->L, deltas, ps->val, ps->err);
+    if (ps->opt_push_sequential) {
+        k_push_apply<<<grid_for(n * 64, 256), 256, 0, st>>>(skeys, spos, n, ps->L, deltas, ps->val, ps->err);
+        PS_HIP(ps, hipGetLastError());
+        return PS_OK;
+    }
+    k_push_ranges<16><<<dim3(grid_for(nranges * 64, 256), (unsigned)((ps->L + 63) / 64)), 256, 0, st>>>(skeys, spos, n, ps->L, deltas, ps->val, part, ps->err);
     PS_HIP(ps, hipGetLastError());
+    if (nranges > 1) {
+        k_push_join<<<dim3(grid_for(nranges * 64, 256), (unsigned)((ps->L + 63) / 64)), 256, 0, st>>>(skeys, n, ps->L, part, ps->val, ps->err);
+        PS_HIP(ps, hipGetLastError());
+    }
     return PS_OK;
 }
 
@@ -299,7 +500,7 @@ extern "C" int ps_localize(ps_handle ps, const int64_t *keys, int64_t n, int32_t
     int rc = launch_check(ps, keys, n, st);
     if (rc) return rc;
     uint32_t id = next_call_id(ps, st);
-    k_localize<<<grid_for(n, 256), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
+    k_localize<<<route_grid(ps, n), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
                                                  ps->stamp_o, ps->stamp_pair, id, ps->stats, ps->err);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
@@ -356,6 +557,7 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
     case PS_OPT_MF_WAVES: if (value < 1 || value > 16) return PS_EINVAL; ps->opt_waves = (int)value; return PS_OK;
     case PS_OPT_MF_PROFILE: ps->opt_profile = value != 0; return PS_OK;
     case PS_OPT_MF_GROUPED: ps->opt_grouped = value != 0; return PS_OK;
+    case PS_OPT_PUSH_SEQUENTIAL: ps->opt_push_sequential = value != 0; return PS_OK;
     case PS_OPT_MF_HEAVY_LEN:
         if (value < 1 || value > (1 << 30)) return PS_EINVAL;
         ps->opt_heavy_len = (int)value; return PS_OK;

@@ -1,7 +1,10 @@
 """GPU parity: parameter-server primitives of the HIP library against the CPU
-oracle, element by element, on the same seeded inputs.  Values of pull/push are
-compared bit for bit with the fp32 oracle (one fp32 addition per update term,
-in argument order); the owner map and every routing counter are exact."""
+oracle, element by element, on the same seeded inputs.  With the sequential
+push order switched on, values of pull/push are compared bit for bit with the
+fp32 oracle (one fp32 addition per update term, in argument order); with the
+default order (a key's terms summed range by range) they must be as close to
+the fp64 oracle as the fp32 oracle is.  The owner map and every routing
+counter are exact in both."""
 import numpy as np
 import pytest
 
@@ -19,14 +22,27 @@ def _zipf_keys(rng, K, n, s=1.1):
     return rng.permutation(K)[rng.choice(K, size=n, p=p)].astype(np.int64)
 
 
-@pytest.mark.parametrize("K,L,W,seed", [(5000, 100, 4, 0), (777, 16, 7, 1), (64, 1, 1, 2), (3001, 130, 5, 3), (100000, 50, 256, 4), (900, 1024, 3, 5)])
-def test_random_operations_match_oracle(K, L, W, seed):
+def _close_as_fp32(got, want32, exact):
+    """got is as close to the fp64 result as the fp32 oracle is (x 1.5, plus a few ulps of the largest value)."""
+    scale = float(np.abs(exact).max()) if exact.size else 0.0
+    err_gpu = float(np.abs(got - exact).max()) if exact.size else 0.0
+    err_f32 = float(np.abs(want32 - exact).max()) if exact.size else 0.0
+    print(f"  max abs difference to the fp64 oracle: GPU {err_gpu:.3e}, fp32 oracle {err_f32:.3e} (largest value {scale:.3g})", flush=True)
+    return err_gpu <= 1.5 * err_f32 + 4 * 2.0 ** -24 * scale
+
+
+@pytest.mark.parametrize("K,L,W,seed,sequential", [(5000, 100, 4, 0, 1), (777, 16, 7, 1, 1), (64, 1, 1, 2, 1), (3001, 130, 5, 3, 1),
+                                                   (100000, 50, 256, 4, 1), (900, 1024, 3, 5, 1),
+                                                   (5000, 100, 4, 0, 0), (64, 1, 1, 2, 0), (3001, 130, 5, 3, 0), (900, 1024, 3, 5, 0)])
+def test_random_operations_match_oracle(K, L, W, seed, sequential):
     torch = _torch()
     from oracle.oracle import Oracle
     from paper_2002_00655_amd import ps as P
-    print(f"case K={K} L={L} W={W} seed={seed}", flush=True)
+    print(f"case K={K} L={L} W={W} seed={seed} sequential={sequential}", flush=True)
     rng = np.random.default_rng(seed)
     orc, srv = Oracle("f32", K, L, W), P.ParameterServer(K, L, W)
+    o64 = None if sequential else Oracle("f64", K, L, W)
+    srv.set_option(P.OPT_PUSH_SEQUENTIAL, sequential)
     dev = torch.device("cuda")
     for step in range(40):
         op = int(rng.integers(0, 3))
@@ -36,26 +52,39 @@ def test_random_operations_match_oracle(K, L, W, seed):
         if op == 0:
             worker = int(rng.integers(-1, W))
             got = srv.pull(kt, worker).cpu().numpy()
-            assert np.array_equal(got, orc.pull(keys, worker)), f"pull step {step}"
+            if sequential:
+                assert np.array_equal(got, orc.pull(keys, worker)), f"pull step {step}"
+            else:
+                assert _close_as_fp32(got, orc.pull(keys, worker), o64.pull(keys, worker)), f"pull step {step}"
         elif op == 1:
             worker = int(rng.integers(-1, W))
             d = rng.standard_normal((n, L)).astype(np.float32)
             srv.push(kt, torch.from_numpy(d).to(dev), worker)
             orc.push(keys, d, worker)
+            if o64 is not None:
+                o64.push(keys, d.astype(np.float64), worker)
         else:
             worker = int(rng.integers(0, W))
             srv.localize(kt, worker)
             orc.localize(keys, worker)
+            if o64 is not None:
+                o64.localize(keys, worker)
         if step % 8 == 7:
             assert srv.stats() == orc.stats(), f"stats step {step}"
     allk = torch.arange(K, device=dev)
-    assert np.array_equal(srv.pull(allk).cpu().numpy(), orc.pull(np.arange(K)))
+    got = srv.pull(allk).cpu().numpy()
+    if sequential:
+        assert np.array_equal(got, orc.pull(np.arange(K)))
+    else:
+        assert _close_as_fp32(got, orc.pull(np.arange(K)), o64.pull(np.arange(K)))
     assert np.array_equal(srv.owner().cpu().numpy(), orc.owner())
     assert srv.stats() == orc.stats()
 
 
-def test_push_applies_duplicates_in_argument_order():
-    """One key mentioned 10,000 times: only the sequential order reproduces the oracle's bits."""
+@pytest.mark.parametrize("sequential", [1, 0])
+def test_push_applies_duplicates_in_argument_order(sequential):
+    """One key mentioned 10,000 times: only the sequential order reproduces the oracle's bits; the default order
+    is as accurate, and gives the same bits every time."""
     torch = _torch()
     from oracle.oracle import Oracle
     from paper_2002_00655_amd import ps as P
@@ -65,11 +94,49 @@ def test_push_applies_duplicates_in_argument_order():
     rng.shuffle(keys)
     d = (rng.standard_normal((keys.size, L)) * 10.0 ** rng.integers(-3, 4, size=(keys.size, 1))).astype(np.float32)
     orc, srv = Oracle("f32", K, L, 2), P.ParameterServer(K, L, 2)
+    srv.set_option(P.OPT_PUSH_SEQUENTIAL, sequential)
     orc.push(keys, d, 1)
     srv.push(torch.from_numpy(keys).cuda(), torch.from_numpy(d).cuda(), 1)
     got = srv.pull(torch.arange(K, device="cuda")).cpu().numpy()
-    assert np.array_equal(got, orc.pull(np.arange(K)))
+    if sequential:
+        assert np.array_equal(got, orc.pull(np.arange(K)))
+    else:
+        o64 = Oracle("f64", K, L, 2)
+        o64.push(keys, d.astype(np.float64), 1)
+        assert _close_as_fp32(got, orc.pull(np.arange(K)), o64.pull(np.arange(K)))
+        for _ in range(3):
+            again = P.ParameterServer(K, L, 2)
+            again.push(torch.from_numpy(keys).cuda(), torch.from_numpy(d).cuda(), 1)
+            assert np.array_equal(again.pull(torch.arange(K, device="cuda")).cpu().numpy(), got)
     assert srv.stats() == orc.stats()
+
+
+@pytest.mark.parametrize("n_same,offset", [(2, 63), (64, 0), (65, 0), (128, 0), (129, 5), (200, 60), (1, 63), (4097, 1)])
+def test_push_runs_across_range_boundaries(n_same, offset):
+    """A key's terms placed so that they start, end or lie right at the boundaries between ranges of 64 sorted
+    positions; two terms across a boundary still give the sequential bits (0 + x is exact)."""
+    torch = _torch()
+    from oracle.oracle import Oracle
+    from paper_2002_00655_amd import ps as P
+    rng = np.random.default_rng(n_same + offset)
+    K, L = 500, 70
+    # keys 0 .. offset-1 once each (they sort first), then key 250 n_same times, then higher keys once each
+    keys = np.concatenate([np.arange(offset), np.full(n_same, 250), 300 + np.arange(100)]).astype(np.int64)
+    keys = keys[rng.permutation(keys.size)]
+    d = rng.standard_normal((keys.size, L)).astype(np.float32)
+    orc, o64, srv = Oracle("f32", K, L, 2), Oracle("f64", K, L, 2), P.ParameterServer(K, L, 2)
+    for o in (orc, o64):
+        o.push(np.arange(K), np.ones((K, L)))
+        o.push(keys, d.astype(np.float64) if o is o64 else d, 0)
+    srv.push(torch.arange(K, device="cuda"), torch.ones((K, L), device="cuda"))
+    srv.push(torch.from_numpy(keys).cuda(), torch.from_numpy(d).cuda(), 0)
+    got = srv.pull(torch.arange(K, device="cuda")).cpu().numpy()
+    want = orc.pull(np.arange(K))
+    others = np.arange(K) != 250
+    assert np.array_equal(got[others], want[others])
+    if n_same <= 2:
+        assert np.array_equal(got, want)
+    assert _close_as_fp32(got, want, o64.pull(np.arange(K)))
 
 
 def test_location_transparency_and_single_owner():
