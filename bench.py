@@ -41,7 +41,7 @@ def kernel_sources_hash():
 
 
 def measured_traffic(args):
-    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel)
+    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0)
     if kernel_sources_hash() == TRAFFIC["kernel_sha256_16"] and key == TRAFFIC["workload"]:
         return TRAFFIC["bytes_per_launch"]
     return None     # the kernel (or the workload) is not the one the counters were taken with
@@ -173,6 +173,7 @@ def main() -> int:
     ap.add_argument("--waves", type=int, default=16)
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
+    ap.add_argument("--team-max", type=int, default=0, help="most wavefronts per long column run (0: library default)")
     ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -226,6 +227,8 @@ def main() -> int:
     srv.set_option(P.OPT_MF_CACHE_ROWS, args.cache_rows)
     if args.heavy_len > 0:
         srv.set_option(P.OPT_MF_HEAVY_LEN, args.heavy_len)
+    if args.team_max > 0:
+        srv.set_option(P.OPT_MF_TEAM_MAX, args.team_max)
     if args.entry_kernel:
         srv.set_option(P.OPT_MF_GROUPED, 0)
     kernel_name = "k_mf_sgd" if (args.entry_kernel or w.rank > 128) else "k_mf_sgd_chunk"

@@ -78,9 +78,11 @@ enum {
                                    the other entries row by row; 0: every column run entry by entry */
     PS_OPT_MF_HEAVY_LEN = 6,    /* column runs with at least this many entries count as long (default 48; read by
                                    mf_load_ratings, so set it before) */
-    PS_OPT_PUSH_SEQUENTIAL = 7  /* 1: ps_push adds the update terms of a key strictly one after the other in argument
+    PS_OPT_PUSH_SEQUENTIAL = 7, /* 1: ps_push adds the update terms of a key strictly one after the other in argument
                                    order, however many there are (one wavefront per key; for bit-for-bit checks
                                    against a sequential server).  0 (default): see ps_push */
+    PS_OPT_MF_TEAM_MAX = 8      /* grouped SGD kernel: the most wavefronts that take the groups of one long column run
+                                   in turn, 1..14 (default 5) */
 };
 
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */

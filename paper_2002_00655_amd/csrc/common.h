@@ -55,6 +55,8 @@ struct MfData {
     // heavy); gstart[run_gptr[r] + g] is the start of group g relative to the run's first entry, one more entry = length
     int64_t *run_gptr = nullptr;      // num_runs + 1
     int32_t *gstart = nullptr;        // num_gstart
+    uint32_t *team_plan = nullptr;    // 16 words per block: which heavy runs each wavefront takes (built on first use)
+    int team_plan_waves = 0;          // the number of heavy wavefronts it was built for
     int64_t num_gstart = 0;
     // block geometry
     int64_t *row_bounds = nullptr;    // device copy, d_row + 1
@@ -89,6 +91,7 @@ struct dpaps_ps {
     int opt_waves = 16;
     int opt_profile = 0;
     int opt_push_sequential = 0;      // 1: ps_push adds each key's terms strictly one after the other
+    int opt_team_max = 5;             // most wavefronts that share one heavy run
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
     // event pairs around the SGD kernel launches (only while profiling is on)
@@ -130,7 +133,8 @@ struct SgdArgs {
     const int64_t *run_gptr; const int32_t *gstart;
     int32_t sweep;              // 0: every run is processed as a heavy run
     int32_t heavy_waves;        // wavefronts that take heavy runs (each has a staging area in LDS)
-    int32_t team;               // wavefronts that share one heavy run
+    int32_t team;               // 2: the heavy wavefronts follow team_plan; 1: one wavefront per heavy run, in turn
+    const uint32_t *team_plan;  // 16 words per block (see k_team_plan)
     // the localize step of the subepoch, done by the same workgroup first (grouped kernel only)
     int32_t fuse_localize; int32_t W; int64_t per_home; int32_t *owner_w;
     int32_t ctick_cap;          // column ticket counters in LDS

@@ -173,7 +173,7 @@ void dpaps_mf_free(dpaps_ps *ps) {
     MfData &f = ps->mf;
     void *ptrs[] = {f.row, f.val, f.info, f.col, f.run_start, f.run_col, f.blk_run_ptr, f.multi_row, f.blk_multi_ptr,
                     f.row_bounds, f.col_bounds, f.blk_nheavy, f.t_cinfo, f.t_val, f.trun_start, f.trun_row, f.trun_wait,
-                    f.blk_trun_ptr, f.run_gptr, f.gstart};
+                    f.blk_trun_ptr, f.run_gptr, f.gstart, f.team_plan};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     ps->mf = MfData();
 }

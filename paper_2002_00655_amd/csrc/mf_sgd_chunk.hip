@@ -147,18 +147,17 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     // and handed from group to group through a counter; the loads, the products <w_s, w_t> before it and
     // the new rows w_s after it overlap with the other wavefront's turn.
     if (wave < hwaves) {
-        // The longest runs are what everything else ends up waiting for.  With 14 heavy wavefronts (of 16):
-        // teams of three for the first two runs, teams of two for the next two, one wavefront each for the
-        // following four.  With 12 (of 12 to 15): teams of three, three and two, and four single wavefronts
-        // that take the remaining runs in turn.  With fewer: one wavefront per run, taking runs in turn.
-        int T = 1, mb = 0, run_first = wave, run_step = hwaves;
+        // The longest runs are what everything else ends up waiting for.  With 12 or more heavy wavefronts each
+        // follows the block's plan: a team of T wavefronts on one long run (this one takes its groups mb, mb + T,
+        // ...), or one wavefront that takes several short runs one after the other.  With fewer: one wavefront
+        // per run, taking runs in turn.
+        int T = 1, mb = 0, run_first = wave, run_last = nheavy, run_step = hwaves;
         if (a.team == 2) {
-            const int pairs_end = hwaves == 14 ? 10 : 8;       // wavefronts 6 .. pairs_end-1 work in pairs
-            if (wave < 6) { T = 3; mb = wave % 3; run_first = wave / 3; run_step = DPAPS_HEAVY_MAX; }
-            else if (wave < pairs_end) { T = 2; mb = (wave - 6) & 1; run_first = 2 + ((wave - 6) >> 1); run_step = DPAPS_HEAVY_MAX; }
-            else { run_first = 2 + ((pairs_end - 6) >> 1) + (wave - pairs_end); run_step = hwaves - pairs_end; }
+            const uint32_t pl = a.team_plan[b * 16 + wave];
+            run_first = (int)(pl & 0xFFu); run_last = (int)((pl >> 8) & 0xFFu); T = (int)((pl >> 16) & 0xFFu); mb = (int)(pl >> 24);
+            run_step = 1;
         }
-        for (int run = run_first; run < nheavy; run += run_step) {
+        for (int run = run_first; run < run_last; run += run_step) {
             const int64_t g = run0 + run;
             const int64_t s0 = a.run_start[g], s1 = a.run_start[g + 1];
             const uint32_t hoff = (uint32_t)((a.run_col[g] - blk_c0) * L * 4);   // the column's row inside the column buffer
@@ -166,7 +165,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
             const int ng = (int)(a.run_gptr[g + 1] - gb) - 1;                   // groups of this run
             float *hsh = hshare + run * 16 * NT;
             uint32_t *hsq = &hseq[run];
-            if (run < 2) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(2);
+            __builtin_amdgcn_s_setprio(2);
             // where the groups start: 64 table entries, one per lane, from group gw on
             int gw = 0;
             int gs_win = a.gstart[gb + (lane <= ng ? lane : ng)];
@@ -257,7 +256,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                             break;
                         }
                     }
-                    if (run < 2) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(2);
+                    __builtin_amdgcn_s_setprio(2);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                     gather(n16, hi);                      // same group, rows as they are now
                     // waited for here, on the rare path, so that where the paths join the common one is not
@@ -279,13 +278,6 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                         *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = x;
                     }
                 }
-                // read ahead: the rows of this wavefront's next group, the per-entry data of the one after
-                {
-                    const int p1 = gs(gi + T), p2 = gs(gi + T + 1);
-                    plan(p2 - p1, n16, hi);
-                    meta_load(s0 + gs(gi + 2 * T));
-                }
-
                 // ---- <w_s, w_t>: G = X X^T (row 15 of X is an old copy of h here; its products are not used)
                 f32x4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gm2 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
@@ -304,6 +296,12 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
 #pragma unroll
                 for (int t = 0; t < CH; ++t) gl[t] = lr * bperm_f(gm[t & 3], 16 * (t >> 2) + n16);
 
+                // this lane's quarter of row n16, for the inner products with h below: fetched before the wait
+                f32x4 xr[NT];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) xr[j] = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
+                __builtin_amdgcn_sched_barrier(0);
+
                 // ---- the part that needs h as the previous group left it --------------------------------
                 for (uint32_t spins = 0; ticket_read(hsq) != (uint32_t)gi;) {
                     __builtin_amdgcn_s_sleep(1);
@@ -314,6 +312,8 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     }
                 }
                 compiler_fence();
+                // from here to the hand-over every other wavefront of the team waits for this one
+                __builtin_amdgcn_s_setprio(3);
                 // h as it is now, lane l its components l, l + 64 (lanes past the row's 16 NT floats: any)
                 float ho[NV];
                 int ck[NV];
@@ -327,21 +327,30 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
                     const f32x4 hq = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
-                    const f32x4 xr = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xr[q], hq[q], pq[q]);
+                    for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xr[j][q], hq[q], pq[q]);
                 }
+                // the rows' components for the new h further down: asked for now, so that they arrive while the
+                // errors are being computed
+                float wv[CH][NV];
+#pragma unroll
+                for (int s = 0; s < CH; ++s)
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) wv[s][cc] = stg[s * RS + ck[cc]];
+                __builtin_amdgcn_sched_barrier(0);
                 float p = (pq[0] + pq[1]) + (pq[2] + pq[3]);
                 p = p + bperm_f(p, ln ^ 16);
                 p = p + bperm_f(p, ln ^ 32);
                 // The errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t].  Steps past the group's end work on
                 // rows of X that are zero and on values that are finite, so what they compute changes nothing
                 // that is used; they are not skipped, to keep the chain free of branches.
-                float e_vec = 0.0f;                        // e_t in every lane with n16 == t
+                float e_vec = 0.0f;                        // e_t in lane t (lanes 0 .. 14)
 #pragma unroll
                 for (int t = 0; t < CH; ++t) {
                     const float e = rl_f(c_val - p, t);    // lane t holds v_t and p_t
-                    e_vec = n16 == t ? e : e_vec;
+                    // into lane t of e_vec (the wait states a lane write needs after the lane read that produced
+                    // its scalar operand are spelled out, since the compiler does not look inside)
+                    __asm__ volatile("s_nop 3\n\tv_writelane_b32 %0, %1, %2" : "+v"(e_vec) : "s"(e), "n"(t));
                     p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p));
                 }
                 // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s
@@ -355,7 +364,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     for (int s = 0; s < CH; ++s) {
                         const float as = rl_f(a_vec, s);
 #pragma unroll
-                        for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(as, stg[s * RS + ck[cc]], hn[cc]);
+                        for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(as, wv[s][cc], hn[cc]);
                     }
 #pragma unroll
                     for (int cc = 0; cc < NV; ++cc) {
@@ -366,6 +375,14 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     }
                     compiler_fence();
                     ticket_write(hsq, (uint32_t)gi + 1u);
+                    __builtin_amdgcn_s_setprio(2);
+                }
+                // read ahead: the rows of this wavefront's next group, the per-entry data of the one after (not
+                // earlier: the registers they arrive in are needed by the part above)
+                {
+                    const int p1 = gs(gi + T), p2 = gs(gi + T + 1);
+                    plan(p2 - p1, n16, hi);
+                    meta_load(s0 + gs(gi + 2 * T));
                 }
                 // this wavefront's copy of h as it was (row 15 of X), for the new rows below
 #pragma unroll
@@ -383,6 +400,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     dst[v] = s < k ? (uint32_t)((r - (int)blk_r0) * L + n16) * 4u : wspan;
                 }
                 float ca[4];                               // (C - I)[t = n16][s = 4 hi + v]; row 15 is not needed any more
+                const float e_t = bperm_f(e_vec, n16);     // e of this lane's row t = n16 (lane 15: zero)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int s = 4 * hi + v;
@@ -392,9 +410,9 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     const int t = n16, pw = s == 15 ? t : t - 1 - s;
                     const float cp = cpow[pw > 0 ? pw : 0];
                     float x = 0.0f;
-                    if (s < t) x = (lr * e_vec) * (lr * es) * cp;
+                    if (s < t) x = (lr * e_t) * (lr * es) * cp;
                     if (s == t) x = -delta;
-                    if (s == 15) x = lr * e_vec * cp;
+                    if (s == 15) x = lr * e_t * cp;
                     ca[v] = t < 15 ? x : 0.0f;
                 }
 #pragma unroll
@@ -599,9 +617,6 @@ static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStr
     }
     if (!f.sweep_ok) { ps->last_error = "the grouped SGD kernel needs rows in ascending order inside the short column runs"; return PS_ELAYOUT; }
     a.sweep = 1;
-    // with 12 or more wavefronts, 12 of them take heavy runs (see the kernel); else at most one per heavy run
-    a.team = waves >= 12 ? 2 : 1;
-    a.heavy_waves = waves >= 16 ? 14 : (waves >= 12 ? 12 : (waves < DPAPS_HEAVY_MAX ? waves : DPAPS_HEAVY_MAX));
     a.ctick_cap = f.max_tail_cols > 1 ? f.max_tail_cols : 1;
     // LDS plan: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters, then as
     // many other column factors as fit
@@ -630,7 +645,54 @@ static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStrea
     return waves <= 12 ? launch_chunk_t<NT, A4, 768>(ps, a, ntasks, waves, st) : launch_chunk_t<NT, A4, 1024>(ps, a, ntasks, waves, st);
 }
 
-int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st) {
+// The plan of a block: word w of its 16 = run_first | run_last << 8 | T << 16 | mb << 24 for heavy wavefront w
+// (T = 0, no runs: the wavefront goes straight to the second part).  Every heavy run gets a wavefront of its
+// own, so that all runs advance side by side (the last groups of consecutive runs tend to wait for each
+// other, and a run that started late would make everything after it late).  The wavefronts that are left
+// join the runs one by one, each time the run with the most groups per wavefront, up to tmax per run.
+__global__ void k_team_plan(const int64_t *blk_run_ptr, const int32_t *blk_nheavy, const int64_t *run_gptr, int64_t nb, int H, int tmax,
+                            uint32_t *plan) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= nb) return;
+    const int64_t run0 = blk_run_ptr[b];
+    int nh = blk_nheavy[b] < DPAPS_HEAVY_MAX ? blk_nheavy[b] : DPAPS_HEAVY_MAX;
+    if (nh > H) nh = H;
+    int g[DPAPS_HEAVY_MAX], T[DPAPS_HEAVY_MAX];
+    for (int i = 0; i < nh; ++i) {
+        g[i] = (int)(run_gptr[run0 + i + 1] - run_gptr[run0 + i]) - 1;
+        T[i] = 1;
+    }
+    for (int left = H - nh; left > 0 && nh > 0; --left) {
+        int best = -1;
+        for (int i = 0; i < nh; ++i)
+            if (T[i] < tmax && g[i] > T[i] && (best < 0 || (int64_t)g[i] * T[best] > (int64_t)g[best] * T[i])) best = i;
+        if (best < 0) break;
+        ++T[best];
+    }
+    int w = 0;
+    for (int i = 0; i < nh; ++i)
+        for (int q = 0; q < T[i]; ++q, ++w) plan[b * 16 + w] = (uint32_t)i | (uint32_t)(i + 1) << 8 | (uint32_t)T[i] << 16 | (uint32_t)q << 24;
+    for (; w < 16; ++w) plan[b * 16 + w] = 0;
+}
+
+int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a_in, int ntasks, int waves, hipStream_t st) {
+    SgdArgs a = a_in;
+    // with 12 or more wavefronts, 12 (14 of 16) of them take heavy runs as the block's plan says; else at most
+    // one per heavy run
+    a.team = waves >= 12 ? 2 : 1;
+    a.heavy_waves = waves >= 16 ? 14 : (waves >= 12 ? 12 : (waves < DPAPS_HEAVY_MAX ? waves : DPAPS_HEAVY_MAX));
+    a.team_plan = nullptr;
+    if (a.team == 2) {
+        MfData &f = ps->mf;
+        if (!f.team_plan) PS_HIP(ps, hipMalloc(&f.team_plan, (size_t)f.num_blocks * 16 * sizeof(uint32_t)));
+        if (f.team_plan_waves != a.heavy_waves * 100 + ps->opt_team_max) {
+            k_team_plan<<<(unsigned)((f.num_blocks + 255) / 256), 256, 0, st>>>(f.blk_run_ptr, f.blk_nheavy, f.run_gptr, f.num_blocks, a.heavy_waves,
+                                                                               ps->opt_team_max, f.team_plan);
+            PS_HIP(ps, hipGetLastError());
+            f.team_plan_waves = a.heavy_waves * 100 + ps->opt_team_max;
+        }
+        a.team_plan = f.team_plan;
+    }
     switch ((a.L + 15) / 16) {
     case 1: return a.L % 4 == 0 ? launch_chunk<1, true>(ps, a, ntasks, waves, st) : launch_chunk<1, false>(ps, a, ntasks, waves, st);
     case 2: return a.L % 4 == 0 ? launch_chunk<2, true>(ps, a, ntasks, waves, st) : launch_chunk<2, false>(ps, a, ntasks, waves, st);
