@@ -189,12 +189,16 @@ int mf_profile_read(ps_handle ps, double *sgd_ms_host_out, int64_t *launches_hos
  * object by neg_obj[b * n_neg_obj + j] (device; the paper perturbs both, 10 times).  The step pulls every key
  * occurrence (values as they are before the step), computes for every scored triple - label +1 for the positive,
  * -1 for a negative - score = Re sum_k e_s[k] w_r[k] conj(e_o[k]), loss = log(1 + exp(-label score)), its gradient g
- * for the 2 dim numbers of each of the three keys, and pushes per occurrence dtheta = -lr g / sqrt(G + g^2 + eps)
- * and dG = g^2 (G: the pulled accumulator) as cumulative updates, in the order (triple of the batch; positive,
- * subject negatives, object negatives; subject, relation, object), which fixes the result bit for bit.
+ * for the 2 dim numbers of each of the three keys, and per occurrence dtheta = -lr g / sqrt(G + g^2 + eps) and
+ * dG = g^2 (G: the pulled accumulator).  These are cumulative updates.  The terms one positive triple and its
+ * negatives have for the same key slot (its subject: 1 + n_neg_obj terms, its relation: all, its object:
+ * 1 + n_neg_subj) are added up in the order of their occurrences, and the batch then pushes 3 + n_neg_subj +
+ * n_neg_obj rows per positive triple, in the order (triple of the batch; subject, relation, object, subject
+ * negatives, object negatives) with ps_push's rule for repeated keys: the result depends on the arguments only.
+ * Pull and push statistics count every key occurrence (3 per scored triple), as separate calls would.
  * worker: as for ps_pull / ps_push (locality statistics).  loss_host_out (may be NULL): sum of the losses of all
- * scored triples; asking for it synchronizes the stream.  dim <= 256.  Scratch is allocated by the library and
- * grows with the batch (3 * batch * (1 + n_neg_subj + n_neg_obj) rows). */
+ * scored triples; asking for it synchronizes the stream.  dim <= 256, 1 + n_neg_subj + n_neg_obj <= 64
+ * (PS_ELIMIT).  Scratch is allocated by the library and grows with the batch. */
 int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, int32_t dim, int64_t batch, const int32_t *subj,
                  const int32_t *rel, const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj, int32_t n_neg_obj,
                  const int32_t *neg_obj, float lr, float eps, double *loss_host_out, void *stream);

@@ -147,6 +147,12 @@ struct SgdArgs {
 // mf_sgd_chunk.hip: the kernel that processes a column's entries in groups (see there)
 int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st);
 
+// ps_store.hip: the two halves of ps_pull and ps_push, for steps that read the store where they use the values
+// and add up the update terms of one data point before they push them
+int dpaps_account_pull(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);
+int dpaps_account_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);
+int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *deltas, hipStream_t st);
+
 int dpaps_fail_hip(dpaps_ps *ps, hipError_t e, const char *what);
 int dpaps_ws_reserve(dpaps_ps *ps, size_t bytes);
 

