@@ -251,7 +251,7 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     double *loss = (double *)((char *)ps->kge_ws + off_loss);
     k_kge_keys<<<grid_for(ntr, 256), 256, 0, st>>>(num_entities, batch, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, keys);
     PS_HIP(ps, hipGetLastError());
-    int rc = dpaps_account_pull(ps, worker, keys, nocc, st);
+    int rc = dpaps_account_pull_push(ps, worker, keys, nocc, st);       // every occurrence is pulled, and pushed below
     if (rc) return rc;
     const unsigned blocks = grid_for(batch * 64, 256);
 #define KGE_GROUP(NC) k_kge_group<NC><<<blocks, 256, 0, st>>>(batch, num_entities, dim, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, \
@@ -264,8 +264,6 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     }
 #undef KGE_GROUP
     PS_HIP(ps, hipGetLastError());
-    rc = dpaps_account_push(ps, worker, keys, nocc, st);
-    if (rc) return rc;
     rc = dpaps_push_apply(ps, ukeys, rows, upd, st);
     if (rc) return rc;
     if (loss_host_out) {

@@ -126,7 +126,8 @@ __device__ __forceinline__ void route_lds_flush(RouteLds &l, u64 *stats, int w0,
 // Locality statistics and message counts of one pull or push call.
 __global__ __launch_bounds__(256) void k_route_access(const int64_t *keys, int64_t n, int32_t worker, const int32_t *owner, int64_t per_home,
                                                        int32_t W, uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id,
-                                                       u64 *stats, int stat_local, int stat_remote, const int32_t *err) {
+                                                       u64 *stats, int stat_local, int stat_remote, int stat_local2, int stat_remote2,
+                                                       const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
     __shared__ RouteLds l;
     route_lds_init(l);
@@ -142,6 +143,9 @@ __global__ __launch_bounds__(256) void k_route_access(const int64_t *keys, int64
         route_key(remote, worker, (int32_t)(k / per_home), o, W, stamp_h, stamp_o, stamp_pair, call_id, l);
     }
     route_lds_flush(l, stats, stat_local, stat_remote, PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY);
+    // a second access to the same keys by the same worker right after (a pull and a push of one step) has the
+    // same locality and sends the same messages once more
+    if (stat_local2 >= 0) route_lds_flush(l, stats, stat_local2, stat_remote2, PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY);
 }
 
 // localize: the home node updates the location at once (Sec. 3.2, step 1); the
@@ -413,12 +417,12 @@ static uint32_t next_call_id(dpaps_ps *ps, hipStream_t st) {
 }
 
 static int route_access(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, int st_local, int st_remote,
-                        hipStream_t st) {
+                        hipStream_t st, int st_local2 = -1, int st_remote2 = -1) {
     if (worker < 0 || n == 0) return PS_OK;
     uint32_t id = next_call_id(ps, st);
     k_route_access<<<route_grid(ps, n), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
                                                      ps->stamp_o, ps->stamp_pair, id, ps->stats, st_local, st_remote,
-                                                     ps->err);
+                                                     st_local2, st_remote2, ps->err);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
 }
@@ -456,6 +460,13 @@ int dpaps_account_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_
     int rc = launch_check(ps, keys, n, st);
     if (rc) return rc;
     return route_access(ps, worker, keys, n, PS_STAT_PUSH_LOCAL, PS_STAT_PUSH_REMOTE, st);
+}
+
+// a pull and a push of the same keys by the same worker with nothing in between that moves a key, counted in one pass
+int dpaps_account_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st) {
+    int rc = launch_check(ps, keys, n, st);
+    if (rc) return rc;
+    return route_access(ps, worker, keys, n, PS_STAT_PULL_LOCAL, PS_STAT_PULL_REMOTE, st, PS_STAT_PUSH_LOCAL, PS_STAT_PUSH_REMOTE);
 }
 
 // the adding itself, for keys that have been checked (the kernels do nothing once the error flag is set)
