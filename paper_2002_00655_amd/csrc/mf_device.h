@@ -24,6 +24,27 @@ __device__ __forceinline__ float wave_sum(float x) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
+// x of lane T of the same row of 16 lanes, in every lane (row_newbcast)
+template <int T>
+__device__ __forceinline__ float row_bcast_lane(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + T, 0xF, 0xF, true));
+}
+
+// x[l] + x[l ^ 32] in every lane: the swap leaves the lower half of x in both halves of one result and the upper
+// half in both halves of the other.  (Element by element into scalars: a bit cast applied to a vector element
+// directly has been seen to pick element 0.)
+__device__ __forceinline__ float add_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const unsigned lo = r[0], hi = r[1];
+    return __uint_as_float(lo) + __uint_as_float(hi);
+}
+// x[l] + x[l ^ 16] in every lane, likewise with the swap of the odd and even rows of 16 lanes
+__device__ __forceinline__ float add_across_row_pairs(float x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const unsigned even = r[0], odd = r[1];
+    return __uint_as_float(even) + __uint_as_float(odd);
+}
+
 __device__ __forceinline__ int rl_i(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
 __device__ __forceinline__ float rl_f(float v, int lane) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));

@@ -296,6 +296,11 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
 #pragma unroll
                 for (int t = 0; t < CH; ++t) gl[t] = lr * bperm_f(gm[t & 3], 16 * (t >> 2) + n16);
 
+                // v_t of the lane's row t = n16 in all four rows of 16 lanes (the per-entry data sits in lanes 0 .. 14)
+                const float v_row = bperm_f(c_val, n16);
+                // table entries for the new h, read before the wait as well
+                const int pw_h = k - 1 - n16;
+                const float cpow_h = cpow[pw_h > 0 ? pw_h : 0], cpm1_k = cpm1[k];
                 // this lane's quarter of row n16, for the inner products with h below: fetched before the wait
                 f32x4 xr[NT];
 #pragma unroll
@@ -323,12 +328,15 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     ho[cc] = hsh[ck[cc]];
                 }
                 // p_s = <w_s, h>: every lane its quarter of row n16 (four partial sums), then the four quarters together
+                f32x4 hq[NT];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) hq[j] = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
+                __builtin_amdgcn_sched_barrier(0);      // all of h asked for before the first product waits for its piece
                 float pq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
-                    const f32x4 hq = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xr[j][q], hq[q], pq[q]);
+                    for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xr[j][q], hq[j][q], pq[q]);
                 }
                 // the rows' components for the new h further down: asked for now, so that they arrive while the
                 // errors are being computed
@@ -339,27 +347,33 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     for (int cc = 0; cc < NV; ++cc) wv[s][cc] = stg[s * RS + ck[cc]];
                 __builtin_amdgcn_sched_barrier(0);
                 float p = (pq[0] + pq[1]) + (pq[2] + pq[3]);
-                p = p + bperm_f(p, ln ^ 16);
-                p = p + bperm_f(p, ln ^ 32);
-                // The errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t].  Steps past the group's end work on
-                // rows of X that are zero and on values that are finite, so what they compute changes nothing
-                // that is used; they are not skipped, to keep the chain free of branches.
-                float e_vec = 0.0f;                        // e_t in lane t (lanes 0 .. 14)
-#pragma unroll
-                for (int t = 0; t < CH; ++t) {
-                    const float e = rl_f(c_val - p, t);    // lane t holds v_t and p_t
-                    // into lane t of e_vec (the wait states a lane write needs after the lane read that produced
-                    // its scalar operand are spelled out, since the compiler does not look inside)
-                    __asm__ volatile("s_nop 3\n\tv_writelane_b32 %0, %1, %2" : "+v"(e_vec) : "s"(e), "n"(t));
-                    p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p));
+                // the four quarters of a row sit in the same lane of the four rows of 16 lanes: two lane swaps in
+                // the vector unit add them up and leave the sum in all four
+                p = add_across_halves(p);
+                p = add_across_row_pairs(p);
+                // The errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t].  Lane (t, any hi) holds v_t (v_row) and p_t, and
+                // e_t reaches the other lanes of its row of 16 by a broadcast inside the vector unit.  Steps past
+                // the group's end work on rows of X that are zero and on values that are finite, so what they
+                // compute changes nothing that is used; they are not skipped, to keep the chain free of branches.
+                float e_vec = 0.0f;                        // e_t in every lane with n16 == t
+#define DPAPS_REC_STEP(t)                                                       \
+                {                                                               \
+                    const float d = v_row - p;                                  \
+                    const float e = row_bcast_lane<t>(d);                       \
+                    e_vec = n16 == t ? d : e_vec;                               \
+                    p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p)); \
                 }
+                DPAPS_REC_STEP(0) DPAPS_REC_STEP(1) DPAPS_REC_STEP(2) DPAPS_REC_STEP(3) DPAPS_REC_STEP(4)
+                DPAPS_REC_STEP(5) DPAPS_REC_STEP(6) DPAPS_REC_STEP(7) DPAPS_REC_STEP(8) DPAPS_REC_STEP(9)
+                DPAPS_REC_STEP(10) DPAPS_REC_STEP(11) DPAPS_REC_STEP(12) DPAPS_REC_STEP(13) DPAPS_REC_STEP(14)
+#undef DPAPS_REC_STEP
+                static_assert(CH == 15, "the recurrence above is written out for 15 entries");
                 // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s
                 {
-                    const int pw = k - 1 - n16;
-                    const float a_vec = (n16 < k ? lr * e_vec : 0.0f) * cpow[pw > 0 ? pw : 0];   // lane s < 15: coefficient of w_s
+                    const float a_vec = (n16 < k ? lr * e_vec : 0.0f) * cpow_h;   // lane s < 15: coefficient of w_s
                     float hn[NV];
 #pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(cpm1[k], ho[cc], ho[cc]);
+                    for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(cpm1_k, ho[cc], ho[cc]);
 #pragma unroll
                     for (int s = 0; s < CH; ++s) {
                         const float as = rl_f(a_vec, s);
@@ -400,7 +414,6 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     dst[v] = s < k ? (uint32_t)((r - (int)blk_r0) * L + n16) * 4u : wspan;
                 }
                 float ca[4];                               // (C - I)[t = n16][s = 4 hi + v]; row 15 is not needed any more
-                const float e_t = bperm_f(e_vec, n16);     // e of this lane's row t = n16 (lane 15: zero)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int s = 4 * hi + v;
@@ -410,9 +423,9 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     const int t = n16, pw = s == 15 ? t : t - 1 - s;
                     const float cp = cpow[pw > 0 ? pw : 0];
                     float x = 0.0f;
-                    if (s < t) x = (lr * e_t) * (lr * es) * cp;
+                    if (s < t) x = (lr * e_vec) * (lr * es) * cp;
                     if (s == t) x = -delta;
-                    if (s == 15) x = lr * e_t * cp;
+                    if (s == 15) x = lr * e_vec * cp;
                     ca[v] = t < 15 ? x : 0.0f;
                 }
 #pragma unroll
