@@ -262,10 +262,10 @@ int orc_mf_block_ratings(int64_t m, int64_t n, int64_t nnz, const int32_t *rows,
  * processes its entries one by one with pull / SGD step / push, then all
  * workers meet at a barrier (Appendix A).  Within a subepoch every access must
  * be local (Sec. 4.1); anything else is reported as ORC_EREMOTE. */
-int orc_mf_sgd_epoch(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, const int32_t *cols, const float *vals,
-                     int32_t d_row, int32_t d_col, const int64_t *row_bounds, const int64_t *col_bounds,
-                     const int64_t *block_ptr, const int32_t *tasks, const int32_t *stratum_ptr,
-                     int32_t num_strata, double lr_in, double lambda_in) {
+static int mf_epoch(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, const int32_t *cols, const float *vals,
+                    int32_t d_row, int32_t d_col, const int64_t *row_bounds, const int64_t *col_bounds,
+                    const int64_t *block_ptr, const int32_t *tasks, const int32_t *stratum_ptr,
+                    int32_t num_strata, double lr_in, double lambda_in, int relocate) {
     if (!ps || m + n != ps->K || num_strata < 0) return ORC_EINVAL;
     const int32_t L = ps->L;
     const REAL lr = (REAL)lr_in, lambda = (REAL)lambda_in;
@@ -286,7 +286,7 @@ int orc_mf_sgd_epoch(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, cons
             used[w] = used[ps->W + rb] = used[ps->W + d_row + cb] = 1;
         }
         if (rc) break;
-        for (int32_t t = t0; t < t1; ++t) {             /* relocate the blocks */
+        for (int32_t t = t0; relocate && t < t1; ++t) { /* relocate the blocks */
             int32_t w = tasks[3 * t], rb = tasks[3 * t + 1], cb = tasks[3 * t + 2];
             int64_t nr = row_bounds[rb + 1] - row_bounds[rb], nc = col_bounds[cb + 1] - col_bounds[cb];
             int64_t *keys = (int64_t *)malloc((size_t)(nr + nc + 1) * sizeof(int64_t));
@@ -316,11 +316,31 @@ int orc_mf_sgd_epoch(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, cons
                 rc = orc_ps_push(ps, w, keys, 2, dwh); if (rc) break;
             }
         }
-        if (rc == ORC_OK && ps->stats[ST_PULL_REMOTE] + ps->stats[ST_PUSH_REMOTE] != remote_before) rc = ORC_EREMOTE;
+        if (relocate && rc == ORC_OK && ps->stats[ST_PULL_REMOTE] + ps->stats[ST_PUSH_REMOTE] != remote_before) rc = ORC_EREMOTE;
         /* barrier: nothing to do in a sequential program */
     }
     free(buf); free(used);
     return rc;
+}
+
+int orc_mf_sgd_epoch(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, const int32_t *cols, const float *vals,
+                     int32_t d_row, int32_t d_col, const int64_t *row_bounds, const int64_t *col_bounds,
+                     const int64_t *block_ptr, const int32_t *tasks, const int32_t *stratum_ptr,
+                     int32_t num_strata, double lr_in, double lambda_in) {
+    return mf_epoch(ps, m, n, rows, cols, vals, d_row, d_col, row_bounds, col_bounds, block_ptr, tasks, stratum_ptr,
+                    num_strata, lr_in, lambda_in, 1);
+}
+
+/* The same epoch on a classic parameter server (Sec. 2.1 "Basic PS Architectures": parameters are allocated
+ * statically; Sec. 4.2, Sec. 4.6): nothing is relocated, every entry's pull and push goes to wherever the two
+ * keys live and is counted as local or remote, with its messages.  The values come out the same (Sec. 2.3:
+ * location transparency). */
+int orc_mf_sgd_epoch_classic(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, const int32_t *cols, const float *vals,
+                             int32_t d_row, int32_t d_col, const int64_t *row_bounds, const int64_t *col_bounds,
+                             const int64_t *block_ptr, const int32_t *tasks, const int32_t *stratum_ptr,
+                             int32_t num_strata, double lr_in, double lambda_in) {
+    return mf_epoch(ps, m, n, rows, cols, vals, d_row, d_col, row_bounds, col_bounds, block_ptr, tasks, stratum_ptr,
+                    num_strata, lr_in, lambda_in, 0);
 }
 
 /* sum over the revealed entries of (v - <w_i, h_j>)^2, accumulated in double */

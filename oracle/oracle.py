@@ -120,8 +120,9 @@ class Oracle:
         return dict(zip(STAT_NAMES, (int(x) for x in out)))
 
     # -- matrix factorization -----------------------------------------------
-    def mf_sgd_epoch(self, m, n, rows, cols, vals, row_bounds, col_bounds, block_ptr, schedule, lr, lam) -> None:
-        """schedule: int32 [S, T, 3] array or list of [T_s, 3] arrays of (worker, row block, col block)."""
+    def mf_sgd_epoch(self, m, n, rows, cols, vals, row_bounds, col_bounds, block_ptr, schedule, lr, lam, classic=False) -> None:
+        """schedule: int32 [S, T, 3] array or list of [T_s, 3] arrays of (worker, row block, col block).
+        classic: nothing is relocated, every access goes to wherever the key lives (a classic parameter server)."""
         strata = [np.ascontiguousarray(s, dtype=np.int32).reshape(-1, 3) for s in schedule]
         tasks = np.concatenate(strata) if strata else np.zeros((0, 3), np.int32)
         sptr = np.concatenate([[0], np.cumsum([s.shape[0] for s in strata])]).astype(np.int32)
@@ -132,7 +133,7 @@ class Oracle:
         rows = np.ascontiguousarray(rows, dtype=np.int32)
         cols = np.ascontiguousarray(cols, dtype=np.int32)
         vals = np.ascontiguousarray(vals, dtype=np.float32)
-        rc = self.lib.orc_mf_sgd_epoch(
+        rc = (self.lib.orc_mf_sgd_epoch_classic if classic else self.lib.orc_mf_sgd_epoch)(
             C.c_void_p(self.h), C.c_int64(m), C.c_int64(n), _p(rows, C.c_int32), _p(cols, C.c_int32), _p(vals, C.c_float),
             C.c_int32(rb.size - 1), C.c_int32(cb.size - 1), _p(rb, C.c_int64), _p(cb, C.c_int64), _p(bp, C.c_int64),
             _p(tasks, C.c_int32), _p(sptr, C.c_int32), C.c_int32(len(strata)),
