@@ -41,7 +41,7 @@ def kernel_sources_hash():
 
 
 def measured_traffic(args):
-    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0)
+    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0 or args.classic > 0)
     if kernel_sources_hash() == TRAFFIC["kernel_sha256_16"] and key == TRAFFIC["workload"]:
         return TRAFFIC["bytes_per_launch"]
     return None     # the kernel (or the workload) is not the one the counters were taken with
@@ -174,6 +174,8 @@ def main() -> int:
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
     ap.add_argument("--team-max", type=int, default=0, help="most wavefronts per long column run (0: library default)")
+    ap.add_argument("--classic", type=int, default=0, choices=[0, 1, 2],
+                    help="the epoch as on a classic parameter server (1: values copied out and back, 2: updated in place)")
     ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -231,7 +233,9 @@ def main() -> int:
         srv.set_option(P.OPT_MF_TEAM_MAX, args.team_max)
     if args.entry_kernel:
         srv.set_option(P.OPT_MF_GROUPED, 0)
-    kernel_name = "k_mf_sgd" if (args.entry_kernel or w.rank > 128) else "k_mf_sgd_chunk"
+    if args.classic:
+        srv.set_option(P.OPT_MF_CLASSIC, args.classic)
+    kernel_name = "k_mf_sgd_classic" if args.classic else ("k_mf_sgd" if (args.entry_kernel or w.rank > 128) else "k_mf_sgd_chunk")
     srv.push(torch.arange(w.m, device=dev), torch.from_numpy(w.W0).to(dev))
     srv.push(w.m + torch.arange(w.n, device=dev), torch.from_numpy(w.H0).to(dev))
     t0 = time.perf_counter()

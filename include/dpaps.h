@@ -81,8 +81,15 @@ enum {
     PS_OPT_PUSH_SEQUENTIAL = 7, /* 1: ps_push adds the update terms of a key strictly one after the other in argument
                                    order, however many there are (one wavefront per key; for bit-for-bit checks
                                    against a sequential server).  0 (default): see ps_push */
-    PS_OPT_MF_TEAM_MAX = 8      /* grouped SGD kernel: the most wavefronts that take the groups of one long column run
+    PS_OPT_MF_TEAM_MAX = 8,     /* grouped SGD kernel: the most wavefronts that take the groups of one long column run
                                    in turn, 1..14 (default 5) */
+    PS_OPT_MF_CLASSIC = 9       /* mf_sgd_epoch as on a classic parameter server (Sec. 2.1, Sec. 4.2, Sec. 4.6): no
+                                   relocation, no residency - every entry pulls its two keys from the store and
+                                   pushes the update terms back, counted as local or remote by the owner map as it
+                                   stands, with the messages.  1: the push reads the stored values again (values
+                                   are copied out of and back into the server); 2: the rows are updated in place.
+                                   0 (default): dynamic parameter allocation.  The values are the same in all
+                                   three; honours PS_OPT_MF_EXACT.  A comparison mode: one wavefront per task */
 };
 
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */

@@ -91,6 +91,7 @@ struct dpaps_ps {
     int opt_waves = 16;
     int opt_profile = 0;
     int opt_push_sequential = 0;      // 1: ps_push adds each key's terms strictly one after the other
+    int opt_classic = 0;              // 1, 2: mf_sgd_epoch as on a classic parameter server (2: updates in place)
     int opt_team_max = 5;             // most wavefronts that share one heavy run
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups

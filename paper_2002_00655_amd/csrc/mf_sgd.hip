@@ -353,6 +353,113 @@ static int launch_sgd(dpaps_ps *ps, const SgdArgs &a, int ntasks, int threads, s
     return PS_OK;
 }
 
+// ---------------------------------------------------------------------------
+// The epoch on a classic parameter server (Sec. 2.1: static allocation; the variants compared in Sec. 4.2 and
+// Sec. 4.6): nothing is relocated and nothing stays with the worker.  One wavefront per task walks its block in
+// stored order; every entry is a pull of its two keys from the store, the step, and a push that reads the
+// stored values again and adds the update terms (in_place = 1: the worker updates the two rows where they are,
+// without the second read - "working directly on the data store", Sec. 4.4).  Every access is counted as
+// local or remote by the owner map as it stands, with the messages a remote one costs (request to the home
+// node, forward if the key lives elsewhere, reply; the two keys of a call share messages to one destination,
+// Sec. 3.7).
+// ---------------------------------------------------------------------------
+struct ClassicArgs {
+    const int32_t *tasks;
+    float *val; const int32_t *owner;
+    const int32_t *e_row, *e_col; const float *e_val;
+    const int64_t *run_start, *blk_run_ptr;
+    int64_t m, per_home;
+    int32_t L, d_col, in_place;
+    float lr, lambda;
+    u64 *stats; int32_t *err;
+};
+
+template <int NV, bool EXACT>
+__global__ __launch_bounds__(64) void k_mf_sgd_classic(ClassicArgs a) {
+    if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    const int lane = threadIdx.x;
+    const int32_t worker = a.tasks[3 * blockIdx.x], rb = a.tasks[3 * blockIdx.x + 1], cb = a.tasks[3 * blockIdx.x + 2];
+    const int64_t b = (int64_t)rb * a.d_col + cb;
+    const int64_t p0 = a.run_start[a.blk_run_ptr[b]], p1 = a.run_start[a.blk_run_ptr[b + 1]];
+    const int L = a.L;
+    const float lr = a.lr, lambda = a.lambda;
+    u64 n_local = 0, n_remote = 0, n_req = 0, n_fwd = 0, n_reply = 0;      // per call (a pull; the push costs the same)
+    for (int64_t p = p0; p < p1; ++p) {
+        const int64_t kr = a.e_row[p], kc = a.m + a.e_col[p];
+        const float v = a.e_val[p];
+        // where the two keys live, and what reaching them costs
+        const int32_t o_r = a.owner[kr], o_c = a.owner[kc];
+        const int32_t h_r = (int32_t)(kr / a.per_home), h_c = (int32_t)(kc / a.per_home);
+        const bool rem_r = o_r != worker, rem_c = o_c != worker;
+        n_local += (rem_r ? 0 : 1) + (rem_c ? 0 : 1);
+        n_remote += (rem_r ? 1 : 0) + (rem_c ? 1 : 0);
+        const bool req_r = rem_r && h_r != worker, req_c = rem_c && h_c != worker;
+        n_req += (req_r ? 1 : 0) + (req_c && !(req_r && h_c == h_r) ? 1 : 0);
+        const bool fwd_r = rem_r && h_r != o_r, fwd_c = rem_c && h_c != o_c;
+        n_fwd += (fwd_r ? 1 : 0) + (fwd_c && !(fwd_r && h_c == h_r && o_c == o_r) ? 1 : 0);
+        n_reply += (rem_r ? 1 : 0) + (rem_c && !(rem_r && o_c == o_r) ? 1 : 0);
+        // pull
+        float *pw = a.val + kr * L, *ph = a.val + kc * L;
+        float w[NV], h[NV], prod[NV];
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+            const bool in = lane + 64 * c < L;
+            w[c] = in ? pw[lane + 64 * c] : 0.0f;
+            h[c] = in ? ph[lane + 64 * c] : 0.0f;
+        }
+        // the step
+        sgd_products<NV, EXACT>(w, h, prod);
+        float dot;
+        if constexpr (EXACT) {
+            dot = 0.0f;                                                   // components summed in index order
+#pragma unroll
+            for (int c = 0; c < NV; ++c) {
+                const int lim = min(64, L - 64 * c);
+                for (int l = 0; l < lim; ++l) dot = dot + rl_f(prod[c], l);
+            }
+        } else {
+            dot = wave_sum(prod[0]);
+        }
+        const float e = v - dot;
+        // push: the update terms are added to what the store holds
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+            if (lane + 64 * c >= L) continue;
+            float dw, dh;
+            if constexpr (EXACT) {
+                dw = lr * (e * h[c] - lambda * w[c]);
+                dh = lr * (e * w[c] - lambda * h[c]);
+            } else {
+                dw = lr * __builtin_fmaf(e, h[c], -(lambda * w[c]));
+                dh = lr * __builtin_fmaf(e, w[c], -(lambda * h[c]));
+            }
+            float cw = w[c], ch = h[c];
+            if (!a.in_place) {
+                cw = __hip_atomic_load(&pw[lane + 64 * c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                ch = __hip_atomic_load(&ph[lane + 64 * c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            pw[lane + 64 * c] = cw + dw;
+            ph[lane + 64 * c] = ch + dh;
+        }
+    }
+    if (lane == 0) {
+        u64 *st = stat_slot(a.stats);
+        if (n_local) { atomicAdd(&st[PS_STAT_PULL_LOCAL], n_local); atomicAdd(&st[PS_STAT_PUSH_LOCAL], n_local); }
+        if (n_remote) { atomicAdd(&st[PS_STAT_PULL_REMOTE], n_remote); atomicAdd(&st[PS_STAT_PUSH_REMOTE], n_remote); }
+        if (n_req) atomicAdd(&st[PS_STAT_MSG_ACC_REQ], 2 * n_req);
+        if (n_fwd) atomicAdd(&st[PS_STAT_MSG_ACC_FWD], 2 * n_fwd);
+        if (n_reply) atomicAdd(&st[PS_STAT_MSG_ACC_REPLY], 2 * n_reply);
+    }
+}
+
+template <int NV>
+static int launch_classic(dpaps_ps *ps, const ClassicArgs &a, int ntasks, hipStream_t st) {
+    if (ps->opt_exact) k_mf_sgd_classic<NV, true><<<ntasks, 64, 0, st>>>(a);
+    else k_mf_sgd_classic<NV, false><<<ntasks, 64, 0, st>>>(a);
+    PS_HIP(ps, hipGetLastError());
+    return PS_OK;
+}
+
 extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32_t *stratum_ptr_host, int32_t num_strata,
                             float lr, float lambda, void *stream) {
     if (!ps || num_strata < 0 || (num_strata > 0 && (!tasks_host || !stratum_ptr_host))) return PS_EINVAL;
@@ -411,8 +518,9 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
         const int ntasks = stratum_ptr_host[s + 1] - stratum_ptr_host[s];
         if (ntasks == 0) continue;
         const int32_t *tasks = ps->d_tasks + 3 * (int64_t)stratum_ptr_host[s];
-        const bool grouped = ps->opt_grouped && !ps->opt_exact && L <= 128 && f.sweep_ok;
-        if (!grouped) {      // the grouped kernel does the localize step itself
+        const bool classic = ps->opt_classic != 0;
+        const bool grouped = !classic && ps->opt_grouped && !ps->opt_exact && L <= 128 && f.sweep_ok;
+        if (!grouped && !classic) {      // the grouped kernel does the localize step itself; a classic server has none
             LocalizeArgs la{tasks, ps->owner, f.row_bounds, f.col_bounds, f.m, ps->per_home, ps->W, ps->stats, ps->err};
             k_mf_localize<<<ntasks, 256, loc_lds, st>>>(la);
             PS_HIP(ps, hipGetLastError());
@@ -443,7 +551,16 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
             ps->ev_used += 2;
             PS_HIP(ps, hipEventRecord(ev0, st));
         }
-        if (grouped) {
+        if (classic) {
+            ClassicArgs ca{tasks, ps->val, ps->owner, f.row, f.col, f.val, f.run_start, f.blk_run_ptr, f.m, ps->per_home,
+                           L, f.d_col, ps->opt_classic == 2 ? 1 : 0, lr, lambda, ps->stats, ps->err};
+            switch (NV) {
+            case 1: rc = launch_classic<1>(ps, ca, ntasks, st); break;
+            case 2: rc = launch_classic<2>(ps, ca, ntasks, st); break;
+            case 3: rc = launch_classic<3>(ps, ca, ntasks, st); break;
+            default: rc = launch_classic<4>(ps, ca, ntasks, st); break;
+            }
+        } else if (grouped) {
             rc = dpaps_launch_sgd_chunk(ps, a, ntasks, ps->opt_waves, st);
         } else if (ps->opt_exact) {
             switch (NV) {

@@ -580,6 +580,7 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
     case PS_OPT_MF_PROFILE: ps->opt_profile = value != 0; return PS_OK;
     case PS_OPT_MF_GROUPED: ps->opt_grouped = value != 0; return PS_OK;
     case PS_OPT_PUSH_SEQUENTIAL: ps->opt_push_sequential = value != 0; return PS_OK;
+    case PS_OPT_MF_CLASSIC: if (value < 0 || value > 2) return PS_EINVAL; ps->opt_classic = (int)value; return PS_OK;
     case PS_OPT_MF_TEAM_MAX: if (value < 1 || value > 14) return PS_EINVAL; ps->opt_team_max = (int)value; return PS_OK;
     case PS_OPT_MF_HEAVY_LEN:
         if (value < 1 || value > (1 << 30)) return PS_EINVAL;
