@@ -161,6 +161,49 @@ def bench_kge(args, torch, dev) -> int:
     return 0
 
 
+def bench_ps_micro(args, torch, dev) -> int:
+    """Stand-alone primitives on a store of the large workload's size (value length 100): pull, push, localize
+    for 2^20 .. 2^24 keys, uniform and Zipf(1.0); rows/s and GB/s by the byte model of each (pull: key + row read
+    + row written = 8 + 8 L; push: key + update row + stored row read and written = 8 + 12 L; localize: key +
+    owner read and written = 16)."""
+    from paper_2002_00655_amd import ps as P
+    K, L, W = 497_959, 100, 256
+    srv = P.ParameterServer(K, L, W)
+    g = torch.Generator(device=dev); g.manual_seed(0)
+    zipf_w = (torch.arange(1, K + 1, device=dev, dtype=torch.float64) ** -1.0)
+    zipf_cdf = torch.cumsum(zipf_w / zipf_w.sum(), 0)
+    perm = torch.randperm(K, device=dev, generator=g)
+    rows = []
+    for logn in (20, 22, 24):
+        n = 1 << logn
+        for dist in ("uniform", "zipf"):
+            if dist == "uniform":
+                keys = torch.randint(0, K, (n,), device=dev, generator=g)
+            else:
+                u = torch.rand(n, device=dev, dtype=torch.float64, generator=g)
+                keys = perm[torch.searchsorted(zipf_cdf, u).clamp_(max=K - 1)]
+            buf = torch.zeros((n, L), device=dev)
+            res = {"n": n, "keys": dist}
+            for name, fn, nbytes in (("pull", lambda: srv.pull(keys, 0, out=buf), 8 + 8 * L),
+                                     ("push", lambda: srv.push(keys, buf, 0), 8 + 12 * L),
+                                     ("localize", lambda: srv.localize(keys, 1), 16)):
+                fn(); torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) / 3
+                res[name] = {"rows_per_s": n / dt, "model_gbs": n * nbytes / dt / 1e9}
+            del buf
+            srv.status()
+            rows.append(res)
+            log(f"n=2^{logn} {dist:8s}: " + ", ".join(f"{k} {res[k]['rows_per_s'] / 1e9:.2f} G rows/s ({res[k]['model_gbs']:.0f} GB/s)"
+                                                        for k in ("pull", "push", "localize")))
+    print(json.dumps({"metric": "parameter-server primitives, rows/s", "unit": "rows/s", "n_gpus": 1, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "ps_micro", "num_keys": K, "value_len": L, "workers": W}, "results": rows}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -179,6 +222,7 @@ def main() -> int:
     ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--ps-micro", action="store_true", help="only time the stand-alone pull / push / localize primitives")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (reference for the HBM traffic counters)")
     args = ap.parse_args()
@@ -202,6 +246,8 @@ def main() -> int:
         return 0
     props = torch.cuda.get_device_properties(0)
     log(f"device: {props.name} {props.gcnArchName}, {props.multi_processor_count} CUs, host cores {os.cpu_count()}")
+    if args.ps_micro:
+        return bench_ps_micro(args, torch, dev)
     if args.workload == "complex":
         return bench_kge(args, torch, dev)
 

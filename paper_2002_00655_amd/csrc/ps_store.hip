@@ -161,8 +161,10 @@ __global__ __launch_bounds__(256) void k_localize(const int64_t *keys, int64_t n
         const int64_t p = base + threadIdx.x;
         const bool active = p < n;
         const int64_t k = active ? keys[p] : 0;
+        // (a key that is seen to be the worker's already is left alone: a stale read only costs an exchange, and
+        // a key mentioned a million times in one call does not turn into a million exchanges on one word)
         int32_t old = worker;
-        if (active) old = atomicExch(&owner[k], worker);
+        if (active && __hip_atomic_load(&owner[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != worker) old = atomicExch(&owner[k], worker);
         const bool moved = active && old != worker;
         lds_count_add(active, &l.count[0]);
         lds_count_add(moved, &l.count[1]);
