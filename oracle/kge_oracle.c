@@ -40,6 +40,7 @@
 typedef struct orc_ps orc_ps;
 int orc_ps_pull(orc_ps *ps, int32_t worker, const int64_t *keys, int64_t n, REAL *out);
 int orc_ps_push(orc_ps *ps, int32_t worker, const int64_t *keys, int64_t n, const REAL *deltas);
+int orc_ps_localize(orc_ps *ps, const int64_t *keys, int64_t n, int32_t worker);
 
 /* score of one triple; e_s, w_r, e_o point at 2 D numbers (real parts, then imaginary parts) */
 REAL orc_kge_score(int32_t D, const REAL *es, const REAL *wr, const REAL *eo) {
@@ -108,5 +109,72 @@ int orc_kge_step(orc_ps *ps, int32_t worker, int64_t num_entities, int32_t D, in
     }
     if (loss_out) *loss_out = loss;
     free(keys); free(vals); free(delta);
+    return rc;
+}
+
+/* the entity keys a batch of triples [t0, t1) will access: per triple its subject, its object, its subject
+ * negatives, its object negatives */
+static int64_t entity_keys(int64_t t0, int64_t t1, const int32_t *subj, const int32_t *obj, int32_t ns, const int32_t *neg_subj,
+                           int32_t no, const int32_t *neg_obj, int64_t *keys) {
+    int64_t n = 0;
+    for (int64_t t = t0; t < t1; ++t) {
+        keys[n++] = subj[t]; keys[n++] = obj[t];
+        for (int32_t j = 0; j < ns; ++j) keys[n++] = neg_subj[t * ns + j];
+        for (int32_t j = 0; j < no; ++j) keys[n++] = neg_obj[t * no + j];
+    }
+    return n;
+}
+
+/*
+ * One epoch as the paper sets knowledge-graph-embedding training up (Appendix A): the triples are partitioned
+ * over P workers (by relation: worker w has the triples [part_ptr[w], part_ptr[w+1])), every worker goes through
+ * its part in batches of B, the workers taking turns (worker 0's batch r, worker 1's batch r, ...).
+ * With lookahead != 0 parameters are allocated where they are used: each worker first localizes the relation
+ * keys of its part ("data clustering": all relation accesses local) and the entity keys of its first batch,
+ * and before it works on a batch it localizes the entity keys of its next one ("latency hiding").  An entity
+ * that another worker localizes in between is accessed remotely: a localization conflict.  With lookahead == 0
+ * nothing is relocated (a classic parameter server).  The values do not depend on lookahead.
+ * loss_out (may be NULL): summed loss of all scored triples of the epoch.
+ */
+int orc_kge_epoch(orc_ps *ps, int64_t num_entities, int32_t D, const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                  int32_t ns, const int32_t *neg_subj, int32_t no, const int32_t *neg_obj, const int64_t *part_ptr, int32_t P,
+                  int64_t B, int32_t lookahead, REAL lr, REAL eps, double *loss_out) {
+    if (P <= 0 || B <= 0) return -1;
+    int64_t longest = 0;
+    for (int32_t w = 0; w < P; ++w) if (part_ptr[w + 1] - part_ptr[w] > longest) longest = part_ptr[w + 1] - part_ptr[w];
+    int64_t cap = (longest > B ? longest : B) * (2 + ns + no) + 1;
+    int64_t *keys = (int64_t *)malloc((size_t)cap * sizeof(int64_t));
+    if (!keys) return -4;
+    int rc = 0;
+    double loss = 0.0;
+    if (lookahead) {
+        for (int32_t w = 0; w < P && !rc; ++w) {                     /* relations go where their triples are */
+            int64_t n = 0;
+            for (int64_t t = part_ptr[w]; t < part_ptr[w + 1]; ++t) keys[n++] = num_entities + rel[t];
+            rc = orc_ps_localize(ps, keys, n, w);
+        }
+        for (int32_t w = 0; w < P && !rc; ++w) {                     /* the first batch's entities */
+            int64_t t0 = part_ptr[w], t1 = t0 + B < part_ptr[w + 1] ? t0 + B : part_ptr[w + 1];
+            rc = orc_ps_localize(ps, keys, entity_keys(t0, t1, subj, obj, ns, neg_subj, no, neg_obj, keys), w);
+        }
+    }
+    for (int64_t r = 0; r * B < longest && !rc; ++r) {
+        for (int32_t w = 0; w < P && !rc; ++w) {
+            int64_t t0 = part_ptr[w] + r * B, end = part_ptr[w + 1];
+            if (t0 >= end) continue;
+            int64_t t1 = t0 + B < end ? t0 + B : end;
+            if (lookahead && t1 < end) {                              /* the batch after this one */
+                int64_t u1 = t1 + B < end ? t1 + B : end;
+                rc = orc_ps_localize(ps, keys, entity_keys(t1, u1, subj, obj, ns, neg_subj, no, neg_obj, keys), w);
+                if (rc) break;
+            }
+            double l = 0.0;
+            rc = orc_kge_step(ps, w, num_entities, D, t1 - t0, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no,
+                              neg_obj + t0 * no, lr, eps, &l);
+            loss += l;
+        }
+    }
+    if (loss_out) *loss_out = loss;
+    free(keys);
     return rc;
 }

@@ -172,6 +172,25 @@ class Oracle:
             raise OracleError(rc, "kge_step")
         return loss.value
 
+    def kge_epoch(self, num_entities, D, subj, rel, obj, neg_subj, neg_obj, part_ptr, batch, lookahead, lr, eps) -> float:
+        """One epoch over triples partitioned over workers (see kge_oracle.c); returns the summed loss."""
+        subj, rel, obj = (np.ascontiguousarray(x, dtype=np.int32) for x in (subj, rel, obj))
+        n = subj.size
+        ns_ = np.ascontiguousarray(neg_subj, dtype=np.int32).reshape(n, -1)
+        no_ = np.ascontiguousarray(neg_obj, dtype=np.int32).reshape(n, -1)
+        pp = np.ascontiguousarray(part_ptr, dtype=np.int64)
+        loss = C.c_double(0.0)
+        real = self._ct
+        rc = self.lib.orc_kge_epoch(
+            C.c_void_p(self.h), C.c_int64(num_entities), C.c_int32(D), _p(subj, C.c_int32), _p(rel, C.c_int32), _p(obj, C.c_int32),
+            C.c_int32(ns_.shape[1]), _p(ns_, C.c_int32), C.c_int32(no_.shape[1]), _p(no_, C.c_int32), _p(pp, C.c_int64),
+            C.c_int32(pp.size - 1), C.c_int64(batch), C.c_int32(lookahead), real(float(np.float32(lr))), real(float(np.float32(eps))),
+            C.byref(loss))
+        if rc:
+            raise OracleError(rc, "kge_epoch")
+        return loss.value
+
+
 def mf_block_ratings(m, n, rows, cols, vals, row_bounds, col_bounds):
     """Entries stored block by block for the subepochs (Sec. 2.2.2); returns
     (rows, cols, vals, block_ptr)."""

@@ -20,7 +20,7 @@ import numpy as np
 __all__ = [
     "MFWorkload", "KGEWorkload", "MF_CONFIGS", "make_mf", "mf_config",
     "zipf_probs", "equal_bounds", "balanced_bounds", "cyclic_schedule",
-    "random_schedule", "make_kge",
+    "random_schedule", "make_kge", "partition_by_relation",
 ]
 
 
@@ -332,3 +332,24 @@ def make_kge(num_entities=500_000, num_relations=600, triples=3_000_000, dim=100
     R0 = (g_i.standard_normal((num_relations, 2 * dim), dtype=np.float32) * np.float32(0.1))
     return KGEWorkload(name=name, num_entities=num_entities, num_relations=num_relations, dim=dim,
                        subj=subj, rel=rel, obj=obj, neg_subj=neg_s, neg_obj=neg_o, E0=E0, R0=R0)
+
+
+def partition_by_relation(w: KGEWorkload, parts: int):
+    """The triples grouped by worker, all triples of a relation with one worker (Appendix A of the paper: the
+    training data is partitioned by relation): relations are dealt to the workers by decreasing frequency, each
+    to the worker with the fewest triples so far; inside a worker's part the triples keep their order.
+    Returns (a copy of the workload with the triples reordered, part_ptr of parts + 1 offsets)."""
+    counts = np.bincount(w.rel, minlength=w.num_relations)
+    load = np.zeros(parts, np.int64)
+    owner = np.zeros(w.num_relations, np.int64)
+    for r in np.argsort(-counts, kind="stable"):
+        p = int(np.argmin(load))
+        owner[r] = p
+        load[p] += counts[r]
+    part = owner[w.rel]
+    order = np.argsort(part, kind="stable")
+    part_ptr = np.concatenate([[0], np.cumsum(np.bincount(part, minlength=parts))]).astype(np.int64)
+    out = KGEWorkload(name=w.name, num_entities=w.num_entities, num_relations=w.num_relations, dim=w.dim,
+                      subj=w.subj[order], rel=w.rel[order], obj=w.obj[order], neg_subj=w.neg_subj[order],
+                      neg_obj=w.neg_obj[order], E0=w.E0, R0=w.R0)
+    return out, part_ptr

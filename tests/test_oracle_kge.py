@@ -162,3 +162,102 @@ def test_training_on_a_small_planted_graph_lowers_the_loss_and_ranks_true_triple
     true_set = set(pos)
     is_true = np.array([c in true_set for c in cand])
     assert learned[is_true].mean() > learned[~is_true].mean() + 1.0
+
+
+# ---- the epoch with relation partitioning and pre-localization (Appendix A) ------------------------------------
+def _epoch_setup(P, seed=7, ne=60, nr=6, n_tr=90):
+    from paper_2002_00655_amd import workloads as wl
+    w = wl.make_kge(num_entities=ne, num_relations=nr, triples=n_tr, dim=D, n_neg_s=2, n_neg_o=1, seed=seed)
+    wp, part_ptr = wl.partition_by_relation(w, P)
+    K = ne + nr
+    init = np.zeros((K, 4 * D))
+    init[:ne, :2 * D] = w.E0
+    init[ne:, :2 * D] = w.R0
+    return wp, part_ptr, init
+
+
+def _epoch(prec, wp, part_ptr, init, P, B, lookahead):
+    o = Oracle(prec, init.shape[0], init.shape[1], P)
+    o.push(np.arange(init.shape[0]), init)
+    loss = o.kge_epoch(wp.num_entities, D, wp.subj, wp.rel, wp.obj, wp.neg_subj, wp.neg_obj, part_ptr, B, lookahead, 0.1, 1e-10)
+    return o, loss
+
+
+def test_partition_keeps_every_relation_with_one_worker():
+    wp, part_ptr, _ = _epoch_setup(3)
+    owners = {}
+    for p in range(3):
+        for r in set(wp.rel[part_ptr[p]:part_ptr[p + 1]].tolist()):
+            assert owners.setdefault(r, p) == p
+    assert part_ptr[-1] == wp.subj.size
+
+
+def test_epoch_is_the_steps_in_turn_and_values_do_not_depend_on_where_parameters_live():
+    P, B = 3, 8
+    wp, part_ptr, init = _epoch_setup(P)
+    a, loss_a = _epoch("f64", wp, part_ptr, init, P, B, 1)
+    b, loss_b = _epoch("f64", wp, part_ptr, init, P, B, 0)
+    # written out with the step alone: round r, workers in turn
+    c = Oracle("f64", init.shape[0], init.shape[1], P)
+    c.push(np.arange(init.shape[0]), init)
+    loss_c, r = 0.0, 0
+    while any(part_ptr[p] + r * B < part_ptr[p + 1] for p in range(P)):
+        for p in range(P):
+            t0, t1 = part_ptr[p] + r * B, min(part_ptr[p] + (r + 1) * B, part_ptr[p + 1])
+            if t0 < t1:
+                sl = slice(t0, t1)
+                loss_c += c.kge_step(wp.num_entities, D, wp.subj[sl], wp.rel[sl], wp.obj[sl], wp.neg_subj[sl], wp.neg_obj[sl], 0.1, 1e-10, p)
+        r += 1
+    K = init.shape[0]
+    assert np.array_equal(a.pull(np.arange(K)), c.pull(np.arange(K))) and np.array_equal(b.pull(np.arange(K)), c.pull(np.arange(K)))
+    assert abs(loss_a - loss_c) < 1e-9 and abs(loss_b - loss_c) < 1e-9
+    assert b.stats() == c.stats() and b.stats()["relocated"] == 0
+
+
+def test_relations_are_always_local_and_entities_remote_only_after_a_conflict():
+    """With pre-localization an access is remote only if another worker localized the key after this worker did
+    (counted here from the sequence of localize calls written out in Python)."""
+    P, B = 3, 8
+    wp, part_ptr, init = _epoch_setup(P, seed=9)
+    o, _ = _epoch("f64", wp, part_ptr, init, P, B, 1)
+    ne, per = wp.num_entities, 1 + wp.neg_subj.shape[1] + wp.neg_obj.shape[1]
+    owner = {}                                                         # key -> worker that localized it last
+    def ents(t0, t1):
+        out = []
+        for t in range(t0, t1):
+            out += [wp.subj[t], wp.obj[t], *wp.neg_subj[t], *wp.neg_obj[t]]
+        return out
+    for p in range(P):
+        for t in range(part_ptr[p], part_ptr[p + 1]):
+            owner[ne + wp.rel[t]] = p
+    for p in range(P):
+        for k in ents(part_ptr[p], min(part_ptr[p] + B, part_ptr[p + 1])):
+            owner[k] = p
+    local = remote = 0
+    r = 0
+    while any(part_ptr[p] + r * B < part_ptr[p + 1] for p in range(P)):
+        for p in range(P):
+            t0, end = part_ptr[p] + r * B, part_ptr[p + 1]
+            if t0 >= end:
+                continue
+            t1 = min(t0 + B, end)
+            for k in ents(t1, min(t1 + B, end)):
+                owner[k] = p
+            for t in range(t0, t1):
+                s_list = [wp.subj[t]] + list(wp.neg_subj[t]) + [wp.subj[t]] * wp.neg_obj.shape[1]
+                o_list = [wp.obj[t]] * (1 + wp.neg_subj.shape[1]) + list(wp.neg_obj[t])
+                for s_, o_ in zip(s_list, o_list):
+                    for k in (s_, ne + wp.rel[t], o_):
+                        if owner[k] == p:
+                            local += 1
+                        else:
+                            remote += 1
+        r += 1
+    st = o.stats()
+    assert st["pull_local"] == st["push_local"] == local and st["pull_remote"] == st["push_remote"] == remote
+    assert local + remote == 3 * per * wp.subj.size
+    assert 0 < remote < local / 2                                       # conflicts exist (popular entities) but are the exception
+    # one worker: never a conflict
+    wp1, pp1, init1 = _epoch_setup(1, seed=9)
+    o1, _ = _epoch("f64", wp1, pp1, init1, 1, B, 1)
+    assert o1.stats()["pull_remote"] == 0 and o1.stats()["push_remote"] == 0
