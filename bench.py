@@ -161,6 +161,50 @@ def bench_kge(args, torch, dev) -> int:
     return 0
 
 
+def bench_kge_epoch(args, torch, dev) -> int:
+    """Epochs of the knowledge-graph workload over several workers with the data partitioned by relation and the next
+    batch's entities localized ahead (kge_sgd_epoch): time per epoch and the share of accesses that are remote
+    (localization conflicts), for 1, 2, 4, 8 workers with pre-localization and 8 workers without."""
+    from paper_2002_00655_amd import workloads as wl
+    from paper_2002_00655_amd import ps as P
+    s = args.scale
+    w = wl.make_kge(num_entities=max(1000, int(500_000 * s)), num_relations=max(10, int(600 * s)), triples=max(args.batch, int(3_000_000 * s)))
+    K, L = w.num_entities + w.num_relations, 4 * w.dim
+    per = 1 + w.neg_subj.shape[1] + w.neg_obj.shape[1]
+    rows = []
+    for parts, lookahead in ((1, 1), (2, 1), (4, 1), (8, 1), (8, 0)):
+        wp, part_ptr = wl.partition_by_relation(w, parts)
+        srv = P.ParameterServer(K, L, 8)
+        init = torch.zeros((K, L), device=dev)
+        init[:w.num_entities, :2 * w.dim] = torch.from_numpy(w.E0).to(dev)
+        init[w.num_entities:, :2 * w.dim] = torch.from_numpy(w.R0).to(dev)
+        for lo in range(0, K, 1 << 17):
+            hi = min(K, lo + (1 << 17))
+            srv.push(torch.arange(lo, hi, device=dev), init[lo:hi])
+        del init
+        data = [torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (wp.subj, wp.rel, wp.obj, wp.neg_subj, wp.neg_obj)]
+        srv.kge_sgd_epoch(w.num_entities, w.dim, *data, part_ptr, args.batch, lookahead, 0.1, 1e-10, want_loss=False)   # warm-up epoch
+        torch.cuda.synchronize()
+        st0 = srv.stats()
+        t0 = time.perf_counter()
+        loss = srv.kge_sgd_epoch(w.num_entities, w.dim, *data, part_ptr, args.batch, lookahead, 0.1, 1e-10)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        st = {k: v - st0[k] for k, v in srv.stats().items()}
+        acc = st["pull_local"] + st["pull_remote"]
+        res = {"workers": parts, "lookahead": lookahead, "epoch_s": dt, "scored_triples_per_s": w.subj.size * per / dt,
+               "remote_share": st["pull_remote"] / acc, "relocated": st["relocated"], "localize_keys": st["localize_keys"],
+               "mean_loss": loss / (w.subj.size * per)}
+        rows.append(res)
+        log(f"workers {parts} lookahead {lookahead}: epoch {dt * 1e3:.1f} ms, {res['scored_triples_per_s'] / 1e6:.1f} M scored triples/s, "
+            f"remote accesses {100 * res['remote_share']:.2f} %, relocations {st['relocated']}, mean loss {res['mean_loss']:.4f}")
+        del srv, data
+    print(json.dumps({"metric": "knowledge-graph epoch over workers", "unit": "s", "n_gpus": 1, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "complex_kge_epoch", "entities": w.num_entities, "relations": w.num_relations,
+                                 "triples": int(w.subj.size), "dim": w.dim, "batch": args.batch}, "results": rows}), flush=True)
+    return 0
+
+
 def bench_ps_micro(args, torch, dev) -> int:
     """Stand-alone primitives on a store of the large workload's size (value length 100): pull, push, localize
     for 2^20 .. 2^24 keys, uniform and Zipf(1.0); rows/s and GB/s by the byte model of each (pull: key + row read
@@ -222,6 +266,7 @@ def main() -> int:
     ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--kge-epoch", action="store_true", help="only time knowledge-graph epochs over 1..8 workers (kge_sgd_epoch)")
     ap.add_argument("--ps-micro", action="store_true", help="only time the stand-alone pull / push / localize primitives")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (reference for the HBM traffic counters)")
@@ -248,6 +293,8 @@ def main() -> int:
     log(f"device: {props.name} {props.gcnArchName}, {props.multi_processor_count} CUs, host cores {os.cpu_count()}")
     if args.ps_micro:
         return bench_ps_micro(args, torch, dev)
+    if args.kge_epoch:
+        return bench_kge_epoch(args, torch, dev)
     if args.workload == "complex":
         return bench_kge(args, torch, dev)
 

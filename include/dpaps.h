@@ -210,6 +210,26 @@ int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, int32_t dim
                  const int32_t *rel, const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj, int32_t n_neg_obj,
                  const int32_t *neg_obj, float lr, float eps, double *loss_host_out, void *stream);
 
+/* One epoch of that training over several workers with the parameters allocated where they are used (Appendix A:
+ * "data clustering" for the relation parameters, "latency hiding" for the entity parameters).  The triples are
+ * given grouped by worker - worker w has [part_ptr_host[w], part_ptr_host[w + 1]), all triples of a relation with
+ * one worker - and every worker goes through its part in batches of `batch` triples, the workers taking turns
+ * (worker 0's batch r, worker 1's batch r, ...), each batch one step as in kge_sgd_step.  With lookahead != 0 every
+ * worker first localizes the relation keys of its part and the entity keys (subjects, objects, negatives) of its
+ * first batch, and before it works on a batch it localizes the entity keys of its next one; an entity that another
+ * worker localizes in between is then accessed remotely (a localization conflict; see the pull / push statistics).
+ * With lookahead == 0 nothing is relocated.  The values are the same either way.  The localize calls and the
+ * access statistics touch the owner map and the counters only and run on a second stream of the library's beside
+ * the work on the values; the call returns with that stream joined into `stream`.  All indices are checked on the
+ * device first (a bad one: PS_EKEY from the next status call, nothing is read through it).
+ * subj, rel, obj, neg_subj, neg_obj: device arrays over all num_triples triples, as for kge_sgd_step;
+ * part_ptr_host: num_parts + 1 offsets, num_parts <= the server's workers.  loss_host_out (may be NULL): sum of the
+ * losses of all scored triples of the epoch; asking for it synchronizes the stream. */
+int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, int64_t num_triples, const int32_t *subj, const int32_t *rel,
+                  const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj, int32_t n_neg_obj, const int32_t *neg_obj,
+                  const int64_t *part_ptr_host, int32_t num_parts, int64_t batch, int32_t lookahead, float lr, float eps,
+                  double *loss_host_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -105,6 +105,8 @@ struct dpaps_ps {
     double *d_sse = nullptr;
     void *kge_ws = nullptr;           // scratch of kge_sgd_step (grows)
     size_t kge_ws_bytes = 0;
+    hipStream_t side_stream = nullptr;   // default priority: the localize calls and statistics of kge_sgd_epoch run here
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::string last_error;
 };
 
@@ -153,6 +155,8 @@ int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves
 int dpaps_account_pull(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);
 int dpaps_account_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);
 int dpaps_account_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);
+int dpaps_route_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);   // without the key check
+int dpaps_localize_checked(dpaps_ps *ps, const int64_t *keys, int64_t n, int32_t worker, hipStream_t st);
 int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *deltas, hipStream_t st);
 
 int dpaps_fail_hip(dpaps_ps *ps, hipError_t e, const char *what);

@@ -16,6 +16,8 @@
 #include "common.h"
 #include "mf_device.h"
 
+#include <algorithm>
+
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
 
 // the key occurrences of the batch, in push order: triple of the batch, then positive /
@@ -271,6 +273,169 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
         PS_HIP(ps, hipGetLastError());
         PS_HIP(ps, hipMemcpyAsync(loss_host_out, loss + batch, sizeof(double), hipMemcpyDeviceToHost, st));
         PS_HIP(ps, hipStreamSynchronize(st));
+    }
+    return PS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// One epoch over workers, with the parameters allocated where they are used (Appendix A of the paper)
+// ---------------------------------------------------------------------------
+// every index of the epoch's triples inside its range (the kernels that follow index the store with them)
+__global__ void k_kge_validate(int64_t num_entities, int64_t num_relations, int64_t n, const int32_t *subj, const int32_t *rel,
+                               const int32_t *obj, int32_t ns, const int32_t *neg_subj, int32_t no, const int32_t *neg_obj, int32_t *err) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n) return;
+    bool bad = subj[t] < 0 || subj[t] >= num_entities || obj[t] < 0 || obj[t] >= num_entities || rel[t] < 0 || rel[t] >= num_relations;
+    for (int32_t j = 0; j < ns; ++j) bad |= neg_subj[t * ns + j] < 0 || neg_subj[t * ns + j] >= num_entities;
+    for (int32_t j = 0; j < no; ++j) bad |= neg_obj[t * no + j] < 0 || neg_obj[t * no + j] >= num_entities;
+    if (bad) atomicExch(err, PS_EKEY);
+}
+
+// the entity keys the triples [t0, t1) will access: per triple its subject, its object, its negatives
+__global__ void k_kge_entity_keys(int64_t t0, int64_t t1, const int32_t *subj, const int32_t *obj, int32_t ns, const int32_t *neg_subj,
+                                  int32_t no, const int32_t *neg_obj, int64_t *keys) {
+    const int64_t t = t0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= t1) return;
+    int64_t *k = keys + (t - t0) * (2 + ns + no);
+    k[0] = subj[t]; k[1] = obj[t];
+    for (int32_t j = 0; j < ns; ++j) k[2 + j] = neg_subj[t * ns + j];
+    for (int32_t j = 0; j < no; ++j) k[2 + ns + j] = neg_obj[t * no + j];
+}
+
+__global__ void k_kge_relation_keys(int64_t num_entities, int64_t t0, int64_t t1, const int32_t *rel, int64_t *keys) {
+    const int64_t t = t0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < t1) keys[t - t0] = num_entities + rel[t];
+}
+
+// *acc += the sum of loss[0 .. n)
+__global__ __launch_bounds__(256) void k_kge_loss_add(const double *loss, int64_t n, double *acc) {
+    __shared__ double s[256];
+    double a = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) a += loss[i];
+    s[threadIdx.x] = a;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) s[threadIdx.x] += s[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *acc += s[0];
+}
+
+extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, int64_t num_triples, const int32_t *subj, const int32_t *rel,
+                             const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj, int32_t n_neg_obj, const int32_t *neg_obj,
+                             const int64_t *part_ptr_host, int32_t num_parts, int64_t batch, int32_t lookahead, float lr, float eps,
+                             double *loss_host_out, void *stream) {
+    if (!ps || num_triples < 0 || dim <= 0 || n_neg_subj < 0 || n_neg_obj < 0 || num_entities <= 0 || batch <= 0 || !part_ptr_host) return PS_EINVAL;
+    if (4 * (int64_t)dim != ps->L || num_entities > ps->K) return PS_EINVAL;
+    if (dim > 256 || 1 + (int64_t)n_neg_subj + n_neg_obj > 64) return PS_ELIMIT;
+    if (num_parts <= 0 || num_parts > ps->W) return PS_EWORKER;
+    if (part_ptr_host[0] != 0 || part_ptr_host[num_parts] != num_triples) return PS_EINVAL;
+    int64_t longest = 0;
+    for (int32_t w = 0; w < num_parts; ++w) {
+        if (part_ptr_host[w + 1] < part_ptr_host[w]) return PS_EINVAL;
+        longest = std::max(longest, part_ptr_host[w + 1] - part_ptr_host[w]);
+    }
+    if (num_triples > 0 && (!subj || !rel || !obj || (n_neg_subj > 0 && !neg_subj) || (n_neg_obj > 0 && !neg_obj))) return PS_EINVAL;
+    if (loss_host_out) *loss_host_out = 0.0;
+    if (num_triples == 0) return PS_OK;
+    const int32_t ns = n_neg_subj, no = n_neg_obj, per = 1 + ns + no, ent = 2 + ns + no;
+    const int64_t bmax = std::min(batch, longest);
+    if (3 * bmax * per >= ((int64_t)1 << 31) || longest * ent >= ((int64_t)1 << 31)) return PS_ELIMIT;
+    hipStream_t vs = (hipStream_t)stream;                  // the work on the values
+    if (!ps->side_stream) {
+        PS_HIP(ps, hipStreamCreateWithFlags(&ps->side_stream, hipStreamNonBlocking));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_fork, hipEventDisableTiming));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_join, hipEventDisableTiming));
+    }
+    hipStream_t bs = ps->side_stream;                      // localize calls and statistics: owner map and counters only
+    // scratch: occurrence keys and localize keys (second stream), update rows, their keys and the losses (first)
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    const int64_t rows_max = bmax * (3 + ns + no);
+    const size_t off_loc = up((size_t)3 * bmax * per * 8);
+    const size_t off_ukeys = off_loc + up((size_t)std::max(longest, bmax * ent) * 8);
+    const size_t off_upd = off_ukeys + up((size_t)rows_max * 8);
+    const size_t off_loss = off_upd + up((size_t)rows_max * ps->L * 4);
+    const size_t bytes = off_loss + (size_t)(bmax + 2) * 8;
+    if (bytes > ps->kge_ws_bytes) {
+        PS_HIP(ps, hipStreamSynchronize(vs));
+        if (ps->kge_ws) PS_HIP(ps, hipFree(ps->kge_ws));
+        ps->kge_ws = nullptr; ps->kge_ws_bytes = 0;
+        hipError_t e = hipMalloc(&ps->kge_ws, bytes);
+        if (e != hipSuccess) { (void)hipGetLastError(); ps->last_error = "out of device memory for the epoch's scratch"; return PS_ENOMEM; }
+        ps->kge_ws_bytes = bytes;
+    }
+    int64_t *okeys = (int64_t *)ps->kge_ws;
+    int64_t *lkeys = (int64_t *)((char *)ps->kge_ws + off_loc);
+    int64_t *ukeys = (int64_t *)((char *)ps->kge_ws + off_ukeys);
+    float *upd = (float *)((char *)ps->kge_ws + off_upd);
+    double *loss = (double *)((char *)ps->kge_ws + off_loss);
+    double *loss_acc = loss + bmax;
+
+    // every index is checked once; both streams start after that
+    k_kge_validate<<<grid_for(num_triples, 256), 256, 0, vs>>>(num_entities, ps->K - num_entities, num_triples, subj, rel, obj, ns, neg_subj,
+                                                             no, neg_obj, ps->err);
+    PS_HIP(ps, hipGetLastError());
+    PS_HIP(ps, hipMemsetAsync(loss_acc, 0, sizeof(double), vs));
+    PS_HIP(ps, hipEventRecord(ps->ev_fork, vs));
+    PS_HIP(ps, hipStreamWaitEvent(bs, ps->ev_fork, 0));
+    int rc = PS_OK;
+    auto localize_entities = [&](int64_t t0, int64_t t1, int32_t w) {
+        if (t1 <= t0) return (int)PS_OK;
+        k_kge_entity_keys<<<grid_for(t1 - t0, 256), 256, 0, bs>>>(t0, t1, subj, obj, ns, neg_subj, no, neg_obj, lkeys);
+        PS_HIP(ps, hipGetLastError());
+        return dpaps_localize_checked(ps, lkeys, (t1 - t0) * ent, w, bs);
+    };
+    if (lookahead) {
+        for (int32_t w = 0; w < num_parts && !rc; ++w) {              // relations go where their triples are
+            const int64_t t0 = part_ptr_host[w], t1 = part_ptr_host[w + 1];
+            if (t1 <= t0) continue;
+            k_kge_relation_keys<<<grid_for(t1 - t0, 256), 256, 0, bs>>>(num_entities, t0, t1, rel, lkeys);
+            PS_HIP(ps, hipGetLastError());
+            rc = dpaps_localize_checked(ps, lkeys, t1 - t0, w, bs);
+        }
+        for (int32_t w = 0; w < num_parts && !rc; ++w)                // the first batch's entities
+            rc = localize_entities(part_ptr_host[w], std::min(part_ptr_host[w] + batch, part_ptr_host[w + 1]), w);
+    }
+    for (int64_t r = 0; r * batch < longest && !rc; ++r) {
+        for (int32_t w = 0; w < num_parts && !rc; ++w) {
+            const int64_t t0 = part_ptr_host[w] + r * batch, end = part_ptr_host[w + 1];
+            if (t0 >= end) continue;
+            const int64_t t1 = std::min(t0 + batch, end), nb = t1 - t0;
+            // second stream: the next batch's entities come to this worker, then this batch's accesses are counted
+            if (lookahead && t1 < end) rc = localize_entities(t1, std::min(t1 + batch, end), w);
+            if (rc) break;
+            k_kge_keys<<<grid_for(nb * per, 256), 256, 0, bs>>>(num_entities, nb, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no,
+                                                                neg_obj + t0 * no, okeys);
+            PS_HIP(ps, hipGetLastError());
+            rc = dpaps_route_pull_push(ps, w, okeys, 3 * nb * per, bs);
+            if (rc) break;
+            // first stream: the values
+            const unsigned blocks = grid_for(nb * 64, 256);
+#define KGE_GROUP(NC) k_kge_group<NC><<<blocks, 256, 0, vs>>>(nb, num_entities, dim, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no, \
+                                                              neg_obj + t0 * no, lr, eps, ps->val, upd, ukeys, loss, ps->err)
+            switch ((dim + 63) / 64) {
+            case 1: KGE_GROUP(1); break;
+            case 2: KGE_GROUP(2); break;
+            case 3: KGE_GROUP(3); break;
+            default: KGE_GROUP(4); break;
+            }
+#undef KGE_GROUP
+            PS_HIP(ps, hipGetLastError());
+            rc = dpaps_push_apply(ps, ukeys, nb * (3 + ns + no), upd, vs);
+            if (rc) break;
+            if (loss_host_out) {
+                k_kge_loss_add<<<1, 256, 0, vs>>>(loss, nb, loss_acc);
+                PS_HIP(ps, hipGetLastError());
+            }
+        }
+    }
+    // the second stream joins the first
+    PS_HIP(ps, hipEventRecord(ps->ev_join, bs));
+    PS_HIP(ps, hipStreamWaitEvent(vs, ps->ev_join, 0));
+    if (rc) return rc;
+    if (loss_host_out) {
+        PS_HIP(ps, hipMemcpyAsync(loss_host_out, loss_acc, sizeof(double), hipMemcpyDeviceToHost, vs));
+        PS_HIP(ps, hipStreamSynchronize(vs));
     }
     return PS_OK;
 }

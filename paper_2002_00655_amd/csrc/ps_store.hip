@@ -395,6 +395,9 @@ extern "C" int ps_destroy(ps_handle ps) {
     if (ps->stamp_h) (void)hipFree(ps->stamp_h);
     if (ps->ws) (void)hipFree(ps->ws);
     if (ps->kge_ws) (void)hipFree(ps->kge_ws);
+    if (ps->side_stream) (void)hipStreamDestroy(ps->side_stream);
+    if (ps->ev_fork) (void)hipEventDestroy(ps->ev_fork);
+    if (ps->ev_join) (void)hipEventDestroy(ps->ev_join);
     if (ps->d_tasks) (void)hipFree(ps->d_tasks);
     for (hipEvent_t e : ps->ev_pool) (void)hipEventDestroy(e);
     delete ps;
@@ -514,6 +517,19 @@ extern "C" int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     int rc = dpaps_account_push(ps, worker, keys, n, st);
     if (rc) return rc;
     return dpaps_push_apply(ps, keys, n, deltas, st);
+}
+
+// the owner updates and statistics of a localize call, for keys that have been checked
+int dpaps_localize_checked(dpaps_ps *ps, const int64_t *keys, int64_t n, int32_t worker, hipStream_t st) {
+    if (n == 0) return PS_OK;
+    uint32_t id = next_call_id(ps, st);
+    k_localize<<<route_grid(ps, n), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
+                                                 ps->stamp_o, ps->stamp_pair, id, ps->stats, ps->err);
+    PS_HIP(ps, hipGetLastError());
+    return PS_OK;
+}
+int dpaps_route_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st) {
+    return route_access(ps, worker, keys, n, PS_STAT_PULL_LOCAL, PS_STAT_PULL_REMOTE, st, PS_STAT_PUSH_LOCAL, PS_STAT_PUSH_REMOTE);
 }
 
 extern "C" int ps_localize(ps_handle ps, const int64_t *keys, int64_t n, int32_t worker, void *stream) {

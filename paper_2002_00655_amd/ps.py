@@ -24,7 +24,7 @@ OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES, OPT_MF_PROFILE, OPT_MF_GROUPED, O
 
 EXPORTS = ["ps_create", "ps_destroy", "ps_pull", "ps_push", "ps_localize", "ps_owner", "ps_stats", "ps_status",
            "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_train_sse",
-           "mf_profile_read", "kge_sgd_step"]
+           "mf_profile_read", "kge_sgd_step", "kge_sgd_epoch"]
 
 
 class PSError(RuntimeError):
@@ -56,6 +56,7 @@ def load_library() -> C.CDLL:
     lib.mf_train_sse.argtypes = [vp, vp, vp]
     lib.mf_profile_read.argtypes = [vp, vp, vp, vp]
     lib.kge_sgd_step.argtypes = [vp, i32, i64, i32, i64, vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp]
+    lib.kge_sgd_epoch.argtypes = [vp, i64, i32, i64, vp, vp, vp, i32, vp, i32, vp, vp, i32, i64, i32, f32, f32, vp, vp]
     for name in EXPORTS:
         if name != "ps_last_error":
             getattr(lib, name).restype = C.c_int
@@ -193,6 +194,21 @@ class ParameterServer:
         self._check(_lib.kge_sgd_step(self._h, worker, num_entities, dim, batch, subj.data_ptr(), rel.data_ptr(), obj.data_ptr(),
                                       ns_.shape[1], ns_.data_ptr(), no_.shape[1], no_.data_ptr(), float(lr), float(eps),
                                       C.addressof(loss) if want_loss else None, _stream()), "kge_sgd_step")
+        return float(loss.value) if want_loss else None
+
+    def kge_sgd_epoch(self, num_entities, dim, subj, rel, obj, neg_subj, neg_obj, part_ptr, batch, lookahead, lr, eps,
+                      want_loss: bool = True):
+        """One epoch over workers with relation partitioning and pre-localization (see include/dpaps.h)."""
+        subj, rel, obj = _dev(subj, torch.int32), _dev(rel, torch.int32), _dev(obj, torch.int32)
+        n = subj.numel()
+        ns_ = _dev(neg_subj, torch.int32).reshape(n, -1) if n else torch.zeros((0, 0), dtype=torch.int32)
+        no_ = _dev(neg_obj, torch.int32).reshape(n, -1) if n else torch.zeros((0, 0), dtype=torch.int32)
+        pp = _host(part_ptr, np.int64)
+        loss = C.c_double(0.0)
+        self._check(_lib.kge_sgd_epoch(self._h, num_entities, dim, n, subj.data_ptr(), rel.data_ptr(), obj.data_ptr(), ns_.shape[1],
+                                       ns_.data_ptr(), no_.shape[1], no_.data_ptr(), pp.ctypes.data, pp.size - 1, int(batch),
+                                       int(lookahead), float(lr), float(eps), C.addressof(loss) if want_loss else None, _stream()),
+                    "kge_sgd_epoch")
         return float(loss.value) if want_loss else None
 
 
