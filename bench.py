@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # HBM bytes per launch of the SGD kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same
 # counters read for a plain 1 GiB copy; summary under profiles/).  Only valid for the kernel sources it was taken with.
 KERNEL_SOURCES = ("mf_sgd_chunk.hip", "mf_sgd.hip", "mf_device.h", "common.h")
-TRAFFIC = {"kernel_sha256_16": "7464a85c24b2c3d5", "workload": ("large", 1.0, "equal", 16, -1, 0, False),
-           "bytes_per_launch": 140.1e6 + 123.1e6}
+TRAFFIC = {"kernel_sha256_16": "8cd835e9635ef420", "workload": ("large", 1.0, "balanced", 16, -1, 0, False),
+           "bytes_per_launch": 146.6e6 + 125.2e6}
 
 
 def kernel_sources_hash():
@@ -256,7 +256,8 @@ def main() -> int:
     ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "wide", "complex"])
     ap.add_argument("--batch", type=int, default=8192, help="positive triples per step (complex only)")
     ap.add_argument("--scale", type=float, default=1.0)
-    ap.add_argument("--bounds", default="equal", choices=["equal", "balanced"])
+    ap.add_argument("--bounds", default="balanced", choices=["equal", "balanced"],
+                    help="block boundaries: ranges with equal numbers of entries (default) or of equal length")
     ap.add_argument("--waves", type=int, default=16)
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
