@@ -158,3 +158,21 @@ def test_epoch_rejects_bad_indices_without_touching_anything():
         srv.kge_sgd_epoch(wp.num_entities, wp.dim, *(torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in
                           (wp.subj, wp.rel, wp.obj, wp.neg_subj, wp.neg_obj)), np.arange(0, 21, 4), 4, 1, LR, EPS)
     assert e.value.code == P.PS_EWORKER
+
+
+def test_limits_of_the_step():
+    """63 negatives per triple (the most one wavefront's lanes can hold scores for) and dim 256 work; one more negative
+    and a larger dim are refused without touching anything."""
+    import torch
+    from paper_2002_00655_amd import ps as P
+    w = wl.make_kge(num_entities=120, num_relations=4, triples=6, dim=256, n_neg_s=40, n_neg_o=23, seed=2)
+    orc, o64, srv = _pair(w, num_workers=2)
+    _steps(w, orc, o64, srv, 3, 2, worker=1)
+    _compare(orc, o64, srv)
+    dev = torch.device("cuda")
+    w2 = wl.make_kge(num_entities=120, num_relations=4, triples=2, dim=256, n_neg_s=40, n_neg_o=24, seed=2)
+    with pytest.raises(P.PSError) as e:
+        srv.kge_sgd_step(w2.num_entities, w2.dim, *(torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in
+                         (w2.subj, w2.rel, w2.obj, w2.neg_subj, w2.neg_obj)), LR, EPS, 0)
+    assert e.value.code == P.PS_ELIMIT
+    _compare(orc, o64, srv)

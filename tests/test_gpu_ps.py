@@ -206,3 +206,28 @@ def test_empty_calls():
     srv.localize(e, 1)
     assert srv.owner(e).numel() == 0
     assert all(v == 0 for v in srv.stats().values())
+
+
+def test_many_workers_and_a_key_mentioned_a_million_times():
+    """2,048 workers (the most a server takes) and one call in which a single key makes up half of 2^21 mentions:
+    counters and owner map exact, values as close to the fp64 oracle as the fp32 oracle's."""
+    torch = _torch()
+    from oracle.oracle import Oracle
+    from paper_2002_00655_amd import ps as P
+    rng = np.random.default_rng(11)
+    K, L, W, n = 5000, 8, 2048, 1 << 21
+    keys = rng.integers(0, K, size=n).astype(np.int64)
+    keys[rng.random(n) < 0.5] = 4321
+    d = rng.standard_normal((n, L)).astype(np.float32)
+    orc, o64, srv = Oracle("f32", K, L, W), Oracle("f64", K, L, W), P.ParameterServer(K, L, W)
+    dev = torch.device("cuda")
+    kt = torch.from_numpy(keys).to(dev)
+    for o in (orc, o64):
+        o.localize(keys[:1000], 2047)
+        o.push(keys, d.astype(np.float64) if o is o64 else d, 1500)
+    srv.localize(kt[:1000], 2047)
+    srv.push(kt, torch.from_numpy(d).to(dev), 1500)
+    got = srv.pull(torch.arange(K, device=dev), 7).cpu().numpy()
+    assert _close_as_fp32(got, orc.pull(np.arange(K), 7), o64.pull(np.arange(K), 7))
+    assert np.array_equal(srv.owner().cpu().numpy(), orc.owner())
+    assert srv.stats() == orc.stats()
