@@ -44,6 +44,7 @@
 #include "mf_device.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #define CH 15                    // entries per group (the 16th row of X is the column's row)
 
@@ -404,15 +405,11 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     if (ln + 64 * cc < 16 * NT) stg[15 * RS + ln + 64 * cc] = ho[cc];
 
                 // ---- the new rows: X' = X + (C - I) X, tile by tile; rows 0 .. k-1 go to the store ----------
-                // where the rows of the result go: lane (n16, hi) holds rows 4 hi + v of every tile; byte
-                // offsets into the block's row factors (past the end for rows without an entry)
-                uint32_t dst[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int s = 4 * hi + v;
-                    const int r = bperm_i(c_row, s);
-                    dst[v] = s < k ? (uint32_t)((r - (int)blk_r0) * L + n16) * 4u : wspan;
-                }
+                // The product is formed transposed (X'^T = X^T (C - I)^T + X^T), which leaves lane (n16, hi) with
+                // components 16 tile + 4 hi .. + 3 of row n16 - the layout the rows were gathered in - so a row
+                // goes to the store in 16-byte pieces.  Byte offset of the lane's piece of tile 0 in the block's
+                // row factors (past the end for rows without an entry, row 15 among them):
+                const uint32_t dst = n16 < k ? (uint32_t)((bperm_i(c_row, n16) - (int)blk_r0) * L + 4 * hi) * 4u : wspan;
                 float ca[4];                               // (C - I)[t = n16][s = 4 hi + v]; row 15 is not needed any more
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
@@ -433,17 +430,22 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     float xn[4];
 #pragma unroll
                     for (int v = 0; v < 4; ++v) xn[v] = stg[(4 * hi + v) * RS + 16 * tile + n16];
-                    f32x4 acc = {xn[0], xn[1], xn[2], xn[3]};             // the I of X + (C - I) X: same ln layout as the result
+                    f32x4 acc = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * tile + 4 * hi]);   // the X of X + (C - I) X
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ca[v], xn[v], acc, 0, 0, 0);
-                    const bool comp = tile < NT - 1 || 16 * tile + n16 < L;       // the component exists
-                    // (element by element into scalars first: a bit cast applied to a vector element directly
-                    // has been seen to pick element 0 every time)
-                    const float r0 = acc[0], r1 = acc[1], r2 = acc[2], r3 = acc[3];
-                    const float rr[4] = {r0, r1, r2, r3};
+                    for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xn[v], ca[v], acc, 0, 0, 0);
+                    if constexpr (A4) {
+                        const bool comp = tile < NT - 1 || 16 * tile + 4 * hi < L;    // the piece exists (the rank is a multiple of 4)
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc), wbuf, (int)(comp ? dst : wspan) + 64 * tile, 0, 0);
+                    } else {
+                        // (element by element into scalars first: a bit cast applied to a vector element directly
+                        // has been seen to pick element 0 every time)
+                        const float r0 = acc[0], r1 = acc[1], r2 = acc[2], r3 = acc[3];
+                        const float rr[4] = {r0, r1, r2, r3};
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(rr[v]), wbuf, (int)(comp ? dst[v] : wspan) + 64 * tile, 0, 0);
+                        for (int q = 0; q < 4; ++q)
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(rr[q]), wbuf,
+                                                                  (int)(16 * tile + 4 * hi + q < L ? dst : wspan) + 64 * tile + 4 * q, 0, 0);
+                    }
                 }
                 // ---- hand the rows on: the stores must have completed before the tickets move ---------
                 {
