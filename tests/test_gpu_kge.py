@@ -48,8 +48,9 @@ def _compare(orc, o64, srv):
     digits only in fp32, is normalised to a step of up to lr all the same, which is where errors of 1e-5 come
     from on either side.  What fixes the bar is the fp64 oracle: the GPU must be as close to it as the fp32
     oracle is (within a factor 4 - these are maxima over few numbers with heavy tails - plus a few units in the
-    last place of the largest value), and within 1e-4 x the largest value of the fp32 oracle.  Owner map and
-    counters are exact."""
+    last place of the largest value).  (Its distance to the fp32 oracle is printed, not tested: it is bounded by
+    the sum of the other two, and the fp32 oracle is no closer to the truth than the GPU.)  Owner map and counters
+    are exact."""
     import torch
     got = srv.pull(torch.arange(srv.K, device="cuda")).cpu().numpy()
     want, exact = orc.pull(np.arange(orc.K)), o64.pull(np.arange(orc.K))
@@ -58,7 +59,6 @@ def _compare(orc, o64, srv):
     print(f"  max abs difference: GPU to fp32 oracle {err:.3e}, GPU to fp64 oracle {err_gpu:.3e}, fp32 to fp64 oracle {err_f32:.3e} "
           f"(largest value {scale:.3g})", flush=True)
     assert err_gpu <= 4.0 * err_f32 + 8 * 2.0 ** -24 * max(1.0, scale)
-    assert err <= 1e-4 * max(1.0, scale)
     assert np.array_equal(srv.owner().cpu().numpy(), orc.owner())
     assert srv.stats() == orc.stats()
 
@@ -175,4 +175,16 @@ def test_limits_of_the_step():
         srv.kge_sgd_step(w2.num_entities, w2.dim, *(torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in
                          (w2.subj, w2.rel, w2.obj, w2.neg_subj, w2.neg_obj)), LR, EPS, 0)
     assert e.value.code == P.PS_ELIMIT
+    _compare(orc, o64, srv)
+
+
+def test_full_configuration_steps():
+    """The configuration itself - 500,000 entities, 600 relations, dim 100, 5 + 5 negatives - and the launch shape
+    bench.py times (batches of 8,192 positive triples): two steps against the fp32 and fp64 oracles, every value of
+    every key compared (about half a minute of host work)."""
+    import torch
+    w = wl.make_kge(triples=2 * 8192)
+    print(f"case complex entities={w.num_entities} relations={w.num_relations} dim={w.dim}", flush=True)
+    orc, o64, srv = _pair(w)
+    _steps(w, orc, o64, srv, 8192, 2, worker=0)
     _compare(orc, o64, srv)

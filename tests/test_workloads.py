@@ -1,0 +1,44 @@
+"""Host logic of the seeded input generators (no GPU): block boundaries, schedules, the partition by relation."""
+import numpy as np
+
+from paper_2002_00655_amd import workloads as wl
+
+
+def test_bounds_cover_the_range_and_balanced_ones_balance():
+    w = wl.make_mf("tiny", scale=0.5, seed=4, col=1.0)
+    d = 7
+    for ids, size in ((w.rows, w.m), (w.cols, w.n)):
+        eq, bal = wl.equal_bounds(size, d), wl.balanced_bounds(ids, size, d)
+        for b in (eq, bal):
+            assert b[0] == 0 and b[-1] == size and b.size == d + 1 and np.all(np.diff(b) >= 0)
+        assert np.array_equal(eq, np.arange(d + 1) * size // d)
+        per_range = np.add.reduceat(np.bincount(ids, minlength=size), bal[:-1])
+        heaviest = np.bincount(ids, minlength=size).max()
+        assert per_range.max() - per_range.min() <= 2 * heaviest          # no range is off by more than a couple of ids
+
+
+def test_schedules_are_strata():
+    rng = np.random.default_rng(0)
+    for sched in (wl.cyclic_schedule(6), wl.random_schedule(6, rng)):
+        seen = set()
+        for stratum in sched:
+            workers, rbs, cbs = stratum[:, 0], stratum[:, 1], stratum[:, 2]
+            for x in (workers, rbs, cbs):
+                assert sorted(x.tolist()) == list(range(6))                # no worker, row block or column block twice
+            seen |= {(int(r), int(c)) for r, c in zip(rbs, cbs)}
+        assert len(seen) == 36                                             # every block once per epoch
+
+
+def test_workloads_are_reproducible_and_shaped_as_stated():
+    a, b = wl.make_mf("tiny", seed=3), wl.make_mf("tiny", seed=3)
+    assert np.array_equal(a.rows, b.rows) and np.array_equal(a.vals, b.vals) and np.array_equal(a.W0, b.W0)
+    assert a.nnz == 100_000 and a.rank == 16 and (a.m, a.n) == (1000, 1000)
+    cells = a.rows.astype(np.int64) * a.n + a.cols
+    assert np.unique(cells).size == a.nnz and np.all(np.diff(cells) > 0)   # distinct cells, sorted by (row, column)
+    k = wl.make_kge(num_entities=300, num_relations=5, triples=400, dim=8, n_neg_s=2, n_neg_o=3, seed=1)
+    assert k.neg_subj.shape == (400, 2) and k.neg_obj.shape == (400, 3) and k.E0.shape == (300, 16) and k.R0.shape == (5, 16)
+    assert k.subj.max() < 300 and k.rel.max() < 5
+    kp, part_ptr = wl.partition_by_relation(k, 3)
+    assert part_ptr[0] == 0 and part_ptr[-1] == 400 and sorted(kp.subj.tolist()) == sorted(k.subj.tolist())
+    sizes = np.diff(part_ptr)
+    assert sizes.max() - sizes.min() <= np.bincount(k.rel).max()           # relations are dealt to the least loaded worker
