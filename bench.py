@@ -41,7 +41,7 @@ def kernel_sources_hash():
 
 
 def measured_traffic(args):
-    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0 or args.classic > 0)
+    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0 or args.classic > 0 or args.handoff)
     if kernel_sources_hash() == TRAFFIC["kernel_sha256_16"] and key == TRAFFIC["workload"]:
         return TRAFFIC["bytes_per_launch"]
     return None     # the kernel (or the workload) is not the one the counters were taken with
@@ -264,6 +264,9 @@ def main() -> int:
     ap.add_argument("--team-max", type=int, default=0, help="most wavefronts per long column run (0: library default)")
     ap.add_argument("--classic", type=int, default=0, choices=[0, 1, 2],
                     help="the epoch as on a classic parameter server (1: values copied out and back, 2: updated in place)")
+    ap.add_argument("--handoff", action="store_true",
+                    help="epochs without barriers: column blocks handed from worker to worker (mf_sgd_epoch_handoff), one launch per epoch")
+    ap.add_argument("--col-blocks", type=int, default=0, help="column blocks (0: as many as row blocks; other values need --handoff)")
     ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -302,12 +305,16 @@ def main() -> int:
     t0 = time.perf_counter()
     w = wl.make_mf(args.workload, scale=args.scale)
     d = w.d_row
+    d_col = args.col_blocks if args.col_blocks > 0 else d
+    if d_col != d and not args.handoff:
+        print("bench.py: --col-blocks needs --handoff (the rotating schedule has as many column blocks as workers)", file=sys.stderr)
+        return 2
     if args.bounds == "balanced":
-        rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d)
+        rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d_col)
     else:
-        rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d)
+        rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d_col)
     t_gen = time.perf_counter() - t0
-    log(f"workload {w.name}: {w.m} x {w.n}, nnz {w.nnz}, rank {w.rank}, {d} x {d} blocks ({args.bounds}); generated in {t_gen:.1f} s")
+    log(f"workload {w.name}: {w.m} x {w.n}, nnz {w.nnz}, rank {w.rank}, {d} x {d_col} blocks ({args.bounds}); generated in {t_gen:.1f} s")
 
     # data layout on the device (set-up, reported but not part of updates/s)
     rows_d, cols_d, vals_d = (torch.from_numpy(x).to(dev) for x in (w.rows, w.cols, w.vals))
@@ -330,6 +337,8 @@ def main() -> int:
     if args.classic:
         srv.set_option(P.OPT_MF_CLASSIC, args.classic)
     kernel_name = "k_mf_sgd_classic" if args.classic else ("k_mf_sgd" if (args.entry_kernel or w.rank > 128) else "k_mf_sgd_chunk")
+    if args.handoff:
+        kernel_name = "k_mf_sgd_handoff"
     srv.push(torch.arange(w.m, device=dev), torch.from_numpy(w.W0).to(dev))
     srv.push(w.m + torch.arange(w.n, device=dev), torch.from_numpy(w.H0).to(dev))
     t0 = time.perf_counter()
@@ -343,12 +352,18 @@ def main() -> int:
     tasks, sptr, _ = _flatten_schedule(wl.cyclic_schedule(d))
     rmse0 = float(np.sqrt(srv.mf_train_sse() / w.nnz))
 
+    def epoch():
+        if args.handoff:
+            srv.mf_sgd_epoch_handoff(w.lr, w.lam, want_order=False)
+        else:
+            srv.mf_sgd_epoch_raw(tasks, sptr, w.lr, w.lam)
+
     for _ in range(args.warmup):
-        srv.mf_sgd_epoch_raw(tasks, sptr, w.lr, w.lam)
+        epoch()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        srv.mf_sgd_epoch_raw(tasks, sptr, w.lr, w.lam)
+        epoch()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     srv.status()
@@ -359,12 +374,21 @@ def main() -> int:
         f"train rmse {rmse0:.4f} -> {rmse1:.4f}")
 
     # duration of the dominant kernel (one launch per stratum), HIP events on the launch stream
-    srv.set_option(P.OPT_MF_PROFILE, 1)
     prof_epochs = max(1, min(args.steps, 3))
-    for _ in range(prof_epochs):
-        srv.mf_sgd_epoch_raw(tasks, sptr, w.lr, w.lam)
-    sgd_ms, launches = srv.mf_profile_read()
-    srv.set_option(P.OPT_MF_PROFILE, 0)
+    if args.handoff:                               # one launch is one epoch
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(prof_epochs):
+            epoch()
+        ev1.record()
+        torch.cuda.synchronize()
+        sgd_ms, launches = ev0.elapsed_time(ev1), prof_epochs
+    else:
+        srv.set_option(P.OPT_MF_PROFILE, 1)
+        for _ in range(prof_epochs):
+            epoch()
+        sgd_ms, launches = srv.mf_profile_read()
+        srv.set_option(P.OPT_MF_PROFILE, 0)
     bytes_per_update = 16 * w.rank + 12            # two rank-r fp32 rows read and written + the 12-byte entry
     units_per_launch = w.nnz * prof_epochs / launches
     avg_launch_s = sgd_ms * 1e-3 / launches
@@ -393,7 +417,7 @@ def main() -> int:
         "metric": "SGD updates/sec, MF rank %d" % w.rank, "value": updates_per_s, "unit": "updates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}_mf", "m": w.m, "n": w.n, "nnz": w.nnz, "rank": w.rank, "blocks": f"{d}x{d}",
+        "config": {"workload": f"{w.name}_mf", "m": w.m, "n": w.n, "nnz": w.nnz, "rank": w.rank, "blocks": f"{d}x{d_col}",
                    "bounds": args.bounds, "lr": w.lr, "lambda": w.lam, "waves": args.waves, "kernel": kernel_name},
         "model_gbs": updates_per_s * bytes_per_update / 1e9,
         "model_frac_of_hbm_peak": updates_per_s * bytes_per_update / 1e9 / HBM_PEAK_GBS,

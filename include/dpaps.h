@@ -178,6 +178,23 @@ int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, const int32
 int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32_t *stratum_ptr_host, int32_t num_strata,
                  float lr, float lambda, void *stream);
 
+/* One pass over all blocks without barriers between subepochs: column blocks are handed from worker to worker
+ * as they become free (the asynchronous form of the blocked schedule - NOMAD, which Sec. 2.2.2 names among the
+ * algorithms that move parameters to the data; each move is a localize, Sec. 2.3).  Worker w keeps row block w for
+ * the whole epoch (needs d_row <= num_workers; one workgroup per worker, one launch per epoch).  A column block is
+ * free or held by one worker.  A worker that has finished a block gives its column block back and takes the first
+ * one, in cyclic order after the one it had, that is free and that it has not had in this epoch (worker w starts
+ * looking at column block floor(w d_col / d_row)); then it localizes its row block and that column block and
+ * processes the block's entries in stored order.  Every block is processed once.  The order depends on timing
+ * and is reported: order_host_out (host, 2 d_row d_col ints, may be NULL; passing it synchronizes the stream)
+ * gets for worker w and its s-th block, at [2 (w d_col + s)], the column block and, next to it, how many workers
+ * had that column block before in this epoch.  The factors, the owner map and the statistics are those of
+ * mf_sgd_epoch over strata of one task each, (w, w, column block), in any sequence that agrees with both of
+ * these orders - blocks that share neither a row block nor a column block commute.
+ * Runs the grouped kernel only: rank <= 128, PS_OPT_MF_EXACT, PS_OPT_MF_CLASSIC off, PS_OPT_MF_GROUPED on
+ * (PS_ELIMIT otherwise), d_col <= 4096.  Scratch is allocated by the library. */
+int mf_sgd_epoch_handoff(ps_handle ps, float lr, float lambda, int32_t *order_host_out, void *stream);
+
 /* Sum over the loaded entries of (v - <w_i, h_j>)^2, accumulated in fp64 from
  * the fp32 factors; synchronizes the stream.  Also reports a deferred error. */
 int mf_train_sse(ps_handle ps, double *sse_host_out, void *stream);

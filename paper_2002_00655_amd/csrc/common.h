@@ -105,6 +105,8 @@ struct dpaps_ps {
     double *d_sse = nullptr;
     void *kge_ws = nullptr;           // scratch of kge_sgd_step (grows)
     size_t kge_ws_bytes = 0;
+    void *handoff_ws = nullptr;       // column block states and the recorded order of mf_sgd_epoch_handoff (grows)
+    size_t handoff_ws_bytes = 0;
     hipStream_t side_stream = nullptr;   // default priority: the localize calls and statistics of kge_sgd_epoch run here
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::string last_error;
@@ -115,6 +117,8 @@ struct dpaps_ps {
 #define DPAPS_HEAVY_WAVES 8
 // Heavy runs of a block at most.
 #define DPAPS_HEAVY_MAX 8
+// Column blocks at most in an epoch with hand-over (one bit each in LDS).
+#define DPAPS_HANDOFF_MAX_COLS 4096
 
 // Arguments of the SGD kernels (one launch = the tasks of one stratum).
 struct SgdArgs {
@@ -145,10 +149,14 @@ struct SgdArgs {
     float lr, lambda;
     u64 *stats;
     int32_t *err;
+    // an epoch with hand-over of column blocks instead of barriers (k_mf_sgd_handoff only)
+    uint32_t *col_state;        // d_col words: visits << 1 | held
+    int32_t *sched;             // per worker and step: column block, visits before
 };
 
 // mf_sgd_chunk.hip: the kernel that processes a column's entries in groups (see there)
 int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st);
+int dpaps_launch_sgd_handoff(dpaps_ps *ps, const SgdArgs &a, int workers, hipStream_t st);
 
 // ps_store.hip: the two halves of ps_pull and ps_push, for steps that read the store where they use the values
 // and add up the update terms of one data point before they push them

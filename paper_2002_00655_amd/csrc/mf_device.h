@@ -67,17 +67,29 @@ __device__ __forceinline__ void ticket_write(uint32_t *tk, uint32_t v) {
 // Row access with lane l holding components l, l+64, ...: only the last of the
 // NV slices can reach past the end of the row, and `tail` says whether this
 // lane's component of that slice exists.
-template <int NV>
+// AGENT: an agent-scope access, which the caches of a compute die pass through, for data that workgroups on
+// different dies hand to each other inside one launch.
+template <bool AGENT>
+__device__ __forceinline__ float load_f(const float *p) {
+    if constexpr (AGENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return *p;
+}
+template <bool AGENT>
+__device__ __forceinline__ void store_f(float *p, float x) {
+    if constexpr (AGENT) __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = x;
+}
+template <int NV, bool AGENT = false>
 __device__ __forceinline__ void load_row_t(const float *p, int lane, bool tail, float (&x)[NV]) {
 #pragma unroll
-    for (int c = 0; c < NV - 1; ++c) x[c] = p[lane + 64 * c];
-    x[NV - 1] = tail ? p[lane + 64 * (NV - 1)] : 0.0f;
+    for (int c = 0; c < NV - 1; ++c) x[c] = load_f<AGENT>(p + lane + 64 * c);
+    x[NV - 1] = tail ? load_f<AGENT>(p + lane + 64 * (NV - 1)) : 0.0f;
 }
-template <int NV>
+template <int NV, bool AGENT = false>
 __device__ __forceinline__ void store_row_t(float *p, int lane, bool tail, const float (&x)[NV]) {
 #pragma unroll
-    for (int c = 0; c < NV - 1; ++c) p[lane + 64 * c] = x[c];
-    if (tail) p[lane + 64 * (NV - 1)] = x[NV - 1];
+    for (int c = 0; c < NV - 1; ++c) store_f<AGENT>(p + lane + 64 * c, x[c]);
+    if (tail) store_f<AGENT>(p + lane + 64 * (NV - 1), x[NV - 1]);
 }
 
 #define INFO_SINGLE 0xFFFFu      // low 16 bits of an info word: the row's only entry in the block
@@ -101,6 +113,8 @@ struct LocalizeArgs {
 };
 
 // All threads of the workgroup call this; bits: 2 * ceil(W / 32) words of LDS scratch.
+// AGENT: the owner map is read and written with agent-scope accesses (see load_f).
+template <bool AGENT = false>
 __device__ __forceinline__ void mf_localize_task(const LocalizeArgs &a, uint32_t *lds_u32, int32_t worker, int32_t rb, int32_t cb) {
     const int words = (a.W + 31) / 32;
     uint32_t *bits_all = lds_u32, *bits_h = lds_u32 + words;
@@ -123,9 +137,13 @@ __device__ __forceinline__ void mf_localize_task(const LocalizeArgs &a, uint32_t
                 const int64_t x0 = sub == 0 ? r0 : c0, x1 = sub == 0 ? r1 : c1;
                 const int64_t s0 = x0 > k_lo ? x0 : k_lo, s1 = x1 < k_hi ? x1 : k_hi;
                 for (int64_t k = s0 + threadIdx.x; k < s1; k += blockDim.x) {
-                    int32_t old = a.owner[k];
+                    int32_t old;
+                    if constexpr (AGENT) old = __hip_atomic_load(&a.owner[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    else old = a.owner[k];
                     if (old != worker) {
-                        a.owner[k] = worker;             // the home node updates the location at once
+                        // the home node updates the location at once
+                        if constexpr (AGENT) __hip_atomic_store(&a.owner[k], worker, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        else a.owner[k] = worker;
                         ++reloc;
                         atomicOr(&bits_h[old >> 5], 1u << (old & 31));
                         atomicOr(&bits_all[old >> 5], 1u << (old & 31));

@@ -460,6 +460,25 @@ static int launch_classic(dpaps_ps *ps, const ClassicArgs &a, int ntasks, hipStr
     return PS_OK;
 }
 
+// the arguments of the SGD kernels that do not depend on the launch
+static SgdArgs sgd_args(dpaps_ps *ps, const int32_t *tasks, float lr, float lambda) {
+    const MfData &f = ps->mf;
+    SgdArgs a{};
+    a.tasks = tasks; a.val = ps->val; a.owner = ps->owner;
+    a.e_row = f.row; a.e_val = f.val; a.e_info = f.info;
+    a.run_start = f.run_start; a.run_col = f.run_col; a.blk_run_ptr = f.blk_run_ptr;
+    a.multi_row = f.multi_row; a.blk_multi_ptr = f.blk_multi_ptr;
+    a.row_bounds = f.row_bounds; a.col_bounds = f.col_bounds;
+    a.m = f.m; a.L = ps->L; a.d_col = f.d_col;
+    a.blk_nheavy = f.blk_nheavy; a.blk_trun_ptr = f.blk_trun_ptr;
+    a.trun_start = f.trun_start; a.trun_row = f.trun_row; a.trun_wait = f.trun_wait;
+    a.t_cinfo = f.t_cinfo; a.t_val = f.t_val;
+    a.run_gptr = f.run_gptr; a.gstart = f.gstart;
+    a.lr = lr; a.lambda = lambda; a.stats = ps->stats; a.err = ps->err;
+    a.W = ps->W; a.per_home = ps->per_home; a.owner_w = ps->owner;
+    return a;
+}
+
 extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32_t *stratum_ptr_host, int32_t num_strata,
                             float lr, float lambda, void *stream) {
     if (!ps || num_strata < 0 || (num_strata > 0 && (!tasks_host || !stratum_ptr_host))) return PS_EINVAL;
@@ -525,20 +544,9 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
             k_mf_localize<<<ntasks, 256, loc_lds, st>>>(la);
             PS_HIP(ps, hipGetLastError());
         }
-        SgdArgs a{};
-        a.tasks = tasks; a.val = ps->val; a.owner = ps->owner;
-        a.e_row = f.row; a.e_val = f.val; a.e_info = f.info;
-        a.run_start = f.run_start; a.run_col = f.run_col; a.blk_run_ptr = f.blk_run_ptr;
-        a.multi_row = f.multi_row; a.blk_multi_ptr = f.blk_multi_ptr;
-        a.row_bounds = f.row_bounds; a.col_bounds = f.col_bounds;
-        a.m = f.m; a.L = L; a.d_col = f.d_col;
+        SgdArgs a = sgd_args(ps, tasks, lr, lambda);
         a.cache_cap = (int32_t)cache_cap; a.ticket_cap = (int32_t)ticket_cap;
-        a.blk_nheavy = f.blk_nheavy; a.blk_trun_ptr = f.blk_trun_ptr;
-        a.trun_start = f.trun_start; a.trun_row = f.trun_row; a.trun_wait = f.trun_wait;
-        a.t_cinfo = f.t_cinfo; a.t_val = f.t_val;
-        a.run_gptr = f.run_gptr; a.gstart = f.gstart;
-        a.lr = lr; a.lambda = lambda; a.stats = ps->stats; a.err = ps->err;
-        a.fuse_localize = grouped ? 1 : 0; a.W = ps->W; a.per_home = ps->per_home; a.owner_w = ps->owner;
+        a.fuse_localize = grouped ? 1 : 0;
         int rc;
         hipEvent_t ev0 = nullptr, ev1 = nullptr;
         if (ps->opt_profile) {
@@ -579,6 +587,45 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
         }
         if (rc) return rc;
         if (ev1) PS_HIP(ps, hipEventRecord(ev1, st));
+    }
+    return PS_OK;
+}
+
+extern "C" int mf_sgd_epoch_handoff(ps_handle ps, float lr, float lambda, int32_t *order_host_out, void *stream) {
+    if (!ps) return PS_EINVAL;
+    MfData &f = ps->mf;
+    if (!f.row) { ps->last_error = "mf_sgd_epoch_handoff before mf_load_ratings"; return PS_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    const int L = ps->L;
+    if (f.d_row > ps->W) { ps->last_error = "mf_sgd_epoch_handoff: more row blocks than workers"; return PS_EWORKER; }
+    if (f.d_col > DPAPS_HANDOFF_MAX_COLS) { ps->last_error = "mf_sgd_epoch_handoff: more than 4096 column blocks"; return PS_ELIMIT; }
+    if (L > 128 || !f.sweep_ok || ps->opt_exact || ps->opt_classic || !ps->opt_grouped) {
+        ps->last_error = "mf_sgd_epoch_handoff runs the grouped kernel only (rank <= 128, default options)";
+        return PS_ELIMIT;
+    }
+    if (f.d_row == 0 || f.d_col == 0) return PS_OK;
+    const size_t n_order = (size_t)f.d_row * f.d_col * 2;
+    const size_t need = (size_t)DPAPS_HANDOFF_MAX_COLS * sizeof(uint32_t) + n_order * sizeof(int32_t);
+    if (need > ps->handoff_ws_bytes) {
+        PS_HIP(ps, hipStreamSynchronize(st));
+        if (ps->handoff_ws) PS_HIP(ps, hipFree(ps->handoff_ws));
+        ps->handoff_ws = nullptr; ps->handoff_ws_bytes = 0;
+        PS_HIP(ps, hipMalloc(&ps->handoff_ws, need));
+        ps->handoff_ws_bytes = need;
+    }
+    SgdArgs a = sgd_args(ps, nullptr, lr, lambda);
+    a.ticket_cap = (int32_t)std::max<int64_t>(f.max_multi_in_block, 1);
+    a.fuse_localize = 1;
+    a.col_state = (uint32_t *)ps->handoff_ws;
+    a.sched = (int32_t *)(a.col_state + DPAPS_HANDOFF_MAX_COLS);
+    // every column block free and unvisited, no order recorded yet (-1: a worker that stopped on an error)
+    PS_HIP(ps, hipMemsetAsync(a.col_state, 0, (size_t)DPAPS_HANDOFF_MAX_COLS * sizeof(uint32_t), st));
+    PS_HIP(ps, hipMemsetAsync(a.sched, 0xFF, n_order * sizeof(int32_t), st));
+    const int rc = dpaps_launch_sgd_handoff(ps, a, f.d_row, st);
+    if (rc) return rc;
+    if (order_host_out) {
+        PS_HIP(ps, hipMemcpyAsync(order_host_out, a.sched, n_order * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        PS_HIP(ps, hipStreamSynchronize(st));
     }
     return PS_OK;
 }

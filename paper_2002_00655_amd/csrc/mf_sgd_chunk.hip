@@ -47,6 +47,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #define CH 15                    // entries per group (the 16th row of X is the column's row)
+#define AUX_SC1 16               // cache policy of a buffer access: agent scope
 
 // value of `v` in lane `src` (any permutation; goes through the LDS crossbar, no memory)
 __device__ __forceinline__ int bperm_i(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }
@@ -56,17 +57,30 @@ __device__ __forceinline__ float bperm_f(float v, int src) {
 
 // NT = number of 16-component tiles of a factor row (rank <= 16 NT); A4: the rank is a multiple of 4,
 // so every row starts on a 16-byte boundary and is read in 16-byte pieces
-// MAXT: the largest workgroup the kernel is compiled for (12 wavefronts leave each of them a third more registers
-// than 16 do, which the first part needs)
-template <int NT, bool A4, int MAXT>
-__global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
-    extern __shared__ __attribute__((aligned(16))) float lds_f[];
-    if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+// AGENT_H: the column factors and the owner map are read and written with agent-scope accesses, which the caches
+// of a compute die pass through to memory, so that the workgroup that takes the column block next - on any die -
+// reads what this one wrote, without a write-back or an invalidation of whole caches (the row factors need none
+// of that: they stay with this workgroup).  Off: plain accesses; the kernel's end publishes everything.
+// One call processes the block (rb, cb) for `worker`; all threads of the workgroup take part.
+template <int NT, bool A4, bool AGENT_H>
+__device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const int32_t worker, const int32_t rb, const int32_t cb) {
+    if constexpr (!AGENT_H) {     // (in the loop, the caller looks: there all threads must take the same way)
+        if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    }
     constexpr int RS = 16 * NT + 4;          // row stride of the staging area in floats (conflict-free for both read patterns)
     constexpr int NV = (NT + 3) / 4;         // 64-component slices of a row
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    // Called in a loop (AGENT_H): the thread's number, the rank and the step sizes pass through empty asm
+    // statements, so that what depends on them - the table of powers of c, lane offsets - is not computed ahead
+    // of the loop and held in registers all the way through it.
+    int tid = threadIdx.x, L_ = a.L;
+    unsigned lr_ = __float_as_uint(a.lr), lambda_ = __float_as_uint(a.lambda);
+    if constexpr (AGENT_H) {
+        __asm__ volatile("" : "+v"(tid));
+        __asm__ volatile("" : "+s"(L_), "+s"(lr_), "+s"(lambda_));
+    }
+    const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
     const int n16_ = lane & 15, hi_ = lane >> 4;
-    const int L = a.L;
+    const int L = L_;
     const bool tail = lane + 64 * (NV - 1) < L;
     const int hwaves = a.heavy_waves;                                  // wavefronts 0 .. hwaves-1 take the heavy runs
     float *stg = lds_f + (size_t)wave * 16 * RS;                       // this wavefront's X: 16 rows (heavy wavefronts only)
@@ -82,7 +96,6 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     __shared__ unsigned int done_entries;
     __shared__ uint32_t give_up;
 
-    const int32_t worker = a.tasks[3 * blockIdx.x], rb = a.tasks[3 * blockIdx.x + 1], cb = a.tasks[3 * blockIdx.x + 2];
     const int64_t b = (int64_t)rb * a.d_col + cb;
     const int64_t run0 = a.blk_run_ptr[b], run1 = a.blk_run_ptr[b + 1];
     const int nmulti = (int)(a.blk_multi_ptr[b + 1] - a.blk_multi_ptr[b]);
@@ -91,7 +104,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     const int ntcols = nruns - nheavy;                                 // non-heavy columns
     const int ncached = min(ntcols, a.hcache_cap);
     const int64_t tr0 = a.blk_trun_ptr[b], tr1 = a.blk_trun_ptr[b + 1];
-    const float lr = a.lr, lambda = a.lambda;
+    const float lr = __uint_as_float(lr_), lambda = __uint_as_float(lambda_);
     const float delta = (float)((double)lr * (double)lambda);         // c = 1 - delta
     // The factors of the block's rows and of its columns, each as a buffer: an access at an offset past
     // the end reads as zero and writes nothing, which is how lanes without a row are switched off
@@ -105,7 +118,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     if (a.fuse_localize) {
         // the localize step of this task (Sec. 2.3), which makes every parameter the worker will touch its own
         LocalizeArgs la{a.tasks, a.owner_w, a.row_bounds, a.col_bounds, a.m, a.per_home, a.W, a.stats, a.err};
-        mf_localize_task(la, reinterpret_cast<uint32_t *>(lds_f), worker, rb, cb);
+        mf_localize_task<AGENT_H>(la, reinterpret_cast<uint32_t *>(lds_f), worker, rb, cb);
     } else {
         // every parameter this worker will touch must be allocated to it (Sec. 4.1: all access is local)
         const int64_t r0 = a.row_bounds[rb], r1 = a.row_bounds[rb + 1];
@@ -121,7 +134,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     // the heavy columns' factors (components past the rank are zero) and their group counters
     for (int i = threadIdx.x; i < DPAPS_HEAVY_MAX * 16 * NT; i += blockDim.x) {
         const int r = i / (16 * NT), k = i - r * 16 * NT;
-        hshare[i] = (r < nheavy && k < L) ? a.val[(a.m + a.run_col[run0 + r]) * (int64_t)L + k] : 0.0f;
+        hshare[i] = (r < nheavy && k < L) ? load_f<AGENT_H>(&a.val[(a.m + a.run_col[run0 + r]) * (int64_t)L + k]) : 0.0f;
     }
     if (threadIdx.x < DPAPS_HEAVY_MAX) hseq[threadIdx.x] = 0;
     {
@@ -129,7 +142,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
 #pragma unroll 4
         for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
             const int s = idx / L;
-            hcache[idx] = a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)];
+            hcache[idx] = load_f<AGENT_H>(&a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)]);
         }
     }
     if (threadIdx.x == 0) {
@@ -385,8 +398,12 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     for (int cc = 0; cc < NV; ++cc) {
                         const bool exists = ln + 64 * cc < L;
                         if (exists) hsh[ln + 64 * cc] = hn[cc];
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf,
-                                                              (int)(exists ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan), 0, 0);
+                        if constexpr (AGENT_H)   // written through to memory, and only as the run leaves it
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf,
+                                                                  (int)(exists && gi + 1 == ng ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan), 0, AUX_SC1);
+                        else
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf,
+                                                                  (int)(exists ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan), 0, 0);
                     }
                     compiler_fence();
                     ticket_write(hsq, (uint32_t)gi + 1u);
@@ -566,9 +583,9 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
                     } else {                                   // did not fit: handed over through memory
                         float *hg = a.val + (a.m + a.run_col[run0 + nheavy + slot]) * (int64_t)L;
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                        load_row_t<NV>(hg, lane, tail, h);
+                        load_row_t<NV, AGENT_H>(hg, lane, tail, h);
                         step(h);
-                        store_row_t<NV>(hg, lane, tail, h);
+                        store_row_t<NV, AGENT_H>(hg, lane, tail, h);
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                     }
                     ticket_write(tk, seq + 1u);
@@ -610,7 +627,7 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
 #pragma unroll 4
         for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
             const int s = idx / L;
-            a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)] = hcache[idx];
+            store_f<AGENT_H>(&a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)], hcache[idx]);
         }
     }
     // each entry was one pull and one push of two local keys
@@ -621,8 +638,97 @@ __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     }
 }
 
+// One workgroup per task of a stratum.
+// MAXT: the largest workgroup the kernel is compiled for (12 wavefronts leave each of them a third more registers
+// than 16 do, which the first part needs)
 template <int NT, bool A4, int MAXT>
-static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
+__global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    sgd_block<NT, A4, false>(a, lds_f, a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1], a.tasks[3 * blockIdx.x + 2]);
+}
+
+// ---- an epoch without barriers: column blocks handed from worker to worker ----------------------------------
+// (the asynchronous form of the blocked schedule - NOMAD, which Sec. 2.2.2 lists among the algorithms that move
+// parameters to where the data is; the move is a localize, Sec. 2.3.)  Workgroup w is worker w and keeps row block
+// w for the whole epoch.  A column block is either free or held by one worker; state word c = visits << 1 | held.
+// A worker that has finished a block gives its column block back and takes another: the first one, in cyclic
+// order after the one it just had, that is free and that it has not had in this epoch.  It never waits while it
+// holds a block, so every wait ends.  Which order results depends on timing; it is written down (sched) so that
+// the epoch can be replayed.
+
+// Wavefront 0 of the workgroup: take a column block; returns it (and how many workers had it before), or -1 when
+// an error is pending or the wait ran out.
+__device__ __forceinline__ int handoff_take(const SgdArgs &a, const uint32_t *todo, int start, int &visit) {
+    const int lane = threadIdx.x, d_col = a.d_col;
+    if (rl_i(__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), 0) != 0) return -1;
+    for (uint32_t spins = 1;; ++spins) {
+        for (int base = 0; base < d_col; base += 64) {
+            int c = start + base + lane;
+            c = c >= d_col ? c - d_col : c;
+            uint32_t sv = 1u;
+            if (base + lane < d_col && ((todo[c >> 5] >> (c & 31)) & 1u)) sv = __hip_atomic_load(&a.col_state[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            unsigned long long free_mask = __ballot((sv & 1u) == 0u);
+            while (free_mask) {
+                const int l = __ffsll((long long)free_mask) - 1;
+                free_mask &= free_mask - 1;
+                const int cc = rl_i(c, l);
+                const uint32_t expect = (uint32_t)rl_i((int)sv, l);
+                int won = 0;
+                if (lane == 0) won = atomicCAS(&a.col_state[cc], expect, expect | 1u) == expect ? 1 : 0;
+                if (rl_i(won, 0)) { visit = (int)(expect >> 1); return cc; }
+            }
+        }
+        __builtin_amdgcn_s_sleep(8);
+        if ((spins & 63u) == 0u) {
+            if (rl_i(__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), 0) != 0) return -1;
+            if (spins > (1u << 21)) { atomicExch(a.err, PS_ESTALL); return -1; }
+        }
+    }
+}
+
+template <int NT, bool A4>
+__global__ __launch_bounds__(1024) void k_mf_sgd_handoff(SgdArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    __shared__ uint32_t todo[DPAPS_HANDOFF_MAX_COLS / 32];
+    __shared__ int s_cb, s_visit;
+    const int32_t worker = blockIdx.x;
+    const int d_col = a.d_col;
+    for (int i = threadIdx.x; i < DPAPS_HANDOFF_MAX_COLS / 32; i += blockDim.x) {
+        const int left = d_col - 32 * i;
+        todo[i] = left >= 32 ? 0xFFFFFFFFu : (left > 0 ? (1u << left) - 1u : 0u);
+    }
+    __syncthreads();
+    int start = (int)((int64_t)worker * d_col / gridDim.x);       // the workers start spread over the column blocks
+    for (int step = 0; step < d_col; ++step) {
+        if (threadIdx.x < 64) {
+            int visit = 0;
+            const int got = handoff_take(a, todo, start, visit);
+            if (threadIdx.x == 0) {
+                s_cb = got; s_visit = visit;
+                if (got >= 0) {
+                    todo[got >> 5] &= ~(1u << (got & 31));
+                    a.sched[2 * ((int64_t)worker * d_col + step)] = got;
+                    a.sched[2 * ((int64_t)worker * d_col + step) + 1] = visit;
+                }
+            }
+        }
+        __syncthreads();
+        const int cb = __builtin_amdgcn_readfirstlane(s_cb);          // the same in all lanes: block addresses stay scalar
+        const int visit = __builtin_amdgcn_readfirstlane(s_visit);
+        if (cb < 0) break;
+        sgd_block<NT, A4, true>(a, lds_f, worker, worker, cb);
+        // every store of this wavefront has reached memory before the barrier, every wavefront's before the release
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (threadIdx.x == 0) __hip_atomic_store(&a.col_state[cb], ((uint32_t)visit + 1u) << 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        start = cb + 1 < d_col ? cb + 1 : 0;
+    }
+}
+
+// LDS plan of sgd_block: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters,
+// then as many other column factors as fit.  Fills in a.sweep, a.ctick_cap, a.hcache_cap.
+template <int NT>
+static int plan_block_lds(dpaps_ps *ps, SgdArgs &a, size_t *lds_out) {
     const MfData &f = ps->mf;
     const int L = a.L;
     // the kernel addresses the factors of a block's rows, and of its columns, with 32-bit byte offsets
@@ -633,8 +739,6 @@ static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStr
     if (!f.sweep_ok) { ps->last_error = "the grouped SGD kernel needs rows in ascending order inside the short column runs"; return PS_ELAYOUT; }
     a.sweep = 1;
     a.ctick_cap = f.max_tail_cols > 1 ? f.max_tail_cols : 1;
-    // LDS plan: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters, then as
-    // many other column factors as fit
     const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 40 + DPAPS_HEAVY_MAX * 16 * NT + DPAPS_HEAVY_MAX) * 4 +
                           ((int64_t)a.ticket_cap + a.ctick_cap) * 4;
     const int64_t budget = (int64_t)ps->lds_bytes - 1024;         // static LDS and slack
@@ -643,7 +747,15 @@ static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStr
     if (hcap > f.max_tail_cols) hcap = f.max_tail_cols;
     if (ps->opt_cache_rows >= 0 && hcap > ps->opt_cache_rows) hcap = ps->opt_cache_rows;
     a.hcache_cap = (int32_t)hcap;
-    const size_t lds = (size_t)(fixed + hcap * L * 4);
+    *lds_out = (size_t)(fixed + hcap * L * 4);
+    return PS_OK;
+}
+
+template <int NT, bool A4, int MAXT>
+static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
+    size_t lds = 0;
+    const int rc = plan_block_lds<NT>(ps, a, &lds);
+    if (rc) return rc;
     static size_t configured = 0;
     if (lds > configured) {
         PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_chunk<NT, A4, MAXT>),
@@ -690,10 +802,25 @@ __global__ void k_team_plan(const int64_t *blk_run_ptr, const int32_t *blk_nheav
     for (; w < 16; ++w) plan[b * 16 + w] = 0;
 }
 
-int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a_in, int ntasks, int waves, hipStream_t st) {
-    SgdArgs a = a_in;
-    // with 12 or more wavefronts, 12 (14 of 16) of them take heavy runs as the block's plan says; else at most
-    // one per heavy run
+template <int NT, bool A4>
+static int launch_handoff(dpaps_ps *ps, SgdArgs a, int workers, hipStream_t st) {
+    size_t lds = 0;
+    const int rc = plan_block_lds<NT>(ps, a, &lds);
+    if (rc) return rc;
+    static size_t configured = 0;
+    if (lds > configured) {
+        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_handoff<NT, A4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds));
+        configured = lds;
+    }
+    k_mf_sgd_handoff<NT, A4><<<workers, 1024, lds, st>>>(a);
+    PS_HIP(ps, hipGetLastError());
+    return PS_OK;
+}
+
+// how the wavefronts of a workgroup share the heavy runs: with 12 or more wavefronts, 12 (14 of 16) of them take
+// heavy runs as the block's plan says; else at most one per heavy run
+static int plan_teams(dpaps_ps *ps, SgdArgs &a, int waves, hipStream_t st) {
     a.team = waves >= 12 ? 2 : 1;
     a.heavy_waves = waves >= 16 ? 14 : (waves >= 12 ? 12 : (waves < DPAPS_HEAVY_MAX ? waves : DPAPS_HEAVY_MAX));
     a.team_plan = nullptr;
@@ -708,6 +835,31 @@ int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a_in, int ntasks, int wa
         }
         a.team_plan = f.team_plan;
     }
+    return PS_OK;
+}
+
+// One launch for a whole epoch: `workers` workgroups of 16 wavefronts, worker w on row block w (see k_mf_sgd_handoff).
+int dpaps_launch_sgd_handoff(dpaps_ps *ps, const SgdArgs &a_in, int workers, hipStream_t st) {
+    SgdArgs a = a_in;
+    const int rc = plan_teams(ps, a, 16, st);
+    if (rc) return rc;
+    switch ((a.L + 15) / 16) {
+    case 1: return a.L % 4 == 0 ? launch_handoff<1, true>(ps, a, workers, st) : launch_handoff<1, false>(ps, a, workers, st);
+    case 2: return a.L % 4 == 0 ? launch_handoff<2, true>(ps, a, workers, st) : launch_handoff<2, false>(ps, a, workers, st);
+    case 3: return a.L % 4 == 0 ? launch_handoff<3, true>(ps, a, workers, st) : launch_handoff<3, false>(ps, a, workers, st);
+    case 4: return a.L % 4 == 0 ? launch_handoff<4, true>(ps, a, workers, st) : launch_handoff<4, false>(ps, a, workers, st);
+    case 5: return a.L % 4 == 0 ? launch_handoff<5, true>(ps, a, workers, st) : launch_handoff<5, false>(ps, a, workers, st);
+    case 6: return a.L % 4 == 0 ? launch_handoff<6, true>(ps, a, workers, st) : launch_handoff<6, false>(ps, a, workers, st);
+    case 7: return a.L % 4 == 0 ? launch_handoff<7, true>(ps, a, workers, st) : launch_handoff<7, false>(ps, a, workers, st);
+    case 8: return a.L % 4 == 0 ? launch_handoff<8, true>(ps, a, workers, st) : launch_handoff<8, false>(ps, a, workers, st);
+    default: return PS_ELIMIT;
+    }
+}
+
+int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a_in, int ntasks, int waves, hipStream_t st) {
+    SgdArgs a = a_in;
+    const int rc = plan_teams(ps, a, waves, st);
+    if (rc) return rc;
     switch ((a.L + 15) / 16) {
     case 1: return a.L % 4 == 0 ? launch_chunk<1, true>(ps, a, ntasks, waves, st) : launch_chunk<1, false>(ps, a, ntasks, waves, st);
     case 2: return a.L % 4 == 0 ? launch_chunk<2, true>(ps, a, ntasks, waves, st) : launch_chunk<2, false>(ps, a, ntasks, waves, st);

@@ -395,6 +395,7 @@ extern "C" int ps_destroy(ps_handle ps) {
     if (ps->stamp_h) (void)hipFree(ps->stamp_h);
     if (ps->ws) (void)hipFree(ps->ws);
     if (ps->kge_ws) (void)hipFree(ps->kge_ws);
+    if (ps->handoff_ws) (void)hipFree(ps->handoff_ws);
     if (ps->side_stream) (void)hipStreamDestroy(ps->side_stream);
     if (ps->ev_fork) (void)hipEventDestroy(ps->ev_fork);
     if (ps->ev_join) (void)hipEventDestroy(ps->ev_join);

@@ -23,7 +23,7 @@ STAT_NAMES = ["pull_local", "pull_remote", "push_local", "push_remote", "relocat
 OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES, OPT_MF_PROFILE, OPT_MF_GROUPED, OPT_MF_HEAVY_LEN, OPT_PUSH_SEQUENTIAL, OPT_MF_TEAM_MAX, OPT_MF_CLASSIC = 1, 2, 3, 4, 5, 6, 7, 8, 9
 
 EXPORTS = ["ps_create", "ps_destroy", "ps_pull", "ps_push", "ps_localize", "ps_owner", "ps_stats", "ps_status",
-           "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_train_sse",
+           "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_sgd_epoch_handoff", "mf_train_sse",
            "mf_profile_read", "kge_sgd_step", "kge_sgd_epoch"]
 
 
@@ -53,6 +53,7 @@ def load_library() -> C.CDLL:
     lib.mf_block_ratings.argtypes = [i64, i64, i64, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.mf_load_ratings.argtypes = [vp, i64, i64, i64, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.mf_sgd_epoch.argtypes = [vp, vp, vp, i32, f32, f32, vp]
+    lib.mf_sgd_epoch_handoff.argtypes = [vp, f32, f32, vp, vp]
     lib.mf_train_sse.argtypes = [vp, vp, vp]
     lib.mf_profile_read.argtypes = [vp, vp, vp, vp]
     lib.kge_sgd_step.argtypes = [vp, i32, i64, i32, i64, vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp]
@@ -161,6 +162,7 @@ class ParameterServer:
         self._check(_lib.mf_load_ratings(self._h, m, n, rows.numel(), rows.data_ptr(), cols.data_ptr(), vals.data_ptr(),
                                          rb.size - 1, cb.size - 1, rb.ctypes.data, cb.ctypes.data, bp.ctypes.data,
                                          _stream()), "mf_load_ratings")
+        self._mf_grid = (rb.size - 1, cb.size - 1)
 
     def mf_sgd_epoch(self, schedule, lr: float, lam: float) -> None:
         """schedule: int32 [S, T, 3] array or list of [T_s, 3] arrays of (worker, row block, column block)."""
@@ -171,6 +173,15 @@ class ParameterServer:
     def mf_sgd_epoch_raw(self, tasks: np.ndarray, sptr: np.ndarray, lr: float, lam: float) -> None:
         self._check(_lib.mf_sgd_epoch(self._h, tasks.ctypes.data, sptr.ctypes.data, sptr.size - 1, float(lr), float(lam),
                                       _stream()), "mf_sgd_epoch")
+
+    def mf_sgd_epoch_handoff(self, lr: float, lam: float, want_order: bool = True):
+        """An epoch with column blocks handed from worker to worker (see include/dpaps.h).  Returns the recorded
+        order as an int32 array [d_row, d_col, 2] of (column block, workers that had it before), or None."""
+        d_row, d_col = self._mf_grid
+        order = np.empty((d_row, d_col, 2), dtype=np.int32) if want_order else None
+        self._check(_lib.mf_sgd_epoch_handoff(self._h, float(lr), float(lam), order.ctypes.data if want_order else None,
+                                              _stream()), "mf_sgd_epoch_handoff")
+        return order
 
     def mf_profile_read(self):
         """(summed SGD kernel time in ms, number of launches) since the last call; needs OPT_MF_PROFILE."""

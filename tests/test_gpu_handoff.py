@@ -1,0 +1,104 @@
+"""GPU parity: an epoch in which column blocks are handed from worker to worker without barriers
+(mf_sgd_epoch_handoff) against the CPU oracle.  The order of the blocks depends on timing, so the library reports
+it; the test checks that the reported order is a valid one and replays it on the oracle as strata of one epoch
+(see test_oracle_handoff.py for what pins the replay).  Bars as for mf_sgd_epoch: owner map and counters
+bit-exact, factors within 1e-4, training RMSE within 1e-5 relative."""
+import numpy as np
+import pytest
+
+from paper_2002_00655_amd import workloads as wl
+from _util import oracle_epochs, compare_state, check_handoff_order, replay_schedule
+
+pytestmark = pytest.mark.gpu
+
+
+def _server(w, rb, cb, blocked, workers):
+    import torch
+    from paper_2002_00655_amd import ps as P
+    br, bc, bv, bp = blocked
+    srv = P.ParameterServer(w.m + w.n, w.rank, workers)
+    dev = torch.device("cuda")
+    srv.push(torch.arange(w.m, device=dev), torch.from_numpy(w.W0).to(dev))
+    srv.push(w.m + torch.arange(w.n, device=dev), torch.from_numpy(w.H0).to(dev))
+    srv.mf_load_ratings(w.m, w.n, torch.from_numpy(br).to(dev), torch.from_numpy(bc).to(dev), torch.from_numpy(bv).to(dev),
+                        rb, cb, bp)
+    return srv
+
+
+def _oracle(w, rb, cb, blocked, workers, orders, prec="f64"):
+    from oracle.oracle import Oracle
+    br, bc, bv, bp = blocked
+    orc = Oracle(prec, w.m + w.n, w.rank, workers)
+    orc.push(np.arange(w.m), w.W0)
+    orc.push(w.m + np.arange(w.n), w.H0)
+    for order in orders:
+        orc.mf_sgd_epoch(w.m, w.n, br, bc, bv, rb, cb, bp, replay_schedule(order), w.lr, w.lam)
+    return orc
+
+
+@pytest.mark.parametrize("name,scale,d_row,d_col,workers,epochs", [
+    ("tiny", 1.0, 4, 4, 4, 2),
+    ("tiny", 1.0, 3, 7, 5, 1),          # more column blocks than workers, a worker without a row block
+    ("tiny", 0.3, 5, 2, 5, 1),          # fewer column blocks than workers: most of them wait
+    ("medium", 0.05, 16, 16, 16, 2),
+    ("medium", 0.05, 12, 40, 12, 1),
+    ("large", 0.002, 32, 64, 32, 1),    # rank 100
+])
+def test_epoch_with_handoff_matches_replay(name, scale, d_row, d_col, workers, epochs):
+    from oracle.oracle import mf_block_ratings
+    w = wl.make_mf(name, scale=scale, seed=21)
+    print(f"case {name}@{scale} {d_row}x{d_col} workers={workers} nnz={w.nnz} rank={w.rank}", flush=True)
+    rb, cb = wl.balanced_bounds(w.rows, w.m, d_row), wl.balanced_bounds(w.cols, w.n, d_col)
+    blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    srv = _server(w, rb, cb, blocked, workers)
+    orders = []
+    for _ in range(epochs):
+        order = srv.mf_sgd_epoch_handoff(w.lr, w.lam)
+        check_handoff_order(order)
+        orders.append(order)
+    srv.status()
+    orc = _oracle(w, rb, cb, blocked, workers, orders)
+    compare_state(orc, srv, exact=False)
+    sse_gpu = srv.mf_train_sse()
+    want = orc.pull(np.arange(orc.K)).astype(np.float64)
+    pred = np.einsum("ij,ij->i", want[w.rows], want[w.m + w.cols])
+    sse = float(((w.vals - pred) ** 2).sum())
+    assert abs(np.sqrt(sse_gpu / w.nnz) - np.sqrt(sse / w.nnz)) <= 1e-5 * np.sqrt(sse / w.nnz)
+
+
+def test_uncached_columns_and_rank_not_multiple_of_four():
+    """Column factors that do not fit in LDS are handed over through memory inside a block as well; rank 50 is
+    read in 4-byte pieces."""
+    from oracle.oracle import mf_block_ratings
+    from paper_2002_00655_amd import ps as P
+    w = wl.make_mf("medium", scale=0.03, seed=5)
+    assert w.rank % 4 != 0
+    d = 8
+    rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d)
+    blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    srv = _server(w, rb, cb, blocked, d)
+    srv.set_option(P.OPT_MF_CACHE_ROWS, 3)
+    order = srv.mf_sgd_epoch_handoff(w.lr, w.lam)
+    check_handoff_order(order)
+    srv.status()
+    compare_state(_oracle(w, rb, cb, blocked, d, [order]), srv, exact=False)
+
+
+def test_limits():
+    from oracle.oracle import mf_block_ratings
+    from paper_2002_00655_amd import ps as P
+    w = wl.make_mf("tiny", scale=0.3, seed=2)
+    rb, cb = wl.equal_bounds(w.m, 4), wl.equal_bounds(w.n, 4)
+    blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    srv = _server(w, rb, cb, blocked, 3)                   # four row blocks, three workers
+    with pytest.raises(P.PSError) as e:
+        srv.mf_sgd_epoch_handoff(w.lr, w.lam)
+    assert e.value.code == P.PS_EWORKER
+    srv = _server(w, rb, cb, blocked, 4)
+    srv.set_option(P.OPT_MF_EXACT, 1)
+    with pytest.raises(P.PSError) as e:
+        srv.mf_sgd_epoch_handoff(w.lr, w.lam)
+    assert e.value.code == P.PS_ELIMIT
+    srv.set_option(P.OPT_MF_EXACT, 0)
+    assert srv.mf_sgd_epoch_handoff(w.lr, w.lam, want_order=False) is None
+    srv.status()
