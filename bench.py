@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # HBM bytes per launch of the SGD kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same
 # counters read for a plain 1 GiB copy; summary under profiles/).  Only valid for the kernel sources it was taken with.
 KERNEL_SOURCES = ("mf_sgd_chunk.hip", "mf_sgd.hip", "mf_device.h", "common.h")
-TRAFFIC = {"kernel_sha256_16": "330e05fe58944c03", "workload": ("large", 1.0, "balanced", 16, -1, 0, False),
-           "bytes_per_launch": 147.6e6 + 126.2e6}
+TRAFFIC = {"kernel_sha256_16": "8a9e98d446f1a753", "workload": ("large", 1.0, "balanced", 8.0, 16, -1, 0, False),
+           "bytes_per_launch": 148.4e6 + 127.1e6}
 
 
 def kernel_sources_hash():
@@ -41,7 +41,7 @@ def kernel_sources_hash():
 
 
 def measured_traffic(args):
-    key = (args.workload, args.scale, args.bounds, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0 or args.classic > 0 or args.handoff)
+    key = (args.workload, args.scale, args.bounds, args.col_cost, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0 or args.classic > 0 or args.handoff)
     if kernel_sources_hash() == TRAFFIC["kernel_sha256_16"] and key == TRAFFIC["workload"]:
         return TRAFFIC["bytes_per_launch"]
     return None     # the kernel (or the workload) is not the one the counters were taken with
@@ -258,6 +258,8 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--bounds", default="balanced", choices=["equal", "balanced"],
                     help="block boundaries: ranges with equal numbers of entries (default) or of equal length")
+    ap.add_argument("--col-cost", type=float, default=8.0,
+                    help="balanced bounds: a column of a block weighs this many entries on top of its own (0: entries only)")
     ap.add_argument("--waves", type=int, default=16)
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
@@ -310,7 +312,7 @@ def main() -> int:
         print("bench.py: --col-blocks needs --handoff (the rotating schedule has as many column blocks as workers)", file=sys.stderr)
         return 2
     if args.bounds == "balanced":
-        rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d_col)
+        rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d_col, per_id=args.col_cost * d)
     else:
         rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d_col)
     t_gen = time.perf_counter() - t0
@@ -418,7 +420,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}_mf", "m": w.m, "n": w.n, "nnz": w.nnz, "rank": w.rank, "blocks": f"{d}x{d_col}",
-                   "bounds": args.bounds, "lr": w.lr, "lambda": w.lam, "waves": args.waves, "kernel": kernel_name},
+                   "bounds": args.bounds, "col_cost": args.col_cost, "lr": w.lr, "lambda": w.lam, "waves": args.waves, "kernel": kernel_name},
         "model_gbs": updates_per_s * bytes_per_update / 1e9,
         "model_frac_of_hbm_peak": updates_per_s * bytes_per_update / 1e9 / HBM_PEAK_GBS,
         "pull_push_rows_per_s": rows_per_s,

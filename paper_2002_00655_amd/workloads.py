@@ -261,9 +261,11 @@ def equal_bounds(size: int, d: int) -> np.ndarray:
     return (np.arange(d + 1, dtype=np.int64) * size) // d
 
 
-def balanced_bounds(ids: np.ndarray, size: int, d: int) -> np.ndarray:
-    """Contiguous ranges holding roughly equal numbers of entries each."""
-    deg = np.bincount(ids, minlength=size).astype(np.int64)
+def balanced_bounds(ids: np.ndarray, size: int, d: int, per_id: float = 0.0) -> np.ndarray:
+    """Contiguous ranges holding roughly equal numbers of entries each.  per_id > 0: ranges of roughly equal
+    weight, where an index weighs its number of entries plus per_id (for blocks whose processing time has a
+    part per row or column on top of the part per entry)."""
+    deg = np.bincount(ids, minlength=size).astype(np.float64) + float(per_id)
     cum = np.concatenate([[0], np.cumsum(deg)])
     targets = np.arange(d + 1, dtype=np.float64) * (cum[-1] / d)
     b = np.searchsorted(cum, targets, side="left").astype(np.int64)

@@ -15,6 +15,14 @@ def test_bounds_cover_the_range_and_balanced_ones_balance():
         per_range = np.add.reduceat(np.bincount(ids, minlength=size), bal[:-1])
         heaviest = np.bincount(ids, minlength=size).max()
         assert per_range.max() - per_range.min() <= 2 * heaviest          # no range is off by more than a couple of ids
+        # with a weight per id on top of its entries, the ranges have equal weight instead
+        per_id = 25.0
+        wb = wl.balanced_bounds(ids, size, d, per_id=per_id)
+        assert wb[0] == 0 and wb[-1] == size and wb.size == d + 1 and np.all(np.diff(wb) >= 0)
+        weight = np.add.reduceat(np.bincount(ids, minlength=size) + per_id, wb[:-1])
+        assert weight.max() - weight.min() <= 2 * (heaviest + per_id)
+        # and a very large weight per id makes them ranges of equal length
+        assert np.abs(wl.balanced_bounds(ids, size, d, per_id=1e9) - eq).max() <= 1
 
 
 def test_schedules_are_strata():
