@@ -102,3 +102,38 @@ def test_limits():
     srv.set_option(P.OPT_MF_EXACT, 0)
     assert srv.mf_sgd_epoch_handoff(w.lr, w.lam, want_order=False) is None
     srv.status()
+
+
+def test_large_config_full_size_with_handoff():
+    """The large configuration (100M entries, rank 100, 256 x 256 blocks, bench.py's block boundaries) in the launch
+    shape that bench.py --handoff times: one epoch, the reported order replayed on the fp32 oracle (about a minute
+    of host work), every key compared."""
+    import time
+    from oracle.oracle import Oracle, mf_block_ratings
+    w = wl.make_mf("large")
+    d = 256
+    print(f"case large with hand-over nnz={w.nnz}", flush=True)
+    rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d, per_id=8.0 * d)
+    t0 = time.time()
+    blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    print(f"  oracle layout {time.time() - t0:.0f} s", flush=True)
+    srv = _server(w, rb, cb, blocked, d)
+    order = srv.mf_sgd_epoch_handoff(w.lr, w.lam)
+    srv.status()
+    check_handoff_order(order)
+    strata = replay_schedule(order)
+    print(f"  reported order: {len(strata)} strata when every block runs as early as the order allows", flush=True)
+    br, bc, bv, bp = blocked
+    orc = Oracle("f32", w.m + w.n, w.rank, d)
+    orc.push(np.arange(w.m), w.W0)
+    orc.push(w.m + np.arange(w.n), w.H0)
+    quarter = (len(strata) + 3) // 4
+    for q in range(4):
+        t0 = time.time()
+        part = strata[q * quarter:(q + 1) * quarter]
+        if part:
+            orc.mf_sgd_epoch(w.m, w.n, br, bc, bv, rb, cb, bp, part, w.lr, w.lam)
+        print(f"  oracle quarter {q + 1} of the replay {time.time() - t0:.0f} s", flush=True)
+    compare_state(orc, srv, exact=False)
+    sse_gpu, sse_orc = srv.mf_train_sse(), orc.mf_train_sse(w.m, br, bc, bv)
+    assert abs(np.sqrt(sse_gpu / w.nnz) - np.sqrt(sse_orc / w.nnz)) <= 1e-5 * np.sqrt(sse_orc / w.nnz)

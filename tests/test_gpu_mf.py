@@ -191,13 +191,13 @@ def test_large_shape_scaled():
 
 def test_large_config_full_size():
     """480,189 x 17,770, 100M entries, rank 100, 256 x 256 blocks with equal numbers of entries per row range and
-    per column range - the configuration and launch shape that bench.py times - one epoch against the fp32 oracle
-    (about a minute of host work)."""
+    column ranges of equal weight (a column as its entries + 8 per block) - the configuration and launch shape that
+    bench.py times - one epoch against the fp32 oracle (about a minute of host work)."""
     import time
     w = wl.make_mf("large")
     d = 256
     print(f"case large nnz={w.nnz}", flush=True)
-    rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d)
+    rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d, per_id=8.0 * d)
     t0 = time.time()
     blocked = _blocked_oracle(w, rb, cb)
     print(f"  oracle layout {time.time() - t0:.0f} s", flush=True)
