@@ -112,74 +112,139 @@ struct LocalizeArgs {
     const int32_t *err;
 };
 
-// All threads of the workgroup call this; bits: 2 * ceil(W / 32) words of LDS scratch.
+// Home nodes (at most) whose keys one task may touch for all of them to be handled in one pass.
+#define DPAPS_LOC_SLOTS 16
+
+// All threads of the workgroup call this.  lds_u32: scratch_words words of LDS scratch, at least 2 * ceil(W / 32);
+// with (home nodes touched + 1) * ceil(W / 32) words (at most DPAPS_LOC_SLOTS home nodes) the keys of all home
+// nodes are handled in one pass, otherwise home node by home node.
 // AGENT: the owner map is read and written with agent-scope accesses (see load_f).
 template <bool AGENT = false>
-__device__ __forceinline__ void mf_localize_task(const LocalizeArgs &a, uint32_t *lds_u32, int32_t worker, int32_t rb, int32_t cb) {
+__device__ __forceinline__ void mf_localize_task(const LocalizeArgs &a, uint32_t *lds_u32, int scratch_words, int32_t worker, int32_t rb,
+                                                 int32_t cb) {
     const int words = (a.W + 31) / 32;
-    uint32_t *bits_all = lds_u32, *bits_h = lds_u32 + words;
     __shared__ int s_reloc, s_req, s_instr;
     const int64_t r0 = a.row_bounds[rb], r1 = a.row_bounds[rb + 1];
     const int64_t c0 = a.m + a.col_bounds[cb], c1 = a.m + a.col_bounds[cb + 1];
-    for (int i = threadIdx.x; i < 2 * words; i += blockDim.x) lds_u32[i] = 0;
-    if (threadIdx.x == 0) { s_reloc = 0; s_req = 0; s_instr = 0; }
-    __syncthreads();
     // home nodes touched by the two key ranges (empty range: lo > hi)
     const int64_t hr_lo = r1 > r0 ? r0 / a.per_home : 1, hr_hi = r1 > r0 ? (r1 - 1) / a.per_home : 0;
     const int64_t hc_lo = c1 > c0 ? c0 / a.per_home : 1, hc_hi = c1 > c0 ? (c1 - 1) / a.per_home : 0;
+    // the owner of a key before; takes the key if it is another's
+    auto take = [&](int64_t k) -> int32_t {
+        int32_t old;
+        if constexpr (AGENT) old = __hip_atomic_load(&a.owner[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else old = a.owner[k];
+        if (old != worker) {
+            // the home node updates the location at once
+            if constexpr (AGENT) __hip_atomic_store(&a.owner[k], worker, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else a.owner[k] = worker;
+        }
+        return old;
+    };
     int reloc = 0;
-    for (int part = 0; part < 2; ++part) {
-        const int64_t lo = part == 0 ? hr_lo : hc_lo, hi = part == 0 ? hr_hi : hc_hi;
-        for (int64_t h = lo; h <= hi; ++h) {
-            if (part == 1 && h >= hr_lo && h <= hr_hi) continue;   // done together with the row range
-            const int64_t k_lo = h * a.per_home, k_hi = k_lo + a.per_home;
-            for (int sub = 0; sub < 2; ++sub) {
-                const int64_t x0 = sub == 0 ? r0 : c0, x1 = sub == 0 ? r1 : c1;
+    // slot of a home node: those of the row range first, those only in the column range behind them
+    const int nslot_r = (int)(hr_hi - hr_lo + 1 > 0 ? hr_hi - hr_lo + 1 : 0);
+    const int nslot_c = (int)(hc_hi - hc_lo + 1 > 0 ? hc_hi - hc_lo + 1 : 0);
+    const int nslots = nslot_r + nslot_c;
+    const bool one_pass = nslots <= DPAPS_LOC_SLOTS && (nslots + 1) * words <= scratch_words;
+    uint32_t *bits_all = one_pass ? lds_u32 + nslots * words : lds_u32;       // the old owners over all home nodes
+    if (one_pass) {
+        // per home node a bit set of the old owners, all filled in one sweep over the keys
+        for (int i = threadIdx.x; i < (nslots + 1) * words; i += blockDim.x) lds_u32[i] = 0;
+        if (threadIdx.x == 0) { s_reloc = 0; s_req = 0; s_instr = 0; }
+        __syncthreads();
+        for (int sub = 0; sub < 2; ++sub) {
+            const int64_t x0 = sub == 0 ? r0 : c0, x1 = sub == 0 ? r1 : c1;
+            const int64_t lo = sub == 0 ? hr_lo : hc_lo, hi = sub == 0 ? hr_hi : hc_hi;
+            for (int64_t h = lo; h <= hi; ++h) {
+                const int slot = sub == 0 || (h >= hr_lo && h <= hr_hi) ? (int)(h - hr_lo) : nslot_r + (int)(h - hc_lo);
+                uint32_t *bits_h = lds_u32 + slot * words;
+                const int64_t k_lo = h * a.per_home, k_hi = k_lo + a.per_home;
                 const int64_t s0 = x0 > k_lo ? x0 : k_lo, s1 = x1 < k_hi ? x1 : k_hi;
                 for (int64_t k = s0 + threadIdx.x; k < s1; k += blockDim.x) {
-                    int32_t old;
-                    if constexpr (AGENT) old = __hip_atomic_load(&a.owner[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    else old = a.owner[k];
+                    const int32_t old = take(k);
                     if (old != worker) {
-                        // the home node updates the location at once
-                        if constexpr (AGENT) __hip_atomic_store(&a.owner[k], worker, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        else a.owner[k] = worker;
                         ++reloc;
                         atomicOr(&bits_h[old >> 5], 1u << (old & 31));
-                        atomicOr(&bits_all[old >> 5], 1u << (old & 31));
                     }
                 }
             }
-            __syncthreads();
-            if (threadIdx.x < 64) {
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            int req = 0, instr = 0;
+            for (int slot = 0; slot < nslots; ++slot) {
+                const int64_t h = slot < nslot_r ? hr_lo + slot : hc_lo + (slot - nslot_r);
+                if (slot >= nslot_r && h >= hr_lo && h <= hr_hi) continue;     // counted with the row range's slot
+                const uint32_t *bits_h = lds_u32 + slot * words;
                 int cnt = 0;
-                for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_h[i]);
+                for (int i = threadIdx.x; i < words; i += 64) {
+                    cnt += __popc(bits_h[i]);
+                    if (bits_h[i]) atomicOr(&bits_all[i], bits_h[i]);
+                }
                 for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
-                if (threadIdx.x == 0 && cnt > 0) {
-                    if (h != worker) s_req += 1;
-                    s_instr += cnt - (int)((bits_h[h >> 5] >> (h & 31)) & 1u);
+                if (cnt > 0) {
+                    if (h != worker) req += 1;
+                    instr += cnt - (int)((bits_h[h >> 5] >> (h & 31)) & 1u);
                 }
             }
-            __syncthreads();
-            for (int i = threadIdx.x; i < words; i += blockDim.x) bits_h[i] = 0;
-            __syncthreads();
+            if (threadIdx.x == 0) { s_req = req; s_instr = instr; }
+        }
+    } else {
+        // home node by home node, one bit set reused
+        uint32_t *bits_h = lds_u32 + words;
+        for (int i = threadIdx.x; i < 2 * words; i += blockDim.x) lds_u32[i] = 0;
+        if (threadIdx.x == 0) { s_reloc = 0; s_req = 0; s_instr = 0; }
+        __syncthreads();
+        for (int part = 0; part < 2; ++part) {
+            const int64_t lo = part == 0 ? hr_lo : hc_lo, hi = part == 0 ? hr_hi : hc_hi;
+            for (int64_t h = lo; h <= hi; ++h) {
+                if (part == 1 && h >= hr_lo && h <= hr_hi) continue;   // done together with the row range
+                const int64_t k_lo = h * a.per_home, k_hi = k_lo + a.per_home;
+                for (int sub = 0; sub < 2; ++sub) {
+                    const int64_t x0 = sub == 0 ? r0 : c0, x1 = sub == 0 ? r1 : c1;
+                    const int64_t s0 = x0 > k_lo ? x0 : k_lo, s1 = x1 < k_hi ? x1 : k_hi;
+                    for (int64_t k = s0 + threadIdx.x; k < s1; k += blockDim.x) {
+                        const int32_t old = take(k);
+                        if (old != worker) {
+                            ++reloc;
+                            atomicOr(&bits_h[old >> 5], 1u << (old & 31));
+                            atomicOr(&bits_all[old >> 5], 1u << (old & 31));
+                        }
+                    }
+                }
+                __syncthreads();
+                if (threadIdx.x < 64) {
+                    int cnt = 0;
+                    for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_h[i]);
+                    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
+                    if (threadIdx.x == 0 && cnt > 0) {
+                        if (h != worker) s_req += 1;
+                        s_instr += cnt - (int)((bits_h[h >> 5] >> (h & 31)) & 1u);
+                    }
+                }
+                __syncthreads();
+                for (int i = threadIdx.x; i < words; i += blockDim.x) bits_h[i] = 0;
+                __syncthreads();
+            }
         }
     }
     if (reloc) atomicAdd(&s_reloc, reloc);
     __syncthreads();
+    int n_transfer = 0, n_reloc = 0, n_req = 0, n_instr = 0;
     if (threadIdx.x < 64) {
-        int cnt = 0;
-        for (int i = threadIdx.x; i < words; i += 64) cnt += __popc(bits_all[i]);
-        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
-        if (threadIdx.x == 0) {
-            u64 *st = stat_slot(a.stats);
-            atomicAdd(&st[PS_STAT_LOCALIZE_KEYS], (u64)((r1 - r0) + (c1 - c0)));
-            if (s_reloc) atomicAdd(&st[PS_STAT_RELOCATED], (u64)s_reloc);
-            if (s_req) atomicAdd(&st[PS_STAT_MSG_LOC_REQ], (u64)s_req);
-            if (s_instr) atomicAdd(&st[PS_STAT_MSG_LOC_INSTRUCT], (u64)s_instr);
-            if (cnt) atomicAdd(&st[PS_STAT_MSG_LOC_TRANSFER], (u64)cnt);
-        }
+        for (int i = threadIdx.x; i < words; i += 64) n_transfer += __popc(bits_all[i]);
+        for (int off = 32; off > 0; off >>= 1) n_transfer += __shfl_xor(n_transfer, off);
+        n_reloc = s_reloc; n_req = s_req; n_instr = s_instr;
     }
-    __syncthreads();
+    __syncthreads();            // the scratch and the three counters may be used again
+    // (after the barrier, so that nobody waits for these additions to arrive: the next barrier of the caller does)
+    if (threadIdx.x == 0) {
+        u64 *st = stat_slot(a.stats);
+        atomicAdd(&st[PS_STAT_LOCALIZE_KEYS], (u64)((r1 - r0) + (c1 - c0)));
+        if (n_reloc) atomicAdd(&st[PS_STAT_RELOCATED], (u64)n_reloc);
+        if (n_req) atomicAdd(&st[PS_STAT_MSG_LOC_REQ], (u64)n_req);
+        if (n_instr) atomicAdd(&st[PS_STAT_MSG_LOC_INSTRUCT], (u64)n_instr);
+        if (n_transfer) atomicAdd(&st[PS_STAT_MSG_LOC_TRANSFER], (u64)n_transfer);
+    }
 }
-

@@ -29,7 +29,8 @@ static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + b
 __global__ __launch_bounds__(256) void k_mf_localize(LocalizeArgs a) {
     extern __shared__ uint32_t lds_loc[];
     if (*(volatile const int32_t *)a.err) return;
-    mf_localize_task(a, lds_loc, a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1], a.tasks[3 * blockIdx.x + 2]);
+    mf_localize_task(a, lds_loc, (DPAPS_LOC_SLOTS + 1) * ((a.W + 31) / 32), a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1],
+                     a.tasks[3 * blockIdx.x + 2]);
 }
 
 // ---------------------------------------------------------------------------
@@ -531,7 +532,7 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
     if (ps->opt_cache_rows >= 0) cache_cap = std::min<int64_t>(cache_cap, ps->opt_cache_rows);
     const size_t lds = (size_t)cache_cap * L * 4 + (size_t)ticket_cap * 4;
     const int threads = 64 * ps->opt_waves;
-    const size_t loc_lds = 2 * (size_t)((ps->W + 31) / 32) * sizeof(uint32_t);
+    const size_t loc_lds = (DPAPS_LOC_SLOTS + 1) * (size_t)((ps->W + 31) / 32) * sizeof(uint32_t);
 
     for (int32_t s = 0; s < num_strata; ++s) {
         const int ntasks = stratum_ptr_host[s + 1] - stratum_ptr_host[s];

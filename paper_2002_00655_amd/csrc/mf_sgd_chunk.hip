@@ -115,10 +115,30 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + blk_r0 * L, 0, (int)wspan, 0x00020000);
     const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + (a.m + blk_c0) * L, 0, (int)hspan, 0x00020000);
 
+    // The column factors that will live in LDS are requested now and put there after the localize step, which
+    // hides their way from memory: of the heavy columns' this thread's first element, of the others' its first HPRE.
+    constexpr int HPRE = 8;
+    auto heavy_elem = [&](int i) {
+        const int r = i / (16 * NT), k = i - r * 16 * NT;
+        return (r < nheavy && k < L) ? load_f<AGENT_H>(&a.val[(a.m + a.run_col[run0 + r]) * (int64_t)L + k]) : 0.0f;
+    };
+    auto cached_elem = [&](int idx) {
+        const int s = idx / L;
+        return load_f<AGENT_H>(&a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)]);
+    };
+    const int ncached_elems = ncached * L;
+    float pre_heavy = 0.0f, pre_cached[HPRE];
+    if (tid < DPAPS_HEAVY_MAX * 16 * NT) pre_heavy = heavy_elem(tid);
+#pragma unroll
+    for (int q = 0; q < HPRE; ++q) {
+        const int idx = tid + q * (int)blockDim.x;
+        pre_cached[q] = idx < ncached_elems ? cached_elem(idx) : 0.0f;
+    }
+
     if (a.fuse_localize) {
         // the localize step of this task (Sec. 2.3), which makes every parameter the worker will touch its own
         LocalizeArgs la{a.tasks, a.owner_w, a.row_bounds, a.col_bounds, a.m, a.per_home, a.W, a.stats, a.err};
-        mf_localize_task<AGENT_H>(la, reinterpret_cast<uint32_t *>(lds_f), worker, rb, cb);
+        mf_localize_task<AGENT_H>(la, reinterpret_cast<uint32_t *>(lds_f), hwaves * 16 * RS, worker, rb, cb);
     } else {
         // every parameter this worker will touch must be allocated to it (Sec. 4.1: all access is local)
         const int64_t r0 = a.row_bounds[rb], r1 = a.row_bounds[rb + 1];
@@ -132,19 +152,16 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     for (int t = threadIdx.x; t < ntcols; t += blockDim.x) ctick[t] = 0;
     for (int i = threadIdx.x; i < hwaves * 16 * RS; i += blockDim.x) lds_f[i] = 0.0f;
     // the heavy columns' factors (components past the rank are zero) and their group counters
-    for (int i = threadIdx.x; i < DPAPS_HEAVY_MAX * 16 * NT; i += blockDim.x) {
-        const int r = i / (16 * NT), k = i - r * 16 * NT;
-        hshare[i] = (r < nheavy && k < L) ? load_f<AGENT_H>(&a.val[(a.m + a.run_col[run0 + r]) * (int64_t)L + k]) : 0.0f;
-    }
+    if (tid < DPAPS_HEAVY_MAX * 16 * NT) hshare[tid] = pre_heavy;
+    for (int i = tid + blockDim.x; i < DPAPS_HEAVY_MAX * 16 * NT; i += blockDim.x) hshare[i] = heavy_elem(i);
     if (threadIdx.x < DPAPS_HEAVY_MAX) hseq[threadIdx.x] = 0;
-    {
-        const int total = ncached * L;
-#pragma unroll 4
-        for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
-            const int s = idx / L;
-            hcache[idx] = load_f<AGENT_H>(&a.val[(a.m + a.run_col[run0 + nheavy + s]) * (int64_t)L + (idx - s * L)]);
-        }
+#pragma unroll
+    for (int q = 0; q < HPRE; ++q) {
+        const int idx = tid + q * (int)blockDim.x;
+        if (idx < ncached_elems) hcache[idx] = pre_cached[q];
     }
+#pragma unroll 4
+    for (int idx = tid + HPRE * (int)blockDim.x; idx < ncached_elems; idx += blockDim.x) hcache[idx] = cached_elem(idx);
     if (threadIdx.x == 0) {
         const double cd = 1.0 - (double)lr * (double)lambda;
         double x = 1.0;
