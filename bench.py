@@ -257,7 +257,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=8192, help="positive triples per step (complex only)")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--bounds", default="balanced", choices=["equal", "balanced"],
-                    help="block boundaries: ranges with equal numbers of entries (default) or of equal length")
+                    help="block boundaries: ranges with equal numbers of entries (default; see --col-cost) or of equal length")
     ap.add_argument("--col-cost", type=float, default=8.0,
                     help="balanced bounds: a column of a block weighs this many entries on top of its own (0: entries only)")
     ap.add_argument("--waves", type=int, default=16)

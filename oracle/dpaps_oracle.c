@@ -16,6 +16,9 @@
  *   - home node (static) / owner node (dynamic) ....... Sec. 3.1 "Location management", Sec. 3.5
  *   - relocation protocol, three messages ............. Sec. 3.2, Fig. "localize-messages"
  *   - remote access, forward strategy, three messages . Sec. 3.3, Fig. "routing" (b)
+ *   - location caches (optional): two messages with a correct entry, four with a
+ *     stale one (double-forward); entries change only with the replies to pull and
+ *     push and with relocations ....................... Sec. 3.3 "Location caching", Fig. "routing" (c), (d)
  *   - message grouping per destination node ........... Sec. 3.7 "Message grouping"
  *   - localization conflict = arrival order ........... Sec. 3.2 (last paragraph)
  *   - parameter blocking with subepochs and a barrier . Sec. 2.2.2, Sec. 4.1, Appendix A
@@ -26,7 +29,11 @@
  *   - home(k) = k / ceil(K / W) (range partition), initial owner = home;
  *   - a hop whose two ends are the same node sends no message (this is what
  *     makes every relocation on two nodes a two-node affair, Table "reloc-stats");
- *   - duplicates of a key in one push are all applied, in argument order.
+ *   - duplicates of a key in one push are all applied, in argument order;
+ *   - location caches: one per node, key -> node, empty at first.  A call routes all its keys with the caches as
+ *     they are when it starts; its replies then set the requester's entries to the owners they came from.  A
+ *     relocation tells the old owner where the key went (it hands the value over); the home node always knows, the
+ *     new owner needs no entry.  A stale entry that names the home node costs what no entry costs.
  *
  * Parity pins for every function here live in tests/test_oracle_*.py.
  */
@@ -43,6 +50,7 @@ enum {
     ST_RELOCATED, ST_LOCALIZE_KEYS,
     ST_MSG_ACC_REQ, ST_MSG_ACC_FWD, ST_MSG_ACC_REPLY,
     ST_MSG_LOC_REQ, ST_MSG_LOC_INSTRUCT, ST_MSG_LOC_TRANSFER,
+    ST_CACHE_HIT, ST_CACHE_STALE,     /* remote accesses routed by a correct / by a stale location cache entry */
     ST_COUNT
 };
 
@@ -61,6 +69,8 @@ typedef struct orc_ps {
     uint8_t *seen_h, *seen_o, *seen_pair;
     int64_t *touched;   /* indices set in seen_pair during the call */
     int64_t n_touched;
+    int32_t *loc;       /* location caches, W x K: loc[n * K + k] = where node n believes key k to be, -1 = no entry;
+                           NULL = the server runs without location caches */
 } orc_ps;
 
 int32_t orc_real_bytes(void) { return (int32_t)sizeof(REAL); }
@@ -89,6 +99,7 @@ orc_ps *orc_ps_create(int64_t K, int32_t L, int32_t W) {
 void orc_ps_destroy(orc_ps *ps) {
     if (!ps) return;
     free(ps->val); free(ps->owner); free(ps->seen_h); free(ps->seen_o); free(ps->seen_pair); free(ps->touched);
+    free(ps->loc);
     free(ps);
 }
 
@@ -119,6 +130,51 @@ static void route_reset(orc_ps *ps) {
     ps->n_touched = 0;
 }
 
+/* Sec. 3.3 "Location caching": switch the location caches on (all entries empty) or off. */
+int orc_ps_location_caches(orc_ps *ps, int32_t on) {
+    if (!ps) return ORC_EINVAL;
+    free(ps->loc); ps->loc = NULL;
+    if (on) {
+        ps->loc = (int32_t *)malloc((size_t)ps->W * (size_t)ps->K * sizeof(int32_t));
+        if (!ps->loc) return ORC_ENOMEM;
+        for (int64_t i = 0; i < (int64_t)ps->W * ps->K; ++i) ps->loc[i] = -1;
+    }
+    return ORC_OK;
+}
+
+/* A remote pull or push of key k by `worker`.  Without an entry in the worker's node's location cache: the
+ * forward strategy (route_key).  With a correct entry the request goes straight to the owner, which replies: two
+ * messages.  With a stale entry it goes to the node named there, which forwards it to the home node, which
+ * forwards it to the owner, which replies: four.  Grouping as in route_key: one request per distinct node
+ * asked, one forward per distinct (from, to), one reply per distinct owner. */
+static void route_access(orc_ps *ps, int32_t worker, int64_t k) {
+    const int32_t h = home_of(ps, k), o = ps->owner[k];
+    const int32_t c = ps->loc ? ps->loc[(int64_t)worker * ps->K + k] : -1;
+    if (c < 0) { route_key(ps, worker, h, o, ST_MSG_ACC_REQ, ST_MSG_ACC_FWD, ST_MSG_ACC_REPLY); return; }
+    if (c == o) {
+        ps->stats[ST_CACHE_HIT]++;
+        /* (the pair (o, o) is marked only so that route_reset finds the two node flags) */
+        int64_t pi = (int64_t)o * ps->W + o;
+        if (!ps->seen_pair[pi]) { ps->seen_pair[pi] = 1; ps->touched[ps->n_touched++] = pi; }
+        if (!ps->seen_h[o]) { ps->seen_h[o] = 1; ps->stats[ST_MSG_ACC_REQ]++; }
+        if (!ps->seen_o[o]) { ps->seen_o[o] = 1; ps->stats[ST_MSG_ACC_REPLY]++; }
+        return;
+    }
+    ps->stats[ST_CACHE_STALE]++;
+    if (c != worker && !ps->seen_h[c]) { ps->seen_h[c] = 1; ps->stats[ST_MSG_ACC_REQ]++; }
+    int64_t p1 = (int64_t)c * ps->W + h, p2 = (int64_t)h * ps->W + o;
+    if (!ps->seen_pair[p1]) { ps->seen_pair[p1] = 1; ps->touched[ps->n_touched++] = p1; if (c != h) ps->stats[ST_MSG_ACC_FWD]++; }
+    if (!ps->seen_pair[p2]) { ps->seen_pair[p2] = 1; ps->touched[ps->n_touched++] = p2; if (h != o) ps->stats[ST_MSG_ACC_FWD]++; }
+    if (!ps->seen_o[o]) { ps->seen_o[o] = 1; ps->stats[ST_MSG_ACC_REPLY]++; }
+}
+
+/* The replies of a call have arrived: the requester's node now knows the owner of every key it asked for. */
+static void cache_replies(orc_ps *ps, int32_t worker, const int64_t *keys, int64_t n) {
+    if (!ps->loc || worker < 0) return;
+    for (int64_t p = 0; p < n; ++p)
+        if (ps->owner[keys[p]] != worker) ps->loc[(int64_t)worker * ps->K + keys[p]] = ps->owner[keys[p]];
+}
+
 /* pull: the current value of each key, wherever it lives (Sec. 2.3). */
 int orc_ps_pull(orc_ps *ps, int32_t worker, const int64_t *keys, int64_t n, REAL *out) {
     if (!ps || n < 0 || (n > 0 && (!keys || !out))) return ORC_EINVAL;
@@ -129,11 +185,11 @@ int orc_ps_pull(orc_ps *ps, int32_t worker, const int64_t *keys, int64_t n, REAL
         for (int32_t c = 0; c < ps->L; ++c) out[p * ps->L + c] = ps->val[k * ps->L + c];
         if (worker >= 0) {
             if (ps->owner[k] == worker) ps->stats[ST_PULL_LOCAL]++;
-            else { ps->stats[ST_PULL_REMOTE]++;
-                   route_key(ps, worker, home_of(ps, k), ps->owner[k], ST_MSG_ACC_REQ, ST_MSG_ACC_FWD, ST_MSG_ACC_REPLY); }
+            else { ps->stats[ST_PULL_REMOTE]++; route_access(ps, worker, k); }
         }
     }
     route_reset(ps);
+    cache_replies(ps, worker, keys, n);
     return ORC_OK;
 }
 
@@ -148,11 +204,11 @@ int orc_ps_push(orc_ps *ps, int32_t worker, const int64_t *keys, int64_t n, cons
         for (int32_t c = 0; c < ps->L; ++c) ps->val[k * ps->L + c] = ps->val[k * ps->L + c] + deltas[p * ps->L + c];
         if (worker >= 0) {
             if (ps->owner[k] == worker) ps->stats[ST_PUSH_LOCAL]++;
-            else { ps->stats[ST_PUSH_REMOTE]++;
-                   route_key(ps, worker, home_of(ps, k), ps->owner[k], ST_MSG_ACC_REQ, ST_MSG_ACC_FWD, ST_MSG_ACC_REPLY); }
+            else { ps->stats[ST_PUSH_REMOTE]++; route_access(ps, worker, k); }
         }
     }
     route_reset(ps);
+    cache_replies(ps, worker, keys, n);
     return ORC_OK;
 }
 
@@ -167,6 +223,7 @@ int orc_ps_localize(orc_ps *ps, const int64_t *keys, int64_t n, int32_t worker) 
         ps->stats[ST_LOCALIZE_KEYS]++;
         if (ps->owner[k] == worker) continue;          /* already here: nothing travels */
         route_key(ps, worker, home_of(ps, k), ps->owner[k], ST_MSG_LOC_REQ, ST_MSG_LOC_INSTRUCT, ST_MSG_LOC_TRANSFER);
+        if (ps->loc) ps->loc[(int64_t)ps->owner[k] * ps->K + k] = worker;   /* the old owner hands the value to `worker` */
         ps->owner[k] = worker;                          /* home updates the location at once */
         ps->stats[ST_RELOCATED]++;
     }

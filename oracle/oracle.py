@@ -17,7 +17,8 @@ _SRC = [os.path.join(_HERE, "dpaps_oracle.c"), os.path.join(_HERE, "kge_oracle.c
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-std=c99", "-Wall"]
 
 STAT_NAMES = ["pull_local", "pull_remote", "push_local", "push_remote", "relocated", "localize_keys",
-              "msg_acc_req", "msg_acc_fwd", "msg_acc_reply", "msg_loc_req", "msg_loc_instruct", "msg_loc_transfer"]
+              "msg_acc_req", "msg_acc_fwd", "msg_acc_reply", "msg_loc_req", "msg_loc_instruct", "msg_loc_transfer",
+              "cache_hit", "cache_stale"]
 
 OK, EINVAL, EKEY, EWORKER, ECONFLICT, ENOMEM, EREMOTE = 0, -1, -2, -3, -4, -5, -7
 
@@ -91,6 +92,12 @@ class Oracle:
         rc = self.lib.orc_ps_push(C.c_void_p(self.h), C.c_int32(worker), _p(k, C.c_int64), C.c_int64(k.size), _p(d, self._ct))
         if rc:
             raise OracleError(rc, "push")
+
+    def location_caches(self, on: bool) -> None:
+        """Sec. 3.3 "Location caching": switch the per-node location caches on (empty) or off."""
+        rc = self.lib.orc_ps_location_caches(C.c_void_p(self.h), C.c_int32(1 if on else 0))
+        if rc:
+            raise OracleError(rc, "location_caches")
 
     def localize(self, keys, worker: int) -> None:
         k = self._keys(keys)
