@@ -164,7 +164,8 @@ def bench_kge(args, torch, dev) -> int:
 def bench_kge_epoch(args, torch, dev) -> int:
     """Epochs of the knowledge-graph workload over several workers with the data partitioned by relation and the next
     batch's entities localized ahead (kge_sgd_epoch): time per epoch and the share of accesses that are remote
-    (localization conflicts), for 1, 2, 4, 8 workers with pre-localization and 8 workers without."""
+    (localization conflicts), for 1, 2, 4, 8 workers with pre-localization and 8 workers without; the last two again
+    with location caches, which change the number of messages that remote accesses cost."""
     from paper_2002_00655_amd import workloads as wl
     from paper_2002_00655_amd import ps as P
     s = args.scale
@@ -172,9 +173,10 @@ def bench_kge_epoch(args, torch, dev) -> int:
     K, L = w.num_entities + w.num_relations, 4 * w.dim
     per = 1 + w.neg_subj.shape[1] + w.neg_obj.shape[1]
     rows = []
-    for parts, lookahead in ((1, 1), (2, 1), (4, 1), (8, 1), (8, 0)):
+    for parts, lookahead, caches in ((1, 1, 0), (2, 1, 0), (4, 1, 0), (8, 1, 0), (8, 0, 0), (8, 1, 1), (8, 0, 1)):
         wp, part_ptr = wl.partition_by_relation(w, parts)
         srv = P.ParameterServer(K, L, 8)
+        srv.set_option(P.OPT_LOCATION_CACHES, caches)
         init = torch.zeros((K, L), device=dev)
         init[:w.num_entities, :2 * w.dim] = torch.from_numpy(w.E0).to(dev)
         init[w.num_entities:, :2 * w.dim] = torch.from_numpy(w.R0).to(dev)
@@ -192,12 +194,16 @@ def bench_kge_epoch(args, torch, dev) -> int:
         dt = time.perf_counter() - t0
         st = {k: v - st0[k] for k, v in srv.stats().items()}
         acc = st["pull_local"] + st["pull_remote"]
-        res = {"workers": parts, "lookahead": lookahead, "epoch_s": dt, "scored_triples_per_s": w.subj.size * per / dt,
-               "remote_share": st["pull_remote"] / acc, "relocated": st["relocated"], "localize_keys": st["localize_keys"],
+        msgs = st["msg_acc_req"] + st["msg_acc_fwd"] + st["msg_acc_reply"]
+        res = {"workers": parts, "lookahead": lookahead, "location_caches": caches, "epoch_s": dt,
+               "scored_triples_per_s": w.subj.size * per / dt, "remote_share": st["pull_remote"] / acc, "relocated": st["relocated"],
+               "localize_keys": st["localize_keys"], "access_messages": msgs, "cache_hit": st["cache_hit"], "cache_stale": st["cache_stale"],
                "mean_loss": loss / (w.subj.size * per)}
         rows.append(res)
-        log(f"workers {parts} lookahead {lookahead}: epoch {dt * 1e3:.1f} ms, {res['scored_triples_per_s'] / 1e6:.1f} M scored triples/s, "
-            f"remote accesses {100 * res['remote_share']:.2f} %, relocations {st['relocated']}, mean loss {res['mean_loss']:.4f}")
+        log(f"workers {parts} lookahead {lookahead} location caches {caches}: epoch {dt * 1e3:.1f} ms, "
+            f"{res['scored_triples_per_s'] / 1e6:.1f} M scored triples/s, remote accesses {100 * res['remote_share']:.2f} %, "
+            f"relocations {st['relocated']}, messages of remote accesses {msgs} (entries correct {st['cache_hit']}, stale {st['cache_stale']}), "
+            f"mean loss {res['mean_loss']:.4f}")
         del srv, data
     print(json.dumps({"metric": "knowledge-graph epoch over workers", "unit": "s", "n_gpus": 1, "dtype": "f32", "data": "synthetic",
                       "config": {"workload": "complex_kge_epoch", "entities": w.num_entities, "relations": w.num_relations,

@@ -63,6 +63,8 @@ enum {
     PS_STAT_LOCALIZE_KEYS,      /* keys passed to localize, moved or not */
     PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY,
     PS_STAT_MSG_LOC_REQ, PS_STAT_MSG_LOC_INSTRUCT, PS_STAT_MSG_LOC_TRANSFER,
+    PS_STAT_CACHE_HIT, PS_STAT_CACHE_STALE,   /* remote accesses routed by a correct / a stale location cache entry
+                                                 (PS_OPT_LOCATION_CACHES) */
     PS_STAT_COUNT
 };
 
@@ -83,13 +85,25 @@ enum {
                                    against a sequential server).  0 (default): see ps_push */
     PS_OPT_MF_TEAM_MAX = 8,     /* grouped SGD kernel: the most wavefronts that take the groups of one long column run
                                    in turn, 1..14 (default 5) */
-    PS_OPT_MF_CLASSIC = 9       /* mf_sgd_epoch as on a classic parameter server (Sec. 2.1, Sec. 4.2, Sec. 4.6): no
+    PS_OPT_MF_CLASSIC = 9,      /* mf_sgd_epoch as on a classic parameter server (Sec. 2.1, Sec. 4.2, Sec. 4.6): no
                                    relocation, no residency - every entry pulls its two keys from the store and
                                    pushes the update terms back, counted as local or remote by the owner map as it
                                    stands, with the messages.  1: the push reads the stored values again (values
                                    are copied out of and back into the server); 2: the rows are updated in place.
                                    0 (default): dynamic parameter allocation.  The values are the same in all
                                    three; honours PS_OPT_MF_EXACT.  A comparison mode: one wavefront per task */
+    PS_OPT_LOCATION_CACHES = 10 /* 1: every node keeps a location cache, key -> node (Sec. 3.3 "Location caching", Fig.
+                                   "routing" (c), (d)), for the message counts of remote pulls and pushes: with a
+                                   correct entry the request goes straight to the owner (2 messages), with a stale
+                                   one to the node named there, on to the home node and on to the owner (4); without
+                                   an entry as without caches (3).  A call is routed with the caches as it finds
+                                   them; afterwards its replies have set the requester's entries for the remote keys
+                                   it mentioned to their owners.  A relocation tells the old owner where the key
+                                   went.  Nothing else changes an entry.  Statistics only: values and owners are
+                                   the same.  Two bytes per node and key (at most 16 GiB: PS_ELIMIT); switching on
+                                   or off empties the caches and synchronizes the device.  While on, mf_sgd_epoch and
+                                   mf_sgd_epoch_handoff return PS_EINVAL: their accesses are local, or go to keys
+                                   at home (classic mode), where an entry changes nothing (Sec. 4.6).  0 (default) */
 };
 
 /* ---- the parameter server (Table "Primitives", Sec. 3.1) ---------------- */

@@ -105,6 +105,7 @@ struct dpaps_ps {
     double *d_sse = nullptr;
     void *kge_ws = nullptr;           // scratch of kge_sgd_step (grows)
     size_t kge_ws_bytes = 0;
+    int16_t *loc = nullptr;           // location caches (PS_OPT_LOCATION_CACHES): W x K, node n's belief where key k is, -1 none
     void *handoff_ws = nullptr;       // column block states and the recorded order of mf_sgd_epoch_handoff (grows)
     size_t handoff_ws_bytes = 0;
     hipStream_t side_stream = nullptr;   // default priority: the localize calls and statistics of kge_sgd_epoch run here

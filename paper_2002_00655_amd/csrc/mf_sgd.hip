@@ -485,6 +485,7 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
     if (!ps || num_strata < 0 || (num_strata > 0 && (!tasks_host || !stratum_ptr_host))) return PS_EINVAL;
     MfData &f = ps->mf;
     if (!f.row) { ps->last_error = "mf_sgd_epoch before mf_load_ratings"; return PS_EINVAL; }
+    if (ps->loc) { ps->last_error = "mf_sgd_epoch does not keep location caches: switch PS_OPT_LOCATION_CACHES off"; return PS_EINVAL; }
     if (num_strata == 0) return PS_OK;
     hipStream_t st = (hipStream_t)stream;
     if (stratum_ptr_host[0] != 0) return PS_EINVAL;
@@ -596,6 +597,7 @@ extern "C" int mf_sgd_epoch_handoff(ps_handle ps, float lr, float lambda, int32_
     if (!ps) return PS_EINVAL;
     MfData &f = ps->mf;
     if (!f.row) { ps->last_error = "mf_sgd_epoch_handoff before mf_load_ratings"; return PS_EINVAL; }
+    if (ps->loc) { ps->last_error = "mf_sgd_epoch_handoff does not keep location caches: switch PS_OPT_LOCATION_CACHES off"; return PS_EINVAL; }
     hipStream_t st = (hipStream_t)stream;
     const int L = ps->L;
     if (f.d_row > ps->W) { ps->last_error = "mf_sgd_epoch_handoff: more row blocks than workers"; return PS_EWORKER; }

@@ -116,18 +116,41 @@ __device__ __forceinline__ void route_key(bool travels, int32_t worker, int32_t 
     lds_count_add(back, &l.count[4]);
 }
 
-// adds count[i] to the statistic which[i] (i < 5), one workgroup's share
-__device__ __forceinline__ void route_lds_flush(RouteLds &l, u64 *stats, int w0, int w1, int w2, int w3, int w4) {
+// adds count[i] to the statistic which[i] (i < 7; -1: none), one workgroup's share
+__device__ __forceinline__ void route_lds_flush(RouteLds &l, u64 *stats, int w0, int w1, int w2, int w3, int w4, int w5 = -1, int w6 = -1) {
     __syncthreads();
-    const int which[5] = {w0, w1, w2, w3, w4};
-    if (threadIdx.x < 5 && l.count[threadIdx.x] != 0) atomicAdd(&stat_slot(stats)[which[threadIdx.x]], (u64)l.count[threadIdx.x]);
+    const int which[7] = {w0, w1, w2, w3, w4, w5, w6};
+    if (threadIdx.x < 7 && which[threadIdx.x] >= 0 && l.count[threadIdx.x] != 0)
+        atomicAdd(&stat_slot(stats)[which[threadIdx.x]], (u64)l.count[threadIdx.x]);
+}
+
+// One key that `worker` reads or writes remotely: home h, owner o, c = what the worker's node's location cache says
+// (Sec. 3.3 "Location caching"; -1: no entry, or no caches).  No entry: request to the home node, which forwards
+// to the owner, which replies.  Correct entry: request straight to the owner.  Stale entry: request to the node
+// named, which forwards to the home node, which forwards to the owner (double-forward).  Grouped per call like
+// route_key: one request per node asked, one forward per (from, to), one reply per owner.
+// count[2..4]: request, forward, reply; count[5], count[6]: accesses with a correct / a stale entry.
+__device__ __forceinline__ void route_access_key(bool remote, int32_t worker, int32_t h, int32_t o, int32_t c, int32_t W,
+                                                 uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, RouteLds &l) {
+    const bool hit = remote && c == o, stale = remote && c >= 0 && c != o;
+    const int32_t asked = hit ? o : (stale ? c : h);
+    const bool req = stamp_first(remote && asked != worker, stamp_h, asked, call_id, l.seen_h, SEEN_H - 1);
+    const bool fresh1 = stamp_first(stale, stamp_pair, c * W + h, call_id, l.seen_pair, SEEN_PAIR - 1);
+    const bool fresh2 = stamp_first(remote && !hit, stamp_pair, h * W + o, call_id, l.seen_pair, SEEN_PAIR - 1);
+    const bool back = stamp_first(remote, stamp_o, o, call_id, l.seen_o, SEEN_H - 1);
+    lds_count_add(req, &l.count[2]);
+    lds_count_add(fresh1 && c != h, &l.count[3]);
+    lds_count_add(fresh2 && h != o, &l.count[3]);
+    lds_count_add(back, &l.count[4]);
+    lds_count_add(hit, &l.count[5]);
+    lds_count_add(stale, &l.count[6]);
 }
 
 // Locality statistics and message counts of one pull or push call.
 __global__ __launch_bounds__(256) void k_route_access(const int64_t *keys, int64_t n, int32_t worker, const int32_t *owner, int64_t per_home,
                                                        int32_t W, uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id,
                                                        u64 *stats, int stat_local, int stat_remote, int stat_local2, int stat_remote2,
-                                                       const int32_t *err) {
+                                                       const int16_t *loc_row, const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
     __shared__ RouteLds l;
     route_lds_init(l);
@@ -140,19 +163,33 @@ __global__ __launch_bounds__(256) void k_route_access(const int64_t *keys, int64
         const bool local = active && o == worker, remote = active && o != worker;
         lds_count_add(local, &l.count[0]);
         lds_count_add(remote, &l.count[1]);
-        route_key(remote, worker, (int32_t)(k / per_home), o, W, stamp_h, stamp_o, stamp_pair, call_id, l);
+        const int32_t c = remote && loc_row ? (int32_t)loc_row[k] : -1;       // this node's location cache, if there are caches
+        route_access_key(remote, worker, (int32_t)(k / per_home), o, c, W, stamp_h, stamp_o, stamp_pair, call_id, l);
     }
-    route_lds_flush(l, stats, stat_local, stat_remote, PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY);
+    route_lds_flush(l, stats, stat_local, stat_remote, PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY, PS_STAT_CACHE_HIT,
+                    PS_STAT_CACHE_STALE);
     // a second access to the same keys by the same worker right after (a pull and a push of one step) has the
     // same locality and sends the same messages once more
+    // (only without location caches: with them the first access's replies change how the second is routed)
     if (stat_local2 >= 0) route_lds_flush(l, stats, stat_local2, stat_remote2, PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY);
+}
+
+// The replies of a pull or push have arrived: the requester's node knows the owner of every remote key it asked
+// for (Sec. 3.3: the caches change without messages of their own).  Several mentions of a key write the same.
+__global__ void k_cache_replies(const int64_t *keys, int64_t n, int32_t worker, const int32_t *owner, int16_t *loc_row, const int32_t *err) {
+    if (*(volatile const int32_t *)err) return;
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    const int64_t k = keys[p];
+    const int32_t o = owner[k];
+    if (o != worker) loc_row[k] = (int16_t)o;
 }
 
 // localize: the home node updates the location at once (Sec. 3.2, step 1); the
 // exchange makes exactly one of several mentions of a key the one that moves it.
 __global__ __launch_bounds__(256) void k_localize(const int64_t *keys, int64_t n, int32_t worker, int32_t *owner, int64_t per_home, int32_t W,
                                                    uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, u64 *stats,
-                                                   const int32_t *err) {
+                                                   int16_t *loc, int64_t K, const int32_t *err) {
     if (*(volatile const int32_t *)err) return;
     __shared__ RouteLds l;
     route_lds_init(l);
@@ -166,6 +203,7 @@ __global__ __launch_bounds__(256) void k_localize(const int64_t *keys, int64_t n
         int32_t old = worker;
         if (active && __hip_atomic_load(&owner[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != worker) old = atomicExch(&owner[k], worker);
         const bool moved = active && old != worker;
+        if (moved && loc) loc[(int64_t)old * K + k] = (int16_t)worker;     // the old owner hands the value over: it knows where to
         lds_count_add(active, &l.count[0]);
         lds_count_add(moved, &l.count[1]);
         route_key(moved, worker, (int32_t)(k / per_home), old, W, stamp_h, stamp_o, stamp_pair, call_id, l);
@@ -396,6 +434,7 @@ extern "C" int ps_destroy(ps_handle ps) {
     if (ps->ws) (void)hipFree(ps->ws);
     if (ps->kge_ws) (void)hipFree(ps->kge_ws);
     if (ps->handoff_ws) (void)hipFree(ps->handoff_ws);
+    if (ps->loc) (void)hipFree(ps->loc);
     if (ps->side_stream) (void)hipStreamDestroy(ps->side_stream);
     if (ps->ev_fork) (void)hipEventDestroy(ps->ev_fork);
     if (ps->ev_join) (void)hipEventDestroy(ps->ev_join);
@@ -425,11 +464,20 @@ static uint32_t next_call_id(dpaps_ps *ps, hipStream_t st) {
 static int route_access(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, int st_local, int st_remote,
                         hipStream_t st, int st_local2 = -1, int st_remote2 = -1) {
     if (worker < 0 || n == 0) return PS_OK;
+    if (ps->loc && st_local2 >= 0) {      // with location caches the second access is routed after the first one's replies
+        const int rc = route_access(ps, worker, keys, n, st_local, st_remote, st);
+        return rc ? rc : route_access(ps, worker, keys, n, st_local2, st_remote2, st);
+    }
     uint32_t id = next_call_id(ps, st);
+    int16_t *loc_row = ps->loc ? ps->loc + (int64_t)worker * ps->K : nullptr;
     k_route_access<<<route_grid(ps, n), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
                                                      ps->stamp_o, ps->stamp_pair, id, ps->stats, st_local, st_remote,
-                                                     st_local2, st_remote2, ps->err);
+                                                     st_local2, st_remote2, loc_row, ps->err);
     PS_HIP(ps, hipGetLastError());
+    if (loc_row) {
+        k_cache_replies<<<grid_for(n, 256), 256, 0, st>>>(keys, n, worker, ps->owner, loc_row, ps->err);
+        PS_HIP(ps, hipGetLastError());
+    }
     return PS_OK;
 }
 
@@ -525,7 +573,7 @@ int dpaps_localize_checked(dpaps_ps *ps, const int64_t *keys, int64_t n, int32_t
     if (n == 0) return PS_OK;
     uint32_t id = next_call_id(ps, st);
     k_localize<<<route_grid(ps, n), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
-                                                 ps->stamp_o, ps->stamp_pair, id, ps->stats, ps->err);
+                                                 ps->stamp_o, ps->stamp_pair, id, ps->stats, ps->loc, ps->K, ps->err);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
 }
@@ -542,7 +590,7 @@ extern "C" int ps_localize(ps_handle ps, const int64_t *keys, int64_t n, int32_t
     if (rc) return rc;
     uint32_t id = next_call_id(ps, st);
     k_localize<<<route_grid(ps, n), 256, 0, st>>>(keys, n, worker, ps->owner, ps->per_home, ps->W, ps->stamp_h,
-                                                 ps->stamp_o, ps->stamp_pair, id, ps->stats, ps->err);
+                                                 ps->stamp_o, ps->stamp_pair, id, ps->stats, ps->loc, ps->K, ps->err);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
 }
@@ -600,6 +648,19 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
     case PS_OPT_MF_GROUPED: ps->opt_grouped = value != 0; return PS_OK;
     case PS_OPT_PUSH_SEQUENTIAL: ps->opt_push_sequential = value != 0; return PS_OK;
     case PS_OPT_MF_CLASSIC: if (value < 0 || value > 2) return PS_EINVAL; ps->opt_classic = (int)value; return PS_OK;
+    case PS_OPT_LOCATION_CACHES: {
+        // one entry of two bytes per node and key (-1: none); switching on or off empties them
+        PS_HIP(ps, hipDeviceSynchronize());
+        if (ps->loc) { PS_HIP(ps, hipFree(ps->loc)); ps->loc = nullptr; }
+        if (value != 0) {
+            const size_t bytes = (size_t)ps->W * (size_t)ps->K * sizeof(int16_t);
+            if (bytes > ((size_t)16 << 30)) { ps->last_error = "location caches: nodes x keys x 2 bytes exceeds 16 GiB"; return PS_ELIMIT; }
+            PS_HIP(ps, hipMalloc(&ps->loc, bytes));
+            PS_HIP(ps, hipMemset(ps->loc, 0xFF, bytes));
+            PS_HIP(ps, hipDeviceSynchronize());
+        }
+        return PS_OK;
+    }
     case PS_OPT_MF_TEAM_MAX: if (value < 1 || value > 14) return PS_EINVAL; ps->opt_team_max = (int)value; return PS_OK;
     case PS_OPT_MF_HEAVY_LEN:
         if (value < 1 || value > (1 << 30)) return PS_EINVAL;
