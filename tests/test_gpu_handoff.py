@@ -66,6 +66,40 @@ def test_epoch_with_handoff_matches_replay(name, scale, d_row, d_col, workers, e
     assert abs(np.sqrt(sse_gpu / w.nnz) - np.sqrt(sse / w.nnz)) <= 1e-5 * np.sqrt(sse / w.nnz)
 
 
+def test_empty_and_one_wide_blocks():
+    """Block boundaries that leave some row blocks and column blocks empty or one index wide: an empty block is
+    still taken, localized (nothing to relocate) and given back."""
+    from oracle.oracle import mf_block_ratings
+    w = wl.make_mf("tiny", scale=0.5, seed=8)
+    d_row, d_col = 6, 9
+    rb = np.sort(np.concatenate([[0, w.m], np.random.default_rng(1).integers(0, w.m, d_row - 1)])).astype(np.int64)
+    rb[2] = rb[1]                                                      # an empty row block
+    cb = np.sort(np.concatenate([[0, w.n], np.random.default_rng(2).integers(0, 3, d_col - 1)])).astype(np.int64)
+    print(f"case ragged rows {rb.tolist()} columns {cb.tolist()}", flush=True)
+    blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    srv = _server(w, rb, cb, blocked, d_row)
+    orders = [srv.mf_sgd_epoch_handoff(w.lr, w.lam) for _ in range(2)]
+    srv.status()
+    for order in orders:
+        check_handoff_order(order)
+    compare_state(_oracle(w, rb, cb, blocked, d_row, orders), srv, exact=False)
+
+
+def test_single_worker_and_single_column_block():
+    from oracle.oracle import mf_block_ratings
+    w = wl.make_mf("tiny", scale=0.2, seed=3)
+    for d_row, d_col in ((1, 5), (4, 1), (1, 1)):
+        rb, cb = wl.equal_bounds(w.m, d_row), wl.equal_bounds(w.n, d_col)
+        blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+        srv = _server(w, rb, cb, blocked, d_row)
+        order = srv.mf_sgd_epoch_handoff(w.lr, w.lam)
+        srv.status()
+        check_handoff_order(order)
+        if d_row == 1:
+            assert order[0, :, 0].tolist() == list(range(d_col))      # alone, a worker takes the column blocks in cyclic order
+        compare_state(_oracle(w, rb, cb, blocked, d_row, [order]), srv, exact=False)
+
+
 def test_uncached_columns_and_rank_not_multiple_of_four():
     """Column factors that do not fit in LDS are handed over through memory inside a block as well; rank 50 is
     read in 4-byte pieces."""
