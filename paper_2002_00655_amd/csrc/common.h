@@ -81,6 +81,8 @@ struct dpaps_ps {
     // growable scratch for ps_push
     void *ws = nullptr;
     size_t ws_bytes = 0;
+    int64_t push_sorted_n = -1;       // what dpaps_push_sort left in ws for dpaps_push_add: number of pairs,
+    size_t push_off_pos = 0, push_off_part = 0;   // offsets of the sorted positions and of the partial sums
     // schedule staging for mf_sgd_epoch
     int32_t *d_tasks = nullptr;
     int64_t d_tasks_cap = 0;
@@ -109,7 +111,7 @@ struct dpaps_ps {
     void *handoff_ws = nullptr;       // column block states and the recorded order of mf_sgd_epoch_handoff (grows)
     size_t handoff_ws_bytes = 0;
     hipStream_t side_stream = nullptr;   // default priority: the localize calls and statistics of kge_sgd_epoch run here
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_sorted = nullptr, ev_added = nullptr;
     std::string last_error;
 };
 
@@ -167,6 +169,9 @@ int dpaps_account_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, i
 int dpaps_route_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st);   // without the key check
 int dpaps_localize_checked(dpaps_ps *ps, const int64_t *keys, int64_t n, int32_t worker, hipStream_t st);
 int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *deltas, hipStream_t st);
+int dpaps_push_sort(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st);     // the two halves of dpaps_push_apply
+int dpaps_push_add(dpaps_ps *ps, int64_t n, const float *deltas, hipStream_t st);
+int dpaps_check_keys(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st);     // the key check of the dpaps_account_* calls
 
 int dpaps_fail_hip(dpaps_ps *ps, hipError_t e, const char *what);
 int dpaps_ws_reserve(dpaps_ps *ps, size_t bytes);

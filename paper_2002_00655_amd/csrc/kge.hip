@@ -21,9 +21,10 @@
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
 
 // the key occurrences of the batch, in push order: triple of the batch, then positive /
-// subject-negatives / object-negatives, then role (subject, relation, object)
+// subject-negatives / object-negatives, then role (subject, relation, object); and, if asked for, the keys of
+// the update rows (per positive triple: subject, relation, object, subject negatives, object negatives)
 __global__ void k_kge_keys(int64_t num_entities, int64_t batch, const int32_t *subj, const int32_t *rel, const int32_t *obj,
-                           int32_t ns, const int32_t *neg_subj, int32_t no, const int32_t *neg_obj, int64_t *keys) {
+                           int32_t ns, const int32_t *neg_subj, int32_t no, const int32_t *neg_obj, int64_t *keys, int64_t *upd_keys) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // scored triple
     const int32_t per = 1 + ns + no;
     if (t >= batch * per) return;
@@ -35,6 +36,11 @@ __global__ void k_kge_keys(int64_t num_entities, int64_t batch, const int32_t *s
     keys[3 * t + 0] = s;
     keys[3 * t + 1] = num_entities + rel[b];
     keys[3 * t + 2] = o;
+    if (upd_keys) {
+        int64_t *u = upd_keys + b * (3 + ns + no);
+        if (j == 0) { u[0] = s; u[1] = num_entities + rel[b]; u[2] = o; }
+        else u[2 + j] = j <= ns ? s : o;                               // the entity that replaced subject or object
+    }
 }
 
 // AdaGrad with the occurrence's own gradient g and the accumulator G as pulled:
@@ -55,7 +61,7 @@ __device__ __forceinline__ Upd adagrad(float g, float G, float lr, float eps) {
 // point's push has one row per key slot - subject, relation, object, every negative - instead
 // of one per occurrence.
 //   loss = log(1 + exp(-label score)),  g = dloss/dscore * dscore/dtheta
-// rows: (3 + ns + no) per positive triple in upd and in upd_keys.  1 + ns + no <= 64.
+// rows: (3 + ns + no) per positive triple in upd and in upd_keys (NULL: the caller has the keys already).  1 + ns + no <= 64.
 template <int NC>
 __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_entities, int32_t D, const int32_t *subj, const int32_t *rel,
                                                     const int32_t *obj, int32_t ns, const int32_t *neg_subj, int32_t no,
@@ -69,7 +75,7 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
     const int64_t ks = subj[b], kr = num_entities + rel[b], ko = obj[b];
     const float *vs = store + ks * L, *vr = store + kr * L, *vo = store + ko * L;
     float *u0 = upd + b * rows * L;
-    if (lane == 0) { upd_keys[b * rows + 0] = ks; upd_keys[b * rows + 1] = kr; upd_keys[b * rows + 2] = ko; }
+    if (lane == 0 && upd_keys) { upd_keys[b * rows + 0] = ks; upd_keys[b * rows + 1] = kr; upd_keys[b * rows + 2] = ko; }
     float sr[NC], si[NC], rr[NC], ri[NC], orl[NC], oi[NC];
     float score = 0.0f;                                              // lane t: score of scored triple t
     {
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
         const bool subject = j < ns;
         const int64_t kn = subject ? neg_subj[b * ns + j] : neg_obj[b * no + (j - ns)];
         const float *vn = store + kn * L;
-        if (lane == 0) upd_keys[b * rows + 3 + j] = kn;
+        if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + j] = kn;
         float pn = 0.0f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -218,6 +224,18 @@ __global__ __launch_bounds__(256) void k_kge_loss_sum(const double *loss, int64_
     if (threadIdx.x == 0) *out = s[0];
 }
 
+// the library's second stream (default priority) and the two events that tie it to the caller's
+static int kge_side_stream(dpaps_ps *ps) {
+    if (!ps->side_stream) {
+        PS_HIP(ps, hipStreamCreateWithFlags(&ps->side_stream, hipStreamNonBlocking));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_fork, hipEventDisableTiming));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_join, hipEventDisableTiming));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_sorted, hipEventDisableTiming));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_added, hipEventDisableTiming));
+    }
+    return PS_OK;
+}
+
 extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, int32_t dim, int64_t batch, const int32_t *subj,
                             const int32_t *rel, const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj,
                             int32_t n_neg_obj, const int32_t *neg_obj, float lr, float eps, double *loss_host_out, void *stream) {
@@ -251,13 +269,26 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     int64_t *ukeys = (int64_t *)((char *)ps->kge_ws + off_ukeys);
     float *upd = (float *)((char *)ps->kge_ws + off_upd);
     double *loss = (double *)((char *)ps->kge_ws + off_loss);
-    k_kge_keys<<<grid_for(ntr, 256), 256, 0, st>>>(num_entities, batch, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, keys);
+    k_kge_keys<<<grid_for(ntr, 256), 256, 0, st>>>(num_entities, batch, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, keys, ukeys);
     PS_HIP(ps, hipGetLastError());
-    int rc = dpaps_account_pull_push(ps, worker, keys, nocc, st);       // every occurrence is pulled, and pushed below
+    int rc = dpaps_check_keys(ps, keys, nocc, st);                      // before anything indexes the store with them
     if (rc) return rc;
+    // What needs the keys only - the statistics of the pull and of the push (every occurrence is pulled, and pushed
+    // below) and the sort of the push - runs on the library's second stream beside the kernel that computes the
+    // update rows; the two meet again before the rows are added.
+    rc = kge_side_stream(ps);
+    if (rc) return rc;
+    hipStream_t bs = ps->side_stream;
+    PS_HIP(ps, hipEventRecord(ps->ev_fork, st));
+    PS_HIP(ps, hipStreamWaitEvent(bs, ps->ev_fork, 0));
+    rc = dpaps_route_pull_push(ps, worker, keys, nocc, bs);
+    if (rc) return rc;
+    rc = dpaps_push_sort(ps, ukeys, rows, bs);
+    if (rc) return rc;
+    PS_HIP(ps, hipEventRecord(ps->ev_join, bs));
     const unsigned blocks = grid_for(batch * 64, 256);
 #define KGE_GROUP(NC) k_kge_group<NC><<<blocks, 256, 0, st>>>(batch, num_entities, dim, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, \
-                                                              lr, eps, ps->val, upd, ukeys, loss, ps->err)
+                                                              lr, eps, ps->val, upd, nullptr, loss, ps->err)
     switch ((dim + 63) / 64) {
     case 1: KGE_GROUP(1); break;
     case 2: KGE_GROUP(2); break;
@@ -266,7 +297,8 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     }
 #undef KGE_GROUP
     PS_HIP(ps, hipGetLastError());
-    rc = dpaps_push_apply(ps, ukeys, rows, upd, st);
+    PS_HIP(ps, hipStreamWaitEvent(st, ps->ev_join, 0));
+    rc = dpaps_push_add(ps, rows, upd, st);
     if (rc) return rc;
     if (loss_host_out) {
         k_kge_loss_sum<<<1, 256, 0, st>>>(loss, batch, loss + batch);
@@ -342,10 +374,9 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
     const int64_t bmax = std::min(batch, longest);
     if (3 * bmax * per >= ((int64_t)1 << 31) || longest * ent >= ((int64_t)1 << 31)) return PS_ELIMIT;
     hipStream_t vs = (hipStream_t)stream;                  // the work on the values
-    if (!ps->side_stream) {
-        PS_HIP(ps, hipStreamCreateWithFlags(&ps->side_stream, hipStreamNonBlocking));
-        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_fork, hipEventDisableTiming));
-        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_join, hipEventDisableTiming));
+    {
+        const int rc = kge_side_stream(ps);
+        if (rc) return rc;
     }
     hipStream_t bs = ps->side_stream;                      // localize calls and statistics: owner map and counters only
     // scratch: occurrence keys and localize keys (second stream), update rows, their keys and the losses (first)
@@ -396,6 +427,7 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
         for (int32_t w = 0; w < num_parts && !rc; ++w)                // the first batch's entities
             rc = localize_entities(part_ptr_host[w], std::min(part_ptr_host[w] + batch, part_ptr_host[w + 1]), w);
     }
+    int64_t steps_done = 0;
     for (int64_t r = 0; r * batch < longest && !rc; ++r) {
         for (int32_t w = 0; w < num_parts && !rc; ++w) {
             const int64_t t0 = part_ptr_host[w] + r * batch, end = part_ptr_host[w + 1];
@@ -405,14 +437,19 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
             if (lookahead && t1 < end) rc = localize_entities(t1, std::min(t1 + batch, end), w);
             if (rc) break;
             k_kge_keys<<<grid_for(nb * per, 256), 256, 0, bs>>>(num_entities, nb, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no,
-                                                                neg_obj + t0 * no, okeys);
+                                                                neg_obj + t0 * no, okeys, ukeys);
             PS_HIP(ps, hipGetLastError());
             rc = dpaps_route_pull_push(ps, w, okeys, 3 * nb * per, bs);
             if (rc) break;
+            // ... and the push's sort, which needs the keys only, once the previous step's sums have read theirs
+            if (steps_done > 0) PS_HIP(ps, hipStreamWaitEvent(bs, ps->ev_added, 0));
+            rc = dpaps_push_sort(ps, ukeys, nb * (3 + ns + no), bs);
+            if (rc) break;
+            PS_HIP(ps, hipEventRecord(ps->ev_sorted, bs));
             // first stream: the values
             const unsigned blocks = grid_for(nb * 64, 256);
 #define KGE_GROUP(NC) k_kge_group<NC><<<blocks, 256, 0, vs>>>(nb, num_entities, dim, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no, \
-                                                              neg_obj + t0 * no, lr, eps, ps->val, upd, ukeys, loss, ps->err)
+                                                              neg_obj + t0 * no, lr, eps, ps->val, upd, nullptr, loss, ps->err)
             switch ((dim + 63) / 64) {
             case 1: KGE_GROUP(1); break;
             case 2: KGE_GROUP(2); break;
@@ -421,8 +458,11 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
             }
 #undef KGE_GROUP
             PS_HIP(ps, hipGetLastError());
-            rc = dpaps_push_apply(ps, ukeys, nb * (3 + ns + no), upd, vs);
+            PS_HIP(ps, hipStreamWaitEvent(vs, ps->ev_sorted, 0));
+            rc = dpaps_push_add(ps, nb * (3 + ns + no), upd, vs);
             if (rc) break;
+            PS_HIP(ps, hipEventRecord(ps->ev_added, vs));
+            ++steps_done;
             if (loss_host_out) {
                 k_kge_loss_add<<<1, 256, 0, vs>>>(loss, nb, loss_acc);
                 PS_HIP(ps, hipGetLastError());

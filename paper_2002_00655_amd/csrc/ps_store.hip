@@ -438,6 +438,8 @@ extern "C" int ps_destroy(ps_handle ps) {
     if (ps->side_stream) (void)hipStreamDestroy(ps->side_stream);
     if (ps->ev_fork) (void)hipEventDestroy(ps->ev_fork);
     if (ps->ev_join) (void)hipEventDestroy(ps->ev_join);
+    if (ps->ev_sorted) (void)hipEventDestroy(ps->ev_sorted);
+    if (ps->ev_added) (void)hipEventDestroy(ps->ev_added);
     if (ps->d_tasks) (void)hipFree(ps->d_tasks);
     for (hipEvent_t e : ps->ev_pool) (void)hipEventDestroy(e);
     delete ps;
@@ -451,6 +453,8 @@ static int launch_check(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_
     }
     return PS_OK;
 }
+
+int dpaps_check_keys(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st) { return launch_check(ps, keys, n, st); }
 
 static uint32_t next_call_id(dpaps_ps *ps, hipStream_t st) {
     if (++ps->call_id == 0) {   // wrapped: forget all stamps
@@ -523,8 +527,10 @@ int dpaps_account_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, i
     return route_access(ps, worker, keys, n, PS_STAT_PULL_LOCAL, PS_STAT_PULL_REMOTE, st, PS_STAT_PUSH_LOCAL, PS_STAT_PUSH_REMOTE);
 }
 
-// the adding itself, for keys that have been checked (the kernels do nothing once the error flag is set)
-int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *deltas, hipStream_t st) {
+// The adding itself, for keys that have been checked (the kernels do nothing once the error flag is set), in two
+// halves: the sort, which needs the keys only (a step that computes its update rows meanwhile runs it beside that
+// work), and the sums, which need the rows.  The sorted pairs stay in the handle's scratch between the two.
+int dpaps_push_sort(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st) {
     // stable sort of (key, position) by key; the positions come from a counting iterator
     int key_bits = 1;
     while (key_bits < 63 && ((int64_t)1 << key_bits) < ps->K) ++key_bits;
@@ -543,6 +549,17 @@ int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *
     float *part = (float *)((char *)ps->ws + off_part);
     void *tmp = (char *)ps->ws + off_tmp;
     PS_HIP(ps, rocprim::radix_sort_pairs<push_sort_config>(tmp, temp_bytes, kin, skeys, iota, spos, (size_t)n, 0, key_bits, st));
+    ps->push_sorted_n = n; ps->push_off_pos = off_pos; ps->push_off_part = off_part;
+    (void)part;
+    return PS_OK;
+}
+
+int dpaps_push_add(dpaps_ps *ps, int64_t n, const float *deltas, hipStream_t st) {
+    if (n != ps->push_sorted_n) { ps->last_error = "push: the sums do not follow their sort"; return PS_EINVAL; }
+    const int64_t nranges = (n + PUSH_RANGE - 1) / PUSH_RANGE;
+    const uint64_t *skeys = (const uint64_t *)ps->ws;
+    const uint32_t *spos = (const uint32_t *)((char *)ps->ws + ps->push_off_pos);
+    float *part = (float *)((char *)ps->ws + ps->push_off_part);
     if (ps->opt_push_sequential) {
         k_push_apply<<<grid_for(n * 64, 256), 256, 0, st>>>(skeys, spos, n, ps->L, deltas, ps->val, ps->err);
         PS_HIP(ps, hipGetLastError());
@@ -555,6 +572,11 @@ int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *
         PS_HIP(ps, hipGetLastError());
     }
     return PS_OK;
+}
+
+int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *deltas, hipStream_t st) {
+    const int rc = dpaps_push_sort(ps, keys, n, st);
+    return rc ? rc : dpaps_push_add(ps, n, deltas, st);
 }
 
 extern "C" int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, const float *deltas, void *stream) {
