@@ -58,6 +58,7 @@ struct MfData {
     uint32_t *team_plan = nullptr;    // 16 words per block: which heavy runs each wavefront takes (built on first use)
     int team_plan_waves = 0;          // the number of heavy wavefronts it was built for
     int64_t num_gstart = 0;
+    int32_t max_run_groups = 0;       // most groups of any heavy run
     // block geometry
     int64_t *row_bounds = nullptr;    // device copy, d_row + 1
     int64_t *col_bounds = nullptr;    // device copy, d_col + 1

@@ -395,6 +395,14 @@ __global__ void k_run_groups(const int64_t *run_start, const uint32_t *blk, cons
     if (fill) gstart[gptr[r] + ng] = (int32_t)(s1 - s0); else cnt[r] = ng + 1;
 }
 
+// out = max(out, the largest of src[0 .. n)) (out starts at zero)
+__global__ void k_max_u32(const uint32_t *src, int64_t n, uint32_t *out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t v = i < n ? src[i] : 0u;
+    for (int off = 32; off > 0; off >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, off));
+    if ((threadIdx.x & 63) == 0 && v > 0) atomicMax(out, v);
+}
+
 __global__ void k_widen_u32(const uint32_t *src, int64_t n, int64_t last, int64_t *dst) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[i]; else if (i == n) dst[i] = last;
@@ -624,8 +632,13 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
         HIPRC(rocprim::exclusive_scan(tmp, tmp_scan, head, scan, 0u, (size_t)num_runs, rocprim::plus<uint32_t>(), st));
         HIPRC(hipMemcpyAsync(&h_tail[0], scan + (num_runs - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         HIPRC(hipMemcpyAsync(&h_tail[1], head + (num_runs - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        // the most groups of any run (head[r] = groups + 1 of a heavy run), into the error word, which is zero here
+        uint32_t h_max = 0;
+        k_max_u32<<<grid_for(num_runs, 256), 256, 0, st>>>(head, num_runs, reinterpret_cast<uint32_t *>(d_err));
+        HIPRC(hipMemcpyAsync(&h_max, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         HIPRC(hipStreamSynchronize(st));
         f.num_gstart = (int64_t)h_tail[0] + h_tail[1];
+        f.max_run_groups = h_max > 0 ? (int32_t)(h_max - 1) : 0;
     }
     HIPRC(hipMalloc(&f.gstart, std::max<int64_t>(f.num_gstart, 1) * sizeof(int32_t)));
     k_widen_u32<<<grid_for(num_runs + 1, 256), 256, 0, st>>>(scan, num_runs, f.num_gstart, f.run_gptr);

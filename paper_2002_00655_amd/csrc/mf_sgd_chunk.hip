@@ -48,6 +48,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #define CH 15                    // entries per group (the 16th row of X is the column's row)
 #define AUX_SC1 16               // cache policy of a buffer access: agent scope
+#define DPAPS_LONG_RUN_GROUPS 64 // data with a column run of at least this many groups in a block: see the recurrence
 
 // value of `v` in lane `src` (any permutation; goes through the LDS crossbar, no memory)
 __device__ __forceinline__ int bperm_i(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }
@@ -62,7 +63,8 @@ __device__ __forceinline__ float bperm_f(float v, int src) {
 // reads what this one wrote, without a write-back or an invalidation of whole caches (the row factors need none
 // of that: they stay with this workgroup).  Off: plain accesses; the kernel's end publishes everything.
 // One call processes the block (rb, cb) for `worker`; all threads of the workgroup take part.
-template <int NT, bool A4, bool AGENT_H>
+// LONG_RUNS: the variant of the recurrence for data with column runs of very many groups (see there).
+template <int NT, bool A4, bool AGENT_H, bool LONG_RUNS>
 __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const int32_t worker, const int32_t rb, const int32_t cb) {
     if constexpr (!AGENT_H) {     // (in the loop, the caller looks: there all threads must take the same way)
         if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
@@ -331,7 +333,8 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                 const float v_row = bperm_f(c_val, n16);
                 // table entries for the new h, read before the wait as well
                 const int pw_h = k - 1 - n16;
-                const float cpow_h = cpow[pw_h > 0 ? pw_h : 0], cpm1_k = cpm1[k];
+                const float cpm1_k = cpm1[k];
+                const float coef_h = n16 < k ? lr * cpow[pw_h > 0 ? pw_h : 0] : 0.0f;   // lane s: lr c^(k-1-s), what e_s w_s weighs in the new h
                 // this lane's quarter of row n16, for the inner products with h below: fetched before the wait
                 f32x4 xr[NT];
 #pragma unroll
@@ -340,7 +343,7 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
 
                 // ---- the part that needs h as the previous group left it --------------------------------
                 for (uint32_t spins = 0; ticket_read(hsq) != (uint32_t)gi;) {
-                    __builtin_amdgcn_s_sleep(1);
+                    if constexpr (!LONG_RUNS) __builtin_amdgcn_s_sleep(1);     // (where runs are very long, the wait is all there is)
                     if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
                         ticket_write(&give_up, 1u);
                         atomicExch(a.err, PS_ESTALL);
@@ -350,6 +353,10 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                 compiler_fence();
                 // from here to the hand-over every other wavefront of the team waits for this one
                 __builtin_amdgcn_s_setprio(3);
+                // p_s = <w_s, h>: every lane its quarter of row n16 (four partial sums), then the four quarters together
+                f32x4 hq[NT];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) hq[j] = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
                 // h as it is now, lane l its components l, l + 64 (lanes past the row's 16 NT floats: any)
                 float ho[NV];
                 int ck[NV];
@@ -358,10 +365,6 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                     ck[cc] = ln + 64 * cc < 16 * NT ? ln + 64 * cc : 0;
                     ho[cc] = hsh[ck[cc]];
                 }
-                // p_s = <w_s, h>: every lane its quarter of row n16 (four partial sums), then the four quarters together
-                f32x4 hq[NT];
-#pragma unroll
-                for (int j = 0; j < NT; ++j) hq[j] = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
                 __builtin_amdgcn_sched_barrier(0);      // all of h asked for before the first product waits for its piece
                 float pq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
@@ -387,6 +390,9 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                 // the group's end work on rows of X that are zero and on values that are finite, so what they
                 // compute changes nothing that is used; they are not skipped, to keep the chain free of branches.
                 float e_vec = 0.0f;                        // e_t in every lane with n16 == t
+                float hn[NV];                              // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s
+#pragma unroll
+                for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(cpm1_k, ho[cc], ho[cc]);
 #define DPAPS_REC_STEP(t)                                                       \
                 {                                                               \
                     const float d = v_row - p;                                  \
@@ -394,36 +400,60 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                     e_vec = n16 == t ? d : e_vec;                               \
                     p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p)); \
                 }
-                DPAPS_REC_STEP(0) DPAPS_REC_STEP(1) DPAPS_REC_STEP(2) DPAPS_REC_STEP(3) DPAPS_REC_STEP(4)
-                DPAPS_REC_STEP(5) DPAPS_REC_STEP(6) DPAPS_REC_STEP(7) DPAPS_REC_STEP(8) DPAPS_REC_STEP(9)
-                DPAPS_REC_STEP(10) DPAPS_REC_STEP(11) DPAPS_REC_STEP(12) DPAPS_REC_STEP(13) DPAPS_REC_STEP(14)
-#undef DPAPS_REC_STEP
-                static_assert(CH == 15, "the recurrence above is written out for 15 entries");
-                // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s
-                {
-                    const float a_vec = (n16 < k ? lr * e_vec : 0.0f) * cpow_h;   // lane s < 15: coefficient of w_s
-                    float hn[NV];
-#pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(cpm1_k, ho[cc], ho[cc]);
+                if constexpr (LONG_RUNS) {
+                    // A run of very many groups is bound by this part alone.  There the terms of the new h are added
+                    // along the way, a few steps behind their e_t (the rows' components come from LDS, and the first
+                    // steps must not wait for them), with the coefficient broadcast like e_t: 15 instructions more
+                    // than below, but none of the reads of a lane into a scalar, which stall the vector unit.
+                    float as_[CH];
+#define DPAPS_REC_STEP_H(t)                                                     \
+                    {                                                           \
+                        const float d = v_row - p;                              \
+                        const float e = row_bcast_lane<t>(d);                   \
+                        as_[t] = row_bcast_lane<t>(d * coef_h);                 \
+                        e_vec = n16 == t ? d : e_vec;                           \
+                        p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p)); \
+                    }
+#define DPAPS_H_TERM(t)                                                         \
+                    _Pragma("unroll")                                           \
+                    for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(as_[t], wv[t][cc], hn[cc]);
+                    DPAPS_REC_STEP_H(0) DPAPS_REC_STEP_H(1) DPAPS_REC_STEP_H(2) DPAPS_REC_STEP_H(3)
+                    DPAPS_REC_STEP_H(4) DPAPS_H_TERM(0) DPAPS_REC_STEP_H(5) DPAPS_H_TERM(1) DPAPS_REC_STEP_H(6) DPAPS_H_TERM(2)
+                    DPAPS_REC_STEP_H(7) DPAPS_H_TERM(3) DPAPS_REC_STEP_H(8) DPAPS_H_TERM(4) DPAPS_REC_STEP_H(9) DPAPS_H_TERM(5)
+                    DPAPS_REC_STEP_H(10) DPAPS_H_TERM(6) DPAPS_REC_STEP_H(11) DPAPS_H_TERM(7) DPAPS_REC_STEP_H(12) DPAPS_H_TERM(8)
+                    DPAPS_REC_STEP_H(13) DPAPS_H_TERM(9) DPAPS_REC_STEP_H(14) DPAPS_H_TERM(10)
+                    DPAPS_H_TERM(11) DPAPS_H_TERM(12) DPAPS_H_TERM(13) DPAPS_H_TERM(14)
+#undef DPAPS_REC_STEP_H
+#undef DPAPS_H_TERM
+                } else {
+                    DPAPS_REC_STEP(0) DPAPS_REC_STEP(1) DPAPS_REC_STEP(2) DPAPS_REC_STEP(3) DPAPS_REC_STEP(4)
+                    DPAPS_REC_STEP(5) DPAPS_REC_STEP(6) DPAPS_REC_STEP(7) DPAPS_REC_STEP(8) DPAPS_REC_STEP(9)
+                    DPAPS_REC_STEP(10) DPAPS_REC_STEP(11) DPAPS_REC_STEP(12) DPAPS_REC_STEP(13) DPAPS_REC_STEP(14)
+                    const float a_vec = e_vec * coef_h;                           // lane s < 15: coefficient of w_s
 #pragma unroll
                     for (int s = 0; s < CH; ++s) {
                         const float as = rl_f(a_vec, s);
 #pragma unroll
                         for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(as, wv[s][cc], hn[cc]);
                     }
+                }
+#undef DPAPS_REC_STEP
+                static_assert(CH == 15, "the recurrence above is written out for 15 entries");
+                // the new h is complete: into LDS for the next group, which may start at once
+                {
 #pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) {
-                        const bool exists = ln + 64 * cc < L;
-                        if (exists) hsh[ln + 64 * cc] = hn[cc];
-                        if constexpr (AGENT_H)   // written through to memory, and only as the run leaves it
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf,
-                                                                  (int)(exists && gi + 1 == ng ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan), 0, AUX_SC1);
-                        else
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf,
-                                                                  (int)(exists ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan), 0, 0);
-                    }
+                    for (int cc = 0; cc < NV; ++cc)
+                        if (ln + 64 * cc < L) hsh[ln + 64 * cc] = hn[cc];
                     compiler_fence();
                     ticket_write(hsq, (uint32_t)gi + 1u);
+                    compiler_fence();
+                    // to memory as the run's last group leaves it (an offset past the end writes nothing)
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) {
+                        const int off = (int)(ln + 64 * cc < L && gi + 1 == ng ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan);
+                        if constexpr (AGENT_H) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf, off, 0, AUX_SC1);
+                        else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf, off, 0, 0);
+                    }
                     __builtin_amdgcn_s_setprio(2);
                 }
                 // read ahead: the rows of this wavefront's next group, the per-entry data of the one after (not
@@ -658,10 +688,10 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
 // One workgroup per task of a stratum.
 // MAXT: the largest workgroup the kernel is compiled for (12 wavefronts leave each of them a third more registers
 // than 16 do, which the first part needs)
-template <int NT, bool A4, int MAXT>
+template <int NT, bool A4, int MAXT, bool LONG_RUNS>
 __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
-    sgd_block<NT, A4, false>(a, lds_f, a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1], a.tasks[3 * blockIdx.x + 2]);
+    sgd_block<NT, A4, false, LONG_RUNS>(a, lds_f, a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1], a.tasks[3 * blockIdx.x + 2]);
 }
 
 // ---- an epoch without barriers: column blocks handed from worker to worker ----------------------------------
@@ -703,7 +733,7 @@ __device__ __forceinline__ int handoff_take(const SgdArgs &a, const uint32_t *to
     }
 }
 
-template <int NT, bool A4>
+template <int NT, bool A4, bool LONG_RUNS>
 __global__ __launch_bounds__(1024) void k_mf_sgd_handoff(SgdArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     __shared__ uint32_t todo[DPAPS_HANDOFF_MAX_COLS / 32];
@@ -733,7 +763,7 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_handoff(SgdArgs a) {
         const int cb = __builtin_amdgcn_readfirstlane(s_cb);          // the same in all lanes: block addresses stay scalar
         const int visit = __builtin_amdgcn_readfirstlane(s_visit);
         if (cb < 0) break;
-        sgd_block<NT, A4, true>(a, lds_f, worker, worker, cb);
+        sgd_block<NT, A4, true, LONG_RUNS>(a, lds_f, worker, worker, cb);
         // every store of this wavefront has reached memory before the barrier, every wavefront's before the release
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -768,25 +798,27 @@ static int plan_block_lds(dpaps_ps *ps, SgdArgs &a, size_t *lds_out) {
     return PS_OK;
 }
 
-template <int NT, bool A4, int MAXT>
+template <int NT, bool A4, int MAXT, bool LONG_RUNS>
 static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
     size_t lds = 0;
     const int rc = plan_block_lds<NT>(ps, a, &lds);
     if (rc) return rc;
     static size_t configured = 0;
     if (lds > configured) {
-        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_chunk<NT, A4, MAXT>),
+        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_chunk<NT, A4, MAXT, LONG_RUNS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = lds;
     }
-    k_mf_sgd_chunk<NT, A4, MAXT><<<ntasks, 64 * waves, lds, st>>>(a);
+    k_mf_sgd_chunk<NT, A4, MAXT, LONG_RUNS><<<ntasks, 64 * waves, lds, st>>>(a);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
 }
 
 template <int NT, bool A4>
 static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
-    return waves <= 12 ? launch_chunk_t<NT, A4, 768>(ps, a, ntasks, waves, st) : launch_chunk_t<NT, A4, 1024>(ps, a, ntasks, waves, st);
+    if (ps->mf.max_run_groups >= DPAPS_LONG_RUN_GROUPS)
+        return waves <= 12 ? launch_chunk_t<NT, A4, 768, true>(ps, a, ntasks, waves, st) : launch_chunk_t<NT, A4, 1024, true>(ps, a, ntasks, waves, st);
+    return waves <= 12 ? launch_chunk_t<NT, A4, 768, false>(ps, a, ntasks, waves, st) : launch_chunk_t<NT, A4, 1024, false>(ps, a, ntasks, waves, st);
 }
 
 // The plan of a block: word w of its 16 = run_first | run_last << 8 | T << 16 | mb << 24 for heavy wavefront w
@@ -819,20 +851,26 @@ __global__ void k_team_plan(const int64_t *blk_run_ptr, const int32_t *blk_nheav
     for (; w < 16; ++w) plan[b * 16 + w] = 0;
 }
 
-template <int NT, bool A4>
-static int launch_handoff(dpaps_ps *ps, SgdArgs a, int workers, hipStream_t st) {
+template <int NT, bool A4, bool LONG_RUNS>
+static int launch_handoff_t(dpaps_ps *ps, SgdArgs a, int workers, hipStream_t st) {
     size_t lds = 0;
     const int rc = plan_block_lds<NT>(ps, a, &lds);
     if (rc) return rc;
     static size_t configured = 0;
     if (lds > configured) {
-        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_handoff<NT, A4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        PS_HIP(ps, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mf_sgd_handoff<NT, A4, LONG_RUNS>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds));
         configured = lds;
     }
-    k_mf_sgd_handoff<NT, A4><<<workers, 1024, lds, st>>>(a);
+    k_mf_sgd_handoff<NT, A4, LONG_RUNS><<<workers, 1024, lds, st>>>(a);
     PS_HIP(ps, hipGetLastError());
     return PS_OK;
+}
+
+template <int NT, bool A4>
+static int launch_handoff(dpaps_ps *ps, SgdArgs a, int workers, hipStream_t st) {
+    return ps->mf.max_run_groups >= DPAPS_LONG_RUN_GROUPS ? launch_handoff_t<NT, A4, true>(ps, a, workers, st)
+                                                          : launch_handoff_t<NT, A4, false>(ps, a, workers, st);
 }
 
 // how the wavefronts of a workgroup share the heavy runs: with 12 or more wavefronts, 12 (14 of 16) of them take

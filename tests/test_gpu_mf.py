@@ -223,6 +223,17 @@ def test_wide_shape_scaled():
     _config_parity(w, 256, epochs=1)
 
 
+def test_very_long_column_runs():
+    """Columns with half of all rows, few row blocks: column runs of 2,500 entries (167 groups) in a block, which the
+    grouped kernel takes with the variant of its recurrence for runs of 64 groups and more."""
+    w = wl.make_mf("wide", scale=0.002)
+    d = 4
+    counts = np.bincount(w.cols, minlength=w.n)
+    print(f"case wide@0.002 {w.m} x {w.n} nnz={w.nnz} longest column {counts.max()}", flush=True)
+    assert counts.max() // d >= 64 * 15
+    _config_parity(w, d, epochs=2)
+
+
 @pytest.mark.parametrize("rank,waves,grouped", [(1, 16, 1), (16, 3, 1), (50, 16, 1), (64, 8, 1), (100, 16, 1), (100, 1, 1), (128, 16, 1),
                                                 (100, 16, 0), (50, 4, 0), (130, 16, 1)])
 def test_normal_arithmetic_both_kernels(rank, waves, grouped):
