@@ -62,11 +62,15 @@ __global__ void k_check_keys(const int64_t *keys, int64_t n, int64_t K, int32_t 
 // destination; a workgroup remembers in LDS which destinations it has already settled, so that device-wide
 // operations on the few hot stamp words stay rare.
 constexpr int ROUTE_BLOCKS_PER_CU = 2;
-constexpr int SEEN_H = 256, SEEN_PAIR = 1024;          // direct-mapped: entry holds idx + 1 of a settled destination
+constexpr int NODE_WORDS = 2048 / 32;                  // one bit per node (at most 2048 workers)
+constexpr int PAIR_BITS = 1 << 16;                     // one bit per (from, to) pair where W x W fits (W <= 256) ...
+constexpr int SEEN_PAIR = 1024;                        // ... else direct-mapped: entry holds idx + 1 of a settled pair
 
 struct RouteLds {
     uint32_t count[8];
-    uint32_t seen_h[SEEN_H], seen_o[SEEN_H], seen_pair[SEEN_PAIR];
+    uint32_t bits_h[NODE_WORDS], bits_o[NODE_WORDS];   // nodes this workgroup has settled as request / reply destinations
+    uint32_t bits_pair[PAIR_BITS / 32];
+    uint32_t seen_pair[SEEN_PAIR];
 };
 
 __device__ __forceinline__ void route_lds_init(RouteLds &l) {
@@ -101,16 +105,44 @@ __device__ __forceinline__ bool stamp_first(bool want, uint32_t *stamps, int32_t
     return first;
 }
 
+// The same where every idx has a bit of its own in LDS: the lane that sets the bit settles idx for the workgroup,
+// no matter how many different destinations the lanes of a wavefront name (with hundreds of nodes and keys drawn at
+// random that is nearly one each, and the loop above goes round once per destination).
+__device__ __forceinline__ bool stamp_first_bit(bool want, uint32_t *stamps, int32_t idx, uint32_t call_id, uint32_t *bits) {
+    bool first = false;
+    if (want) {
+        const uint32_t m = 1u << (idx & 31);
+        if ((atomicOr(&bits[idx >> 5], m) & m) == 0u &&
+            __hip_atomic_load(&stamps[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != call_id)
+            first = atomicExch(&stamps[idx], call_id) != call_id;
+    }
+    return first;
+}
+__device__ __forceinline__ bool stamp_first_pair(bool want, uint32_t *stamp_pair, int32_t from, int32_t to, int32_t W, uint32_t call_id,
+                                                 RouteLds &l) {
+    if (W * W <= PAIR_BITS) return stamp_first_bit(want, stamp_pair, from * W + to, call_id, l.bits_pair);
+    return stamp_first(want, stamp_pair, from * W + to, call_id, l.seen_pair, SEEN_PAIR - 1);
+}
+
+// home node of key k: k / per_home without the 64-bit division (double has 53 bits, keys and per_home fewer; the
+// quotient estimate is off by at most one)
+__device__ __forceinline__ int32_t home_node(int64_t k, int64_t per_home, double inv_per_home) {
+    int64_t h = (int64_t)((double)k * inv_per_home);
+    if (h * per_home > k) --h;
+    else if ((h + 1) * per_home <= k) ++h;
+    return (int32_t)h;
+}
+
 // One key that must travel for requester `worker`: home h, current owner o.
 // Within one call the messages to one destination are grouped (Sec. 3.7); the
 // stamps record which destinations this call has already been charged for.
 // count[2..4]: request, forward, reply (or their localize counterparts).
 __device__ __forceinline__ void route_key(bool travels, int32_t worker, int32_t h, int32_t o, int32_t W,
                                           uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, RouteLds &l) {
-    const bool req = stamp_first(travels && h != worker, stamp_h, h, call_id, l.seen_h, SEEN_H - 1);
-    const bool fresh = stamp_first(travels, stamp_pair, h * W + o, call_id, l.seen_pair, SEEN_PAIR - 1);
+    const bool req = stamp_first_bit(travels && h != worker, stamp_h, h, call_id, l.bits_h);
+    const bool fresh = stamp_first_pair(travels, stamp_pair, h, o, W, call_id, l);
     const bool fwd = fresh && (h != o);
-    const bool back = stamp_first(travels && o != worker, stamp_o, o, call_id, l.seen_o, SEEN_H - 1);
+    const bool back = stamp_first_bit(travels && o != worker, stamp_o, o, call_id, l.bits_o);
     lds_count_add(req, &l.count[2]);
     lds_count_add(fwd, &l.count[3]);
     lds_count_add(back, &l.count[4]);
@@ -134,10 +166,10 @@ __device__ __forceinline__ void route_access_key(bool remote, int32_t worker, in
                                                  uint32_t *stamp_h, uint32_t *stamp_o, uint32_t *stamp_pair, uint32_t call_id, RouteLds &l) {
     const bool hit = remote && c == o, stale = remote && c >= 0 && c != o;
     const int32_t asked = hit ? o : (stale ? c : h);
-    const bool req = stamp_first(remote && asked != worker, stamp_h, asked, call_id, l.seen_h, SEEN_H - 1);
-    const bool fresh1 = stamp_first(stale, stamp_pair, c * W + h, call_id, l.seen_pair, SEEN_PAIR - 1);
-    const bool fresh2 = stamp_first(remote && !hit, stamp_pair, h * W + o, call_id, l.seen_pair, SEEN_PAIR - 1);
-    const bool back = stamp_first(remote, stamp_o, o, call_id, l.seen_o, SEEN_H - 1);
+    const bool req = stamp_first_bit(remote && asked != worker, stamp_h, asked, call_id, l.bits_h);
+    const bool fresh1 = stamp_first_pair(stale, stamp_pair, c, h, W, call_id, l);
+    const bool fresh2 = stamp_first_pair(remote && !hit, stamp_pair, h, o, W, call_id, l);
+    const bool back = stamp_first_bit(remote, stamp_o, o, call_id, l.bits_o);
     lds_count_add(req, &l.count[2]);
     lds_count_add(fresh1 && c != h, &l.count[3]);
     lds_count_add(fresh2 && h != o, &l.count[3]);
@@ -154,6 +186,7 @@ __global__ __launch_bounds__(256) void k_route_access(const int64_t *keys, int64
     if (*(volatile const int32_t *)err) return;
     __shared__ RouteLds l;
     route_lds_init(l);
+    const double inv_per_home = 1.0 / (double)per_home;
     const int64_t step = (int64_t)gridDim.x * blockDim.x;
     for (int64_t base = (int64_t)blockIdx.x * blockDim.x; base < n; base += step) {     // whole workgroups walk together
         const int64_t p = base + threadIdx.x;
@@ -164,7 +197,7 @@ __global__ __launch_bounds__(256) void k_route_access(const int64_t *keys, int64
         lds_count_add(local, &l.count[0]);
         lds_count_add(remote, &l.count[1]);
         const int32_t c = remote && loc_row ? (int32_t)loc_row[k] : -1;       // this node's location cache, if there are caches
-        route_access_key(remote, worker, (int32_t)(k / per_home), o, c, W, stamp_h, stamp_o, stamp_pair, call_id, l);
+        route_access_key(remote, worker, home_node(k, per_home, inv_per_home), o, c, W, stamp_h, stamp_o, stamp_pair, call_id, l);
     }
     route_lds_flush(l, stats, stat_local, stat_remote, PS_STAT_MSG_ACC_REQ, PS_STAT_MSG_ACC_FWD, PS_STAT_MSG_ACC_REPLY, PS_STAT_CACHE_HIT,
                     PS_STAT_CACHE_STALE);
@@ -193,6 +226,7 @@ __global__ __launch_bounds__(256) void k_localize(const int64_t *keys, int64_t n
     if (*(volatile const int32_t *)err) return;
     __shared__ RouteLds l;
     route_lds_init(l);
+    const double inv_per_home = 1.0 / (double)per_home;
     const int64_t step = (int64_t)gridDim.x * blockDim.x;
     for (int64_t base = (int64_t)blockIdx.x * blockDim.x; base < n; base += step) {
         const int64_t p = base + threadIdx.x;
@@ -206,7 +240,7 @@ __global__ __launch_bounds__(256) void k_localize(const int64_t *keys, int64_t n
         if (moved && loc) loc[(int64_t)old * K + k] = (int16_t)worker;     // the old owner hands the value over: it knows where to
         lds_count_add(active, &l.count[0]);
         lds_count_add(moved, &l.count[1]);
-        route_key(moved, worker, (int32_t)(k / per_home), old, W, stamp_h, stamp_o, stamp_pair, call_id, l);
+        route_key(moved, worker, home_node(k, per_home, inv_per_home), old, W, stamp_h, stamp_o, stamp_pair, call_id, l);
     }
     route_lds_flush(l, stats, PS_STAT_LOCALIZE_KEYS, PS_STAT_RELOCATED, PS_STAT_MSG_LOC_REQ, PS_STAT_MSG_LOC_INSTRUCT, PS_STAT_MSG_LOC_TRANSFER);
 }
