@@ -408,7 +408,7 @@ def main() -> int:
     log(f"{kernel_name}: {launches} launches, avg {avg_launch_s * 1e6:.1f} us, model {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
 
     # pull + push rows per second through the C ABI (uniform random keys, value_len = rank)
-    n_keys = 1 << 20
+    n_keys = 1 << 22
     g = torch.Generator(device=dev); g.manual_seed(0)
     keys = torch.randint(0, w.m + w.n, (n_keys,), device=dev, generator=g)
     deltas = torch.zeros((n_keys, w.rank), device=dev)
@@ -429,7 +429,7 @@ def main() -> int:
                    "bounds": args.bounds, "col_cost": args.col_cost, "lr": w.lr, "lambda": w.lam, "waves": args.waves, "kernel": kernel_name},
         "model_gbs": updates_per_s * bytes_per_update / 1e9,
         "model_frac_of_hbm_peak": updates_per_s * bytes_per_update / 1e9 / HBM_PEAK_GBS,
-        "pull_push_rows_per_s": rows_per_s,
+        "pull_push_rows_per_s": rows_per_s, "pull_push_keys_per_call": n_keys,
         "setup_ms": {"generate_host": t_gen * 1e3, "block_ratings": t_block * 1e3, "load_ratings": t_load * 1e3},
         "train_rmse": [rmse0, rmse1],
         "roofline": roofline,
