@@ -261,12 +261,50 @@ def equal_bounds(size: int, d: int) -> np.ndarray:
     return (np.arange(d + 1, dtype=np.int64) * size) // d
 
 
+def _split_by_weight(cum: np.ndarray, lo: int, hi: int, parts: int) -> np.ndarray:
+    """Inner boundaries (parts - 1 of them) that cut indices [lo, hi) into `parts` stretches of roughly equal weight;
+    cum[i] = weight of the indices before i."""
+    targets = cum[lo] + np.arange(1, parts, dtype=np.float64) * ((cum[hi] - cum[lo]) / parts)
+    b = lo + np.searchsorted(cum[lo:hi + 1], targets, side="left")
+    return np.clip(b, lo, hi).astype(np.int64)
+
+
 def balanced_bounds(ids: np.ndarray, size: int, d: int, per_id: float = 0.0) -> np.ndarray:
     """Contiguous ranges holding roughly equal numbers of entries each.  per_id > 0: ranges of roughly equal
     weight, where an index weighs its number of entries plus per_id (for blocks whose processing time has a
-    part per row or column on top of the part per entry)."""
+    part per row or column on top of the part per entry).  An index with more entries than an average range has
+    gets a range of its own - next to anything else it would only make the heaviest range heavier -, and the
+    other ranges are dealt out to the stretches between such indices in proportion to their weights."""
     deg = np.bincount(ids, minlength=size).astype(np.float64) + float(per_id)
     cum = np.concatenate([[0], np.cumsum(deg)])
+    solo = np.flatnonzero(deg - float(per_id) > ids.size / d)          # by entries alone, whatever else weighs
+    if solo.size:
+        # the stretches between the heavy indices, and how many ranges each gets: one each, the rest by weight
+        starts = np.concatenate([[0], solo + 1])
+        ends = np.concatenate([solo, [size]])
+        nonempty = ends > starts
+        spare = d - solo.size - int(nonempty.sum())
+        if spare >= 0:
+            weight = np.where(nonempty, cum[ends] - cum[starts], 0.0)
+            share = weight / weight.sum() * spare if weight.sum() > 0 else np.zeros(starts.size)
+            parts = np.floor(share).astype(np.int64)
+            order = np.argsort(-(share - parts), kind="stable")
+            order = order[nonempty[order]]
+            left = spare - int(parts.sum())
+            for j in range(left if order.size else 0):     # (more than one round only if stretches weigh nothing)
+                parts[order[j % order.size]] += 1
+            parts[nonempty] += 1
+            firsts = []                                    # first index of every range, in order
+            for k in range(starts.size):
+                if nonempty[k]:
+                    firsts.append(np.array([starts[k]], dtype=np.int64))
+                    firsts.append(_split_by_weight(cum, int(starts[k]), int(ends[k]), int(parts[k])))
+                if k < solo.size:
+                    firsts.append(np.array([solo[k]], dtype=np.int64))
+            out = np.concatenate(firsts + [np.array([size], dtype=np.int64)])
+            if out.size == d + 1:
+                return out
+        # (too few ranges to set every heavy index apart: cut by weight alone)
     targets = np.arange(d + 1, dtype=np.float64) * (cum[-1] / d)
     b = np.searchsorted(cum, targets, side="left").astype(np.int64)
     b[0], b[-1] = 0, size

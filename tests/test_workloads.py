@@ -25,6 +25,33 @@ def test_bounds_cover_the_range_and_balanced_ones_balance():
         assert np.abs(wl.balanced_bounds(ids, size, d, per_id=1e9) - eq).max() <= 1
 
 
+def test_balanced_bounds_set_heavy_indices_apart():
+    """An index with more entries than an average range has gets a range of its own; every range is non-empty and the
+    others share what is left evenly; with too few ranges for that the plain cut by weight is used."""
+    rng = np.random.default_rng(0)
+    size, d = 1000, 16
+    deg = rng.integers(1, 50, size=size)
+    heavy = [0, 1, 500, 999]
+    deg[heavy] = [5000, 4000, 9000, 7000]
+    ids = np.repeat(np.arange(size), deg)
+    for per_id in (0.0, 3.0):
+        b = wl.balanced_bounds(ids, size, d, per_id=per_id)
+        assert b[0] == 0 and b[-1] == size and b.size == d + 1 and np.all(np.diff(b) > 0)
+        for h in heavy:
+            assert h in b and h + 1 in b
+        per_range = np.add.reduceat(deg, b[:-1])
+        rest = np.array([x for x, lo in zip(per_range, b[:-1]) if lo not in heavy])
+        # the stretches between the heavy indices get whole numbers of ranges: alike within a few per cent
+        assert rest.max() <= 1.15 * rest.min()
+    # three indices with all the entries and four ranges: no way to set them all apart
+    ids3 = np.repeat([0, 5, 9], [100, 100, 100])
+    b = wl.balanced_bounds(ids3, 10, 4)
+    assert b[0] == 0 and b[-1] == 10 and b.size == 5 and np.all(np.diff(b) >= 0)
+    # ... with eight there is: each alone, the stretches between them cut further
+    b = wl.balanced_bounds(ids3, 10, 8)
+    assert b.size == 9 and all(x in b for x in (0, 1, 5, 6, 9, 10)) and np.all(np.diff(b) >= 0)
+
+
 def test_schedules_are_strata():
     rng = np.random.default_rng(0)
     for sched in (wl.cyclic_schedule(6), wl.random_schedule(6, rng)):
