@@ -65,7 +65,8 @@ __device__ __forceinline__ Upd adagrad(float g, float G, float lr, float eps) {
 template <int NC>
 __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_entities, int32_t D, const int32_t *subj, const int32_t *rel,
                                                     const int32_t *obj, int32_t ns, const int32_t *neg_subj, int32_t no,
-                                                    const int32_t *neg_obj, float lr, float eps, const float *store, float *upd,
+                                                    const int32_t *neg_obj, float lr, float eps, const float *__restrict__ store,
+                                                    float *__restrict__ upd,
                                                     int64_t *upd_keys, double *loss, const int32_t *err) {
     if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     const int lane = threadIdx.x & 63;
@@ -132,6 +133,19 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
     }
     // the running sums of the subject's, the relation's and the object's updates, started by the positive triple
     float as_t[NC][2], as_g[NC][2], ar_t[NC][2], ar_g[NC][2], ao_t[NC][2], ao_g[NC][2];
+    // the accumulators of subject, relation and object as pulled: read once, used by every triple they occur in
+    float Gs[NC][2], Gr[NC][2], Go[NC][2];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int k = lane + 64 * c;
+        const bool in = k < D;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            Gs[c][p] = in ? vs[2 * D + p * D + k] : 0.0f;
+            Gr[c][p] = in ? vr[2 * D + p * D + k] : 0.0f;
+            Go[c][p] = in ? vo[2 * D + p * D + k] : 0.0f;
+        }
+    }
     {
         const float dl = rl_f(dlv, 0);
 #pragma unroll
@@ -143,9 +157,9 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
                                    {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
-                const Upd us = adagrad(g[0][p], in ? vs[2 * D + p * D + k] : 0.0f, lr, eps);
-                const Upd ur = adagrad(g[1][p], in ? vr[2 * D + p * D + k] : 0.0f, lr, eps);
-                const Upd uo = adagrad(g[2][p], in ? vo[2 * D + p * D + k] : 0.0f, lr, eps);
+                const Upd us = adagrad(g[0][p], Gs[c][p], lr, eps);
+                const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
+                const Upd uo = adagrad(g[2][p], Go[c][p], lr, eps);
                 as_t[c][p] = us.dt; as_g[c][p] = us.dg; ar_t[c][p] = ur.dt; ar_g[c][p] = ur.dg; ao_t[c][p] = uo.dt; ao_g[c][p] = uo.dg;
             }
         }
@@ -167,9 +181,9 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
             for (int p = 0; p < 2; ++p) {
                 const Upd un_ = adagrad(g[0][p], vn[2 * D + p * D + k], lr, eps);
                 un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
-                const Upd ur = adagrad(g[1][p], vr[2 * D + p * D + k], lr, eps);
+                const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
                 ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
-                const Upd uo = adagrad(g[2][p], vo[2 * D + p * D + k], lr, eps);
+                const Upd uo = adagrad(g[2][p], Go[c][p], lr, eps);
                 ao_t[c][p] = ao_t[c][p] + uo.dt; ao_g[c][p] = ao_g[c][p] + uo.dg;
             }
         }
@@ -189,9 +203,9 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
                                    {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
-                const Upd us = adagrad(g[0][p], vs[2 * D + p * D + k], lr, eps);
+                const Upd us = adagrad(g[0][p], Gs[c][p], lr, eps);
                 as_t[c][p] = as_t[c][p] + us.dt; as_g[c][p] = as_g[c][p] + us.dg;
-                const Upd ur = adagrad(g[1][p], vr[2 * D + p * D + k], lr, eps);
+                const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
                 ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
                 const Upd un_ = adagrad(g[2][p], vn[2 * D + p * D + k], lr, eps);
                 un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
