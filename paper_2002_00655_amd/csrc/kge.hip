@@ -94,45 +94,14 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
         const float sc = wave_sum(part);
         score = lane == 0 ? sc : score;
     }
-    for (int j = 0; j < ns + no; ++j) {                             // the negatives: subject or object replaced by n
-        const bool subject = j < ns;
-        const int64_t kn = subject ? neg_subj[b * ns + j] : neg_obj[b * no + (j - ns)];
-        const float *vn = store + kn * L;
-        if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + j] = kn;
-        float pn = 0.0f;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int k = lane + 64 * c;
-            const bool in = k < D;
-            const float nr = in ? vn[k] : 0.0f, ni = in ? vn[D + k] : 0.0f;
-            pn += subject ? nr * rr[c] * orl[c] + ni * rr[c] * oi[c] + nr * ri[c] * oi[c] - ni * ri[c] * orl[c]
-                          : sr[c] * rr[c] * nr + si[c] * rr[c] * ni + sr[c] * ri[c] * ni - si[c] * ri[c] * nr;
-        }
-        const float sc = wave_sum(pn);
-        score = lane == 1 + j ? sc : score;
-    }
-    // loss and dloss/dscore of all scored triples at once (lane t: triple t; the positive one is triple 0)
-    float dlv;
-    {
-        const float label = lane == 0 ? 1.0f : -1.0f;
-        const float z = -label * score;
-        // sigmoid(z) and log(1 + exp(z)), written so that neither overflows
-        const double en = exp((double)(z >= 0.0f ? -z : z));
-        const float ex = (float)en;
+    // dloss/dscore of one scored triple (the same value in every lane): -label sigmoid(-label score), written so that
+    // nothing overflows, the exponential in double as in the oracle
+    auto dloss = [](float label, float sc) {
+        const float z = -label * sc;
+        const float ex = (float)exp((double)(z >= 0.0f ? -z : z));
         const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
-        const double ls = z >= 0.0f ? (double)z + log1p(en) : log1p(en);
-        dlv = -label * sig;
-        double loss_sum = 0.0;
-        for (int t = 0; t < 1 + ns + no; ++t) {
-            const uint64_t bits = __builtin_bit_cast(uint64_t, ls);
-            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, t);
-            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(bits >> 32), t);
-            loss_sum += __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-        }
-        if (lane == 0) loss[b] = loss_sum;
-    }
-    // the running sums of the subject's, the relation's and the object's updates, started by the positive triple
-    float as_t[NC][2], as_g[NC][2], ar_t[NC][2], ar_g[NC][2], ao_t[NC][2], ao_g[NC][2];
+        return -label * sig;
+    };
     // the accumulators of subject, relation and object as pulled: read once, used by every triple they occur in
     float Gs[NC][2], Gr[NC][2], Go[NC][2];
 #pragma unroll
@@ -146,12 +115,12 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
             Go[c][p] = in ? vo[2 * D + p * D + k] : 0.0f;
         }
     }
+    // the running sums of the subject's, the relation's and the object's updates, started by the positive triple
+    float as_t[NC][2], as_g[NC][2], ar_t[NC][2], ar_g[NC][2], ao_t[NC][2], ao_g[NC][2];
     {
-        const float dl = rl_f(dlv, 0);
+        const float dl = dloss(1.0f, rl_f(score, 0));
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            const int k = lane + 64 * c;
-            const bool in = k < D;
             const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
                                    {dl * (sr[c] * orl[c] + si[c] * oi[c]), dl * (sr[c] * oi[c] - si[c] * orl[c])},
                                    {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
@@ -164,22 +133,37 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
             }
         }
     }
+    // The negatives, each in one go - its row (values and accumulators) is asked for at once, then its score, the
+    // derivative of its loss, its own update row and its terms for the two keys it shares with the positive triple.
     // subject replaced by n: the triple (n, r, o), label -1
     for (int j = 0; j < ns; ++j) {
-        const float *vn = store + (int64_t)neg_subj[b * ns + j] * L;
+        const int64_t kn = neg_subj[b * ns + j];
+        const float *vn = store + kn * L;
         float *un = u0 + (int64_t)(3 + j) * L;
-        const float dl = rl_f(dlv, 1 + j);
+        if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + j] = kn;
+        float nr[NC], ni[NC], Gn[NC][2];
+        float pn = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int k = lane + 64 * c;
+            const bool in = k < D;
+            nr[c] = in ? vn[k] : 0.0f; ni[c] = in ? vn[D + k] : 0.0f;
+            Gn[c][0] = in ? vn[2 * D + k] : 0.0f; Gn[c][1] = in ? vn[3 * D + k] : 0.0f;
+            pn += nr[c] * rr[c] * orl[c] + ni[c] * rr[c] * oi[c] + nr[c] * ri[c] * oi[c] - ni[c] * ri[c] * orl[c];
+        }
+        const float sc = wave_sum(pn);
+        score = lane == 1 + j ? sc : score;
+        const float dl = dloss(-1.0f, sc);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const int k = lane + 64 * c;
             if (k >= D) continue;
-            const float nr = vn[k], ni = vn[D + k];
             const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
-                                   {dl * (nr * orl[c] + ni * oi[c]), dl * (nr * oi[c] - ni * orl[c])},
-                                   {dl * (nr * rr[c] - ni * ri[c]), dl * (ni * rr[c] + nr * ri[c])}};
+                                   {dl * (nr[c] * orl[c] + ni[c] * oi[c]), dl * (nr[c] * oi[c] - ni[c] * orl[c])},
+                                   {dl * (nr[c] * rr[c] - ni[c] * ri[c]), dl * (ni[c] * rr[c] + nr[c] * ri[c])}};
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
-                const Upd un_ = adagrad(g[0][p], vn[2 * D + p * D + k], lr, eps);
+                const Upd un_ = adagrad(g[0][p], Gn[c][p], lr, eps);
                 un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
                 const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
                 ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
@@ -190,16 +174,29 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
     }
     // object replaced by n: the triple (s, r, n), label -1
     for (int j = 0; j < no; ++j) {
-        const float *vn = store + (int64_t)neg_obj[b * no + j] * L;
+        const int64_t kn = neg_obj[b * no + j];
+        const float *vn = store + kn * L;
         float *un = u0 + (int64_t)(3 + ns + j) * L;
-        const float dl = rl_f(dlv, 1 + ns + j);
+        if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + ns + j] = kn;
+        float nr[NC], ni[NC], Gn[NC][2];
+        float pn = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int k = lane + 64 * c;
+            const bool in = k < D;
+            nr[c] = in ? vn[k] : 0.0f; ni[c] = in ? vn[D + k] : 0.0f;
+            Gn[c][0] = in ? vn[2 * D + k] : 0.0f; Gn[c][1] = in ? vn[3 * D + k] : 0.0f;
+            pn += sr[c] * rr[c] * nr[c] + si[c] * rr[c] * ni[c] + sr[c] * ri[c] * ni[c] - si[c] * ri[c] * nr[c];
+        }
+        const float sc = wave_sum(pn);
+        score = lane == 1 + ns + j ? sc : score;
+        const float dl = dloss(-1.0f, sc);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const int k = lane + 64 * c;
             if (k >= D) continue;
-            const float nr = vn[k], ni = vn[D + k];
-            const float g[3][2] = {{dl * (rr[c] * nr + ri[c] * ni), dl * (rr[c] * ni - ri[c] * nr)},
-                                   {dl * (sr[c] * nr + si[c] * ni), dl * (sr[c] * ni - si[c] * nr)},
+            const float g[3][2] = {{dl * (rr[c] * nr[c] + ri[c] * ni[c]), dl * (rr[c] * ni[c] - ri[c] * nr[c])},
+                                   {dl * (sr[c] * nr[c] + si[c] * ni[c]), dl * (sr[c] * ni[c] - si[c] * nr[c])},
                                    {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
@@ -207,10 +204,25 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
                 as_t[c][p] = as_t[c][p] + us.dt; as_g[c][p] = as_g[c][p] + us.dg;
                 const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
                 ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
-                const Upd un_ = adagrad(g[2][p], vn[2 * D + p * D + k], lr, eps);
+                const Upd un_ = adagrad(g[2][p], Gn[c][p], lr, eps);
                 un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
             }
         }
+    }
+    // the losses of all scored triples at once (lane t: triple t; the positive one is triple 0)
+    {
+        const float label = lane == 0 ? 1.0f : -1.0f;
+        const float z = -label * score;
+        const double en = exp((double)(z >= 0.0f ? -z : z));
+        const double ls = z >= 0.0f ? (double)z + log1p(en) : log1p(en);
+        double loss_sum = 0.0;
+        for (int t = 0; t < 1 + ns + no; ++t) {
+            const uint64_t bits = __builtin_bit_cast(uint64_t, ls);
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, t);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(bits >> 32), t);
+            loss_sum += __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+        }
+        if (lane == 0) loss[b] = loss_sum;
     }
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
