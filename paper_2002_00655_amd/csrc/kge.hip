@@ -52,14 +52,14 @@ __device__ __forceinline__ Upd adagrad(float g, float G, float lr, float eps) {
 }
 
 // One wavefront per positive triple and its negatives (lane l handles components l, l + 64, ...).
-// First the scores of the 1 + ns + no scored triples from the values as the store holds them
-// (the pull), score t ending up in lane t, so that loss and derivative of all of them are
-// computed in one go.  Then every occurrence's AdaGrad update, where the occurrences of the
-// subject (in the positive triple and the ones with a replaced object), of the relation (in
-// all of them) and of the object (in the positive triple and the ones with a replaced
-// subject) are added up, in the order of the occurrences, before they are pushed: the data
-// point's push has one row per key slot - subject, relation, object, every negative - instead
-// of one per occurrence.
+// The values come from the store as it holds them (the pull).  The positive triple first, then
+// every negative in one go: its row, its score, the derivative of its loss (the same in all
+// lanes), its AdaGrad update.  The occurrences of the subject (in the positive triple and the
+// ones with a replaced object), of the relation (in all of them) and of the object (in the
+// positive triple and the ones with a replaced subject) are added up, in the order of the
+// occurrences, before they are pushed: the data point's push has one row per key slot -
+// subject, relation, object, every negative - instead of one per occurrence.  Score t is also
+// kept in lane t, and the losses of all scored triples are evaluated together at the end.
 //   loss = log(1 + exp(-label score)),  g = dloss/dscore * dscore/dtheta
 // rows: (3 + ns + no) per positive triple in upd and in upd_keys (NULL: the caller has the keys already).  1 + ns + no <= 64.
 template <int NC>
