@@ -299,17 +299,18 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     PS_HIP(ps, hipGetLastError());
     int rc = dpaps_check_keys(ps, keys, nocc, st);                      // before anything indexes the store with them
     if (rc) return rc;
-    // What needs the keys only - the statistics of the pull and of the push (every occurrence is pulled, and pushed
-    // below) and the sort of the push - runs on the library's second stream beside the kernel that computes the
-    // update rows; the two meet again before the rows are added.
+    // What needs the keys only - the sort of the push, and the statistics of the pull and of the push (every
+    // occurrence is pulled, and pushed below) - runs on the library's second stream beside the kernel that computes
+    // the update rows; the sums wait for the sort, the end of the step for the statistics.
     rc = kge_side_stream(ps);
     if (rc) return rc;
     hipStream_t bs = ps->side_stream;
     PS_HIP(ps, hipEventRecord(ps->ev_fork, st));
     PS_HIP(ps, hipStreamWaitEvent(bs, ps->ev_fork, 0));
-    rc = dpaps_route_pull_push(ps, worker, keys, nocc, bs);
-    if (rc) return rc;
     rc = dpaps_push_sort(ps, ukeys, rows, bs);
+    if (rc) return rc;
+    PS_HIP(ps, hipEventRecord(ps->ev_sorted, bs));
+    rc = dpaps_route_pull_push(ps, worker, keys, nocc, bs);
     if (rc) return rc;
     PS_HIP(ps, hipEventRecord(ps->ev_join, bs));
     const unsigned blocks = grid_for(batch * 64, 256);
@@ -323,8 +324,9 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     }
 #undef KGE_GROUP
     PS_HIP(ps, hipGetLastError());
-    PS_HIP(ps, hipStreamWaitEvent(st, ps->ev_join, 0));
+    PS_HIP(ps, hipStreamWaitEvent(st, ps->ev_sorted, 0));
     rc = dpaps_push_add(ps, rows, upd, st);
+    PS_HIP(ps, hipStreamWaitEvent(st, ps->ev_join, 0));
     if (rc) return rc;
     if (loss_host_out) {
         k_kge_loss_sum<<<1, 256, 0, st>>>(loss, batch, loss + batch);
