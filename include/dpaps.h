@@ -204,7 +204,8 @@ int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32_t *stratum
  * gets for worker w and its s-th block, at [2 (w d_col + s)], the column block and, next to it, how many workers
  * had that column block before in this epoch.  The factors, the owner map and the statistics are those of
  * mf_sgd_epoch over strata of one task each, (w, w, column block), in any sequence that agrees with both of
- * these orders - blocks that share neither a row block nor a column block commute.
+ * these orders - blocks that share neither a row block nor a column block commute.  If a deferred error stops the
+ * epoch (see ps_status), the entries of the blocks that were not taken are -1.
  * Runs the grouped kernel only: rank <= 128, PS_OPT_MF_EXACT, PS_OPT_MF_CLASSIC off, PS_OPT_MF_GROUPED on
  * (PS_ELIMIT otherwise), d_col <= 4096.  Scratch is allocated by the library. */
 int mf_sgd_epoch_handoff(ps_handle ps, float lr, float lambda, int32_t *order_host_out, void *stream);
