@@ -116,9 +116,6 @@ struct dpaps_ps {
     std::string last_error;
 };
 
-// Wavefronts of a workgroup that process heavy runs in the grouped SGD kernel (when it has more wavefronts than
-// that); also the largest number of heavy runs of a block.
-#define DPAPS_HEAVY_WAVES 8
 // Heavy runs of a block at most.
 #define DPAPS_HEAVY_MAX 8
 // Column blocks at most in an epoch with hand-over (one bit each in LDS).
@@ -142,7 +139,6 @@ struct SgdArgs {
     const uint32_t *trun_start; const int32_t *trun_row; const uint32_t *trun_wait;
     const uint32_t *t_cinfo; const float *t_val;
     const int64_t *run_gptr; const int32_t *gstart;
-    int32_t sweep;              // 0: every run is processed as a heavy run
     int32_t heavy_waves;        // wavefronts that take heavy runs (each has a staging area in LDS)
     int32_t team;               // 2: the heavy wavefronts follow team_plan; 1: one wavefront per heavy run, in turn
     const uint32_t *team_plan;  // 16 words per block (see k_team_plan)

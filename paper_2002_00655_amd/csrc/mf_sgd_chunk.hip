@@ -773,7 +773,7 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_handoff(SgdArgs a) {
 }
 
 // LDS plan of sgd_block: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters,
-// then as many other column factors as fit.  Fills in a.sweep, a.ctick_cap, a.hcache_cap.
+// then as many other column factors as fit.  Fills in a.ctick_cap, a.hcache_cap.
 template <int NT>
 static int plan_block_lds(dpaps_ps *ps, SgdArgs &a, size_t *lds_out) {
     const MfData &f = ps->mf;
@@ -784,7 +784,6 @@ static int plan_block_lds(dpaps_ps *ps, SgdArgs &a, size_t *lds_out) {
         return PS_ELIMIT;
     }
     if (!f.sweep_ok) { ps->last_error = "the grouped SGD kernel needs rows in ascending order inside the short column runs"; return PS_ELAYOUT; }
-    a.sweep = 1;
     a.ctick_cap = f.max_tail_cols > 1 ? f.max_tail_cols : 1;
     const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 40 + DPAPS_HEAVY_MAX * 16 * NT + DPAPS_HEAVY_MAX) * 4 +
                           ((int64_t)a.ticket_cap + a.ctick_cap) * 4;
