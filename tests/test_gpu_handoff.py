@@ -100,6 +100,28 @@ def test_single_worker_and_single_column_block():
         compare_state(_oracle(w, rb, cb, blocked, d_row, [order]), srv, exact=False)
 
 
+def test_very_long_runs_in_column_blocks_of_their_own():
+    """Columns with half of all rows, 4 row blocks and 256 column ranges cut by `balanced_bounds`: the heaviest columns
+    get ranges of their own, their runs have over a hundred groups (the kernel's variant for very long runs), and
+    there are 64 times more column blocks than workers."""
+    from oracle.oracle import mf_block_ratings
+    w = wl.make_mf("wide", scale=0.002)
+    d_row, d_col = 4, 256
+    rb, cb = wl.balanced_bounds(w.rows, w.m, d_row), wl.balanced_bounds(w.cols, w.n, d_col, per_id=8.0 * d_row)
+    counts = np.bincount(w.cols, minlength=w.n)
+    alone = [int(c) for c in np.flatnonzero(counts > w.nnz / d_col) if c in cb and c + 1 in cb]
+    print(f"case wide@0.002 {d_row}x{d_col}: {len(alone)} columns in ranges of their own, longest run {counts.max() // d_row} entries",
+          flush=True)
+    assert len(alone) >= 10 and counts.max() // d_row >= 64 * 15
+    blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    srv = _server(w, rb, cb, blocked, d_row)
+    orders = [srv.mf_sgd_epoch_handoff(w.lr, w.lam) for _ in range(2)]
+    srv.status()
+    for order in orders:
+        check_handoff_order(order)
+    compare_state(_oracle(w, rb, cb, blocked, d_row, orders), srv, exact=False)
+
+
 def test_uncached_columns_and_rank_not_multiple_of_four():
     """Column factors that do not fit in LDS are handed over through memory inside a block as well; rank 50 is
     read in 4-byte pieces."""
