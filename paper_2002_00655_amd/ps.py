@@ -105,7 +105,7 @@ class ParameterServer:
         self._h = h
 
     def close(self) -> None:
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:       # (at interpreter exit the module's globals may be gone)
             _lib.ps_destroy(self._h)
             self._h = None
 
