@@ -9,7 +9,11 @@
  * call.  `stream` is a hipStream_t (NULL = the null stream).  Calls are
  * asynchronous on that stream and take effect in stream order, which is the
  * program order of one client (Sec. 3.4, "Asynchronous operations"); one
- * handle must not be driven from two streams at once.
+ * handle must not be driven from two streams at once.  Some calls put part of
+ * their work (statistics, a sort) on a second stream that the library creates
+ * at default priority; that work starts after what precedes the call on
+ * `stream` and `stream` waits for it before the call's effects are complete, so
+ * the order seen on `stream` is unchanged.
  *
  * Keys are 0 .. num_keys-1; each key holds a vector of value_len fp32 values
  * (Sec. 4.1 "Settings and measures": "each key held a vector of parameter

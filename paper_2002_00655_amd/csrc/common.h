@@ -170,6 +170,7 @@ int dpaps_push_sort(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st
 int dpaps_push_add(dpaps_ps *ps, int64_t n, const float *deltas, hipStream_t st);
 int dpaps_check_keys(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st);     // the key check of the dpaps_account_* calls
 
+int dpaps_side_stream(dpaps_ps *ps);   // creates the library's second stream and its events on first use
 int dpaps_fail_hip(dpaps_ps *ps, hipError_t e, const char *what);
 int dpaps_ws_reserve(dpaps_ps *ps, size_t bytes);
 

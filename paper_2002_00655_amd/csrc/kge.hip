@@ -250,18 +250,6 @@ __global__ __launch_bounds__(256) void k_kge_loss_sum(const double *loss, int64_
     if (threadIdx.x == 0) *out = s[0];
 }
 
-// the library's second stream (default priority) and the two events that tie it to the caller's
-static int kge_side_stream(dpaps_ps *ps) {
-    if (!ps->side_stream) {
-        PS_HIP(ps, hipStreamCreateWithFlags(&ps->side_stream, hipStreamNonBlocking));
-        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_fork, hipEventDisableTiming));
-        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_join, hipEventDisableTiming));
-        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_sorted, hipEventDisableTiming));
-        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_added, hipEventDisableTiming));
-    }
-    return PS_OK;
-}
-
 extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, int32_t dim, int64_t batch, const int32_t *subj,
                             const int32_t *rel, const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj,
                             int32_t n_neg_obj, const int32_t *neg_obj, float lr, float eps, double *loss_host_out, void *stream) {
@@ -302,7 +290,7 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     // What needs the keys only - the sort of the push, and the statistics of the pull and of the push (every
     // occurrence is pulled, and pushed below) - runs on the library's second stream beside the kernel that computes
     // the update rows; the sums wait for the sort, the end of the step for the statistics.
-    rc = kge_side_stream(ps);
+    rc = dpaps_side_stream(ps);
     if (rc) return rc;
     hipStream_t bs = ps->side_stream;
     PS_HIP(ps, hipEventRecord(ps->ev_fork, st));
@@ -403,7 +391,7 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
     if (3 * bmax * per >= ((int64_t)1 << 31) || longest * ent >= ((int64_t)1 << 31)) return PS_ELIMIT;
     hipStream_t vs = (hipStream_t)stream;                  // the work on the values
     {
-        const int rc = kge_side_stream(ps);
+        const int rc = dpaps_side_stream(ps);
         if (rc) return rc;
     }
     hipStream_t bs = ps->side_stream;                      // localize calls and statistics: owner map and counters only

@@ -488,6 +488,30 @@ static int launch_check(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_
     return PS_OK;
 }
 
+// the library's second stream (default priority) and the events that tie it to the caller's
+int dpaps_side_stream(dpaps_ps *ps) {
+    if (!ps->side_stream) {
+        PS_HIP(ps, hipStreamCreateWithFlags(&ps->side_stream, hipStreamNonBlocking));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_fork, hipEventDisableTiming));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_join, hipEventDisableTiming));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_sorted, hipEventDisableTiming));
+        PS_HIP(ps, hipEventCreateWithFlags(&ps->ev_added, hipEventDisableTiming));
+    }
+    return PS_OK;
+}
+
+// Calls with this many keys or more count their statistics on the second stream, beside the work on the values
+// (below that the two extra waits between streams cost more than the statistics kernel takes).
+constexpr int64_t SIDE_STATS_MIN_KEYS = (int64_t)1 << 20;
+
+// statistics of a large pull or push, started on the second stream once the keys are checked; the caller's stream
+// waits for them when the call's own kernels are queued (dpaps_side_stats_join)
+static int side_stats_fork(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, int st_local, int st_remote, hipStream_t st);
+static int side_stats_join(dpaps_ps *ps, hipStream_t st) {
+    PS_HIP(ps, hipStreamWaitEvent(st, ps->ev_join, 0));
+    return PS_OK;
+}
+
 int dpaps_check_keys(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st) { return launch_check(ps, keys, n, st); }
 
 static uint32_t next_call_id(dpaps_ps *ps, hipStream_t st) {
@@ -519,6 +543,17 @@ static int route_access(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64
     return PS_OK;
 }
 
+static int side_stats_fork(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, int st_local, int st_remote, hipStream_t st) {
+    int rc = dpaps_side_stream(ps);
+    if (rc) return rc;
+    PS_HIP(ps, hipEventRecord(ps->ev_fork, st));
+    PS_HIP(ps, hipStreamWaitEvent(ps->side_stream, ps->ev_fork, 0));
+    rc = route_access(ps, worker, keys, n, st_local, st_remote, ps->side_stream);
+    if (rc) return rc;
+    PS_HIP(ps, hipEventRecord(ps->ev_join, ps->side_stream));
+    return PS_OK;
+}
+
 int dpaps_account_pull(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st) {
     int rc = launch_check(ps, keys, n, st);
     if (rc) return rc;
@@ -530,8 +565,10 @@ extern "C" int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     if (worker < -1 || worker >= ps->W) return PS_EWORKER;
     if (n == 0) return PS_OK;
     hipStream_t st = (hipStream_t)stream;
-    int rc = dpaps_account_pull(ps, worker, keys, n, st);
+    const bool side = worker >= 0 && n >= SIDE_STATS_MIN_KEYS;
+    int rc = side ? launch_check(ps, keys, n, st) : dpaps_account_pull(ps, worker, keys, n, st);
     if (rc) return rc;
+    if (side && (rc = side_stats_fork(ps, worker, keys, n, PS_STAT_PULL_LOCAL, PS_STAT_PULL_REMOTE, st)) != PS_OK) return rc;
     const int64_t pieces = n * (ps->L / 4);
     if (ps->L % 4 == 0 && pieces < ((int64_t)1 << 32) - 256 && ((uintptr_t)out & 15) == 0)
         k_pull_v4<<<grid_for(pieces, 256), 256, 0, st>>>(keys, (uint32_t)pieces, (uint32_t)(ps->L / 4),
@@ -539,7 +576,7 @@ extern "C" int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     else
         k_pull<<<grid_for(n * ps->L, 256), 256, 0, st>>>(keys, n, ps->L, ps->val, out, ps->err);
     PS_HIP(ps, hipGetLastError());
-    return PS_OK;
+    return side ? side_stats_join(ps, st) : PS_OK;
 }
 
 // The library's default switches from a merge sort (two launches per doubling of the sorted length) to passes
@@ -619,9 +656,13 @@ extern "C" int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     if (n >= ((int64_t)1 << 31)) return PS_ELIMIT;
     if (n == 0) return PS_OK;
     hipStream_t st = (hipStream_t)stream;
-    int rc = dpaps_account_push(ps, worker, keys, n, st);
+    const bool side = worker >= 0 && n >= SIDE_STATS_MIN_KEYS;
+    int rc = side ? launch_check(ps, keys, n, st) : dpaps_account_push(ps, worker, keys, n, st);
     if (rc) return rc;
-    return dpaps_push_apply(ps, keys, n, deltas, st);
+    if (side && (rc = side_stats_fork(ps, worker, keys, n, PS_STAT_PUSH_LOCAL, PS_STAT_PUSH_REMOTE, st)) != PS_OK) return rc;
+    rc = dpaps_push_apply(ps, keys, n, deltas, st);
+    if (rc) return rc;
+    return side ? side_stats_join(ps, st) : PS_OK;
 }
 
 // the owner updates and statistics of a localize call, for keys that have been checked

@@ -231,3 +231,34 @@ def test_many_workers_and_a_key_mentioned_a_million_times():
     assert _close_as_fp32(got, orc.pull(np.arange(K), 7), o64.pull(np.arange(K), 7))
     assert np.array_equal(srv.owner().cpu().numpy(), orc.owner())
     assert srv.stats() == orc.stats()
+
+
+@pytest.mark.parametrize("caches", [0, 1])
+def test_calls_of_a_million_keys(caches):
+    """From 2^20 keys on a pull or push counts its statistics on the library's second stream beside the work on the
+    values: same counters, same values, also when small calls and relocations come right before and after."""
+    torch = _torch()
+    from oracle.oracle import Oracle
+    from paper_2002_00655_amd import ps as P
+    K, L, W = 50000, 2, 24
+    n = (1 << 20) + 37
+    rng = np.random.default_rng(7)
+    orc, srv = Oracle("f32", K, L, W), P.ParameterServer(K, L, W)
+    orc.location_caches(bool(caches))
+    srv.set_option(P.OPT_LOCATION_CACHES, caches)
+    dev = torch.device("cuda")
+    for rnd in range(3):
+        few = rng.integers(0, K, size=500)
+        srv.localize(torch.from_numpy(few).to(dev), rnd % W)
+        orc.localize(few, rnd % W)
+        keys = _zipf_keys(rng, K, n) if rnd % 2 else rng.integers(0, K, size=n)
+        kt = torch.from_numpy(np.ascontiguousarray(keys)).to(dev)
+        worker = int(rng.integers(0, W))
+        d = rng.integers(-2, 3, size=(n, L)).astype(np.float32)          # small integers: exact in any order
+        srv.push(kt, torch.from_numpy(d).to(dev), worker)
+        orc.push(keys, d, worker)
+        assert np.array_equal(srv.pull(kt, worker).cpu().numpy(), orc.pull(keys, worker)), rnd
+        srv.pull(kt[:100], (worker + 1) % W)
+        orc.pull(keys[:100], (worker + 1) % W)
+        assert srv.stats() == orc.stats(), rnd
+    assert np.array_equal(srv.owner().cpu().numpy(), orc.owner())
