@@ -122,6 +122,21 @@ def test_very_long_runs_in_column_blocks_of_their_own():
     compare_state(_oracle(w, rb, cb, blocked, d_row, orders), srv, exact=False)
 
 
+def test_many_more_workers_than_column_blocks():
+    """300 workers and 3 column blocks: nearly everybody waits nearly all the time, and a column block's 300 visits
+    are one long chain of hand-overs."""
+    from oracle.oracle import mf_block_ratings
+    w = wl.make_mf("tiny", scale=0.5, seed=12)
+    d_row, d_col = 300, 3
+    rb, cb = wl.equal_bounds(w.m, d_row), wl.equal_bounds(w.n, d_col)
+    blocked = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    srv = _server(w, rb, cb, blocked, d_row)
+    order = srv.mf_sgd_epoch_handoff(w.lr, w.lam)
+    srv.status()
+    check_handoff_order(order)
+    compare_state(_oracle(w, rb, cb, blocked, d_row, [order]), srv, exact=False)
+
+
 def test_uncached_columns_and_rank_not_multiple_of_four():
     """Column factors that do not fit in LDS are handed over through memory inside a block as well; rank 50 is
     read in 4-byte pieces."""
