@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libdpaps.so")
-SOURCES = ["ps_store.hip", "mf_prepare.hip", "mf_sgd.hip", "mf_sgd_chunk.hip", "kge.hip"]
+SOURCES = ["ps_store.hip", "key_sort.hip", "mf_prepare.hip", "mf_sgd.hip", "mf_sgd_chunk.hip", "kge.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

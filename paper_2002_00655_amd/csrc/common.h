@@ -82,8 +82,9 @@ struct dpaps_ps {
     // growable scratch for ps_push
     void *ws = nullptr;
     size_t ws_bytes = 0;
-    int64_t push_sorted_n = -1;       // what dpaps_push_sort left in ws for dpaps_push_add: number of pairs,
-    size_t push_off_pos = 0, push_off_part = 0;   // offsets of the sorted positions and of the partial sums
+    void *push_base = nullptr;        // what the sort of a push left for its sums: the scratch it used,
+    int64_t push_sorted_n = -1;       // the number of pairs,
+    size_t push_off_pos = 0, push_off_part = 0;   // the offsets of the sorted positions and of the partial sums
     // schedule staging for mf_sgd_epoch
     int32_t *d_tasks = nullptr;
     int64_t d_tasks_cap = 0;
@@ -169,6 +170,11 @@ int dpaps_push_apply(dpaps_ps *ps, const int64_t *keys, int64_t n, const float *
 int dpaps_push_sort(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st);     // the two halves of dpaps_push_apply
 int dpaps_push_add(dpaps_ps *ps, int64_t n, const float *deltas, hipStream_t st);
 int dpaps_check_keys(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st);     // the key check of the dpaps_account_* calls
+
+// key_sort.hip: stable sort of (key, position) pairs by key (see there)
+int dpaps_key_bits(int64_t num_keys);
+size_t dpaps_sort_scratch_bytes(int64_t n, int key_bits);
+int dpaps_sort_pairs(dpaps_ps *ps, const int64_t *keys, int64_t n, int key_bits, uint64_t *skeys, uint32_t *spos, void *scratch, hipStream_t st);
 
 int dpaps_side_stream(dpaps_ps *ps);   // creates the library's second stream and its events on first use
 int dpaps_fail_hip(dpaps_ps *ps, hipError_t e, const char *what);

@@ -3,11 +3,6 @@
 // Sec. 3.5, Sec. 3.7 of the paper).
 #include "common.h"
 
-#include <cstring>
-#include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_scan.hpp>
-#include <rocprim/iterator/counting_iterator.hpp>
-
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -579,11 +574,6 @@ extern "C" int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     return side ? side_stats_join(ps, st) : PS_OK;
 }
 
-// The library's default switches from a merge sort (two launches per doubling of the sorted length) to passes
-// over the key's digits only above a million pairs; measured here on keys of 19 bits, the digit passes win
-// from about 200,000 pairs on (2^18 pairs: 161 against 172 us for the whole push; 2^17: 125 against 98).
-using push_sort_config = rocprim::radix_sort_config<rocprim::default_config, rocprim::default_config, rocprim::default_config, 200000>;
-
 // what ps_push does before it adds: key check, locality statistics and message counts
 int dpaps_account_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, int64_t n, hipStream_t st) {
     int rc = launch_check(ps, keys, n, st);
@@ -600,37 +590,42 @@ int dpaps_account_pull_push(dpaps_ps *ps, int32_t worker, const int64_t *keys, i
 
 // The adding itself, for keys that have been checked (the kernels do nothing once the error flag is set), in two
 // halves: the sort, which needs the keys only (a step that computes its update rows meanwhile runs it beside that
-// work), and the sums, which need the rows.  The sorted pairs stay in the handle's scratch between the two.
-int dpaps_push_sort(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st) {
-    // stable sort of (key, position) by key; the positions come from a counting iterator
-    int key_bits = 1;
-    while (key_bits < 63 && ((int64_t)1 << key_bits) < ps->K) ++key_bits;
-    size_t temp_bytes = 0;
-    const uint64_t *kin = reinterpret_cast<const uint64_t *>(keys);
-    rocprim::counting_iterator<uint32_t> iota(0);
-    PS_HIP(ps, rocprim::radix_sort_pairs<push_sort_config>(nullptr, temp_bytes, kin, (uint64_t *)nullptr, iota, (uint32_t *)nullptr,
-                                                           (size_t)n, 0, key_bits, st));
+// work), and the sums, which need the rows.  The sorted pairs stay in the scratch between the two.
+// Scratch of a push of n pairs: sorted keys, sorted positions, two partial-sum rows per range, the sort's own.
+struct PushLayout { size_t off_pos, off_part, off_sort, bytes; };
+static PushLayout push_layout(const dpaps_ps *ps, int64_t n) {
     const int64_t nranges = (n + PUSH_RANGE - 1) / PUSH_RANGE;
     const size_t part_bytes = ps->opt_push_sequential ? 0 : align_up((size_t)nranges * 2 * ps->L * sizeof(float));
-    size_t off_keys = 0, off_pos = align_up((size_t)n * 8), off_part = off_pos + align_up((size_t)n * 4), off_tmp = off_part + part_bytes;
-    int rc = dpaps_ws_reserve(ps, off_tmp + temp_bytes);
+    PushLayout l;
+    l.off_pos = align_up((size_t)n * 8);
+    l.off_part = l.off_pos + align_up((size_t)n * 4);
+    l.off_sort = l.off_part + part_bytes;
+    l.bytes = l.off_sort + dpaps_sort_scratch_bytes(n, dpaps_key_bits(ps->K));
+    return l;
+}
+
+// the sort into `base` (scratch of at least push_layout(n).bytes, not allocated here)
+static int push_sort_into(dpaps_ps *ps, void *base, const int64_t *keys, int64_t n, hipStream_t st) {
+    const PushLayout l = push_layout(ps, n);
+    uint64_t *skeys = (uint64_t *)base;
+    uint32_t *spos = (uint32_t *)((char *)base + l.off_pos);
+    const int rc = dpaps_sort_pairs(ps, keys, n, dpaps_key_bits(ps->K), skeys, spos, (char *)base + l.off_sort, st);
     if (rc) return rc;
-    uint64_t *skeys = (uint64_t *)((char *)ps->ws + off_keys);
-    uint32_t *spos = (uint32_t *)((char *)ps->ws + off_pos);
-    float *part = (float *)((char *)ps->ws + off_part);
-    void *tmp = (char *)ps->ws + off_tmp;
-    PS_HIP(ps, rocprim::radix_sort_pairs<push_sort_config>(tmp, temp_bytes, kin, skeys, iota, spos, (size_t)n, 0, key_bits, st));
-    ps->push_sorted_n = n; ps->push_off_pos = off_pos; ps->push_off_part = off_part;
-    (void)part;
+    ps->push_base = base; ps->push_sorted_n = n; ps->push_off_pos = l.off_pos; ps->push_off_part = l.off_part;
     return PS_OK;
 }
 
+int dpaps_push_sort(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st) {
+    const int rc = dpaps_ws_reserve(ps, push_layout(ps, n).bytes);
+    return rc ? rc : push_sort_into(ps, ps->ws, keys, n, st);
+}
+
 int dpaps_push_add(dpaps_ps *ps, int64_t n, const float *deltas, hipStream_t st) {
-    if (n != ps->push_sorted_n) { ps->last_error = "push: the sums do not follow their sort"; return PS_EINVAL; }
+    if (n != ps->push_sorted_n || !ps->push_base) { ps->last_error = "push: the sums do not follow their sort"; return PS_EINVAL; }
     const int64_t nranges = (n + PUSH_RANGE - 1) / PUSH_RANGE;
-    const uint64_t *skeys = (const uint64_t *)ps->ws;
-    const uint32_t *spos = (const uint32_t *)((char *)ps->ws + ps->push_off_pos);
-    float *part = (float *)((char *)ps->ws + ps->push_off_part);
+    const uint64_t *skeys = (const uint64_t *)ps->push_base;
+    const uint32_t *spos = (const uint32_t *)((char *)ps->push_base + ps->push_off_pos);
+    float *part = (float *)((char *)ps->push_base + ps->push_off_part);
     if (ps->opt_push_sequential) {
         k_push_apply<<<grid_for(n * 64, 256), 256, 0, st>>>(skeys, spos, n, ps->L, deltas, ps->val, ps->err);
         PS_HIP(ps, hipGetLastError());
