@@ -136,6 +136,19 @@ int ps_pull(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, float 
  * key does, at the price of one wavefront per key. */
 int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, const float *deltas, void *stream);
 
+/* ps_push for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, same result bit for bit and same statistics as ps_push, but
+ * the call makes no hipMalloc / hipFree and calls no allocating routine: its scratch (sorted pairs, the sort's
+ * buffers, partial sums) is a fixed array of 16 MiB in device memory, one per device the library runs on, held
+ * until the process ends.  Limits (PS_ELIMIT, nothing changed): n <= PS_PUSH_NOALLOC_MAX_KEYS and
+ * ceil(n / 64) * value_len <= PS_PUSH_NOALLOC_MAX_PARTIAL.  The statistics run on `stream` itself (no second
+ * stream).  All calls on one device share that device's array, whatever the handle: calls that overlap on one
+ * device (two streams, two handles) race; the array keeps the last call's contents and every call overwrites
+ * what it reads.  No memset nodes are issued, so the call may be captured into a graph. */
+#define PS_PUSH_NOALLOC_MAX_KEYS 262144
+#define PS_PUSH_NOALLOC_MAX_PARTIAL 1048576
+int ps_push_noalloc(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, const float *deltas, void *stream);
+
 /* localize: relocate the keys to `worker` (Sec. 3.1 "API", Sec. 3.2).  The
  * value is untouched, there is no replica, and the last localize of a key in
  * stream order decides its owner (Sec. 3.2, localization conflicts). */

@@ -5,6 +5,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 // ---------------------------------------------------------------------------
@@ -407,6 +408,8 @@ static inline unsigned route_grid(const dpaps_ps *ps, int64_t n) {
     return (unsigned)(need < cap ? need : cap);
 }
 
+static int static_scratch_init(dpaps_ps *ps);
+
 extern "C" int ps_create(int64_t num_keys, int32_t value_len, int32_t num_workers, ps_handle *out) {
     if (!out) return PS_EINVAL;
     *out = nullptr;
@@ -418,6 +421,10 @@ extern "C" int ps_create(int64_t num_keys, int32_t value_len, int32_t num_worker
     hipError_t e;
 #define CR(call) do { e = (call); if (e != hipSuccess) { int rc_ = dpaps_fail_hip(ps, e, #call); ps_destroy(ps); return rc_; } } while (0)
     CR(hipGetDevice(&ps->device));
+    {
+        const int rc_ = static_scratch_init(ps);
+        if (rc_) { ps_destroy(ps); return rc_; }
+    }
     int v = 0;
     CR(hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, ps->device));
     ps->lds_bytes = v;
@@ -509,10 +516,15 @@ static int side_stats_join(dpaps_ps *ps, hipStream_t st) {
 
 int dpaps_check_keys(dpaps_ps *ps, const int64_t *keys, int64_t n, hipStream_t st) { return launch_check(ps, keys, n, st); }
 
+__global__ void k_fill_u32(uint32_t *p, size_t n, uint32_t v) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
 static uint32_t next_call_id(dpaps_ps *ps, hipStream_t st) {
-    if (++ps->call_id == 0) {   // wrapped: forget all stamps
-        size_t W = (size_t)ps->W;
-        (void)hipMemsetAsync(ps->stamp_h, 0, (2 * W + W * W) * sizeof(uint32_t), st);
+    if (++ps->call_id == 0) {   // wrapped: forget all stamps (a kernel, not a memset node: callers may be capturing)
+        const size_t W = (size_t)ps->W, words = 2 * W + W * W;
+        k_fill_u32<<<grid_for((int64_t)words, 256), 256, 0, st>>>(ps->stamp_h, words, 0u);
         ps->call_id = 1;
     }
     return ps->call_id;
@@ -658,6 +670,47 @@ extern "C" int ps_push(ps_handle ps, int32_t worker, const int64_t *keys, int64_
     rc = dpaps_push_apply(ps, keys, n, deltas, st);
     if (rc) return rc;
     return side ? side_stats_join(ps, st) : PS_OK;
+}
+
+// ---- a push that allocates nothing -------------------------------------------------------------------------
+// For callers that cannot allocate (code under graph capture, serving loops, harnesses that forbid it): the
+// scratch of the push - sorted pairs, the sort's buffers and counters, partial sums - lives in a fixed array in
+// device memory, one copy per device that the library runs on, held until the process ends.  Its address on a
+// device is looked up once, by ps_create with that device current, and kept per device; host code uses that
+// address only, never the array's name.
+constexpr size_t PUSH_STATIC_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[PUSH_STATIC_BYTES];
+constexpr int PUSH_STATIC_DEVICES = 64;
+static void *g_scratch_ptr[PUSH_STATIC_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch_init(dpaps_ps *ps) {
+    if (ps->device < 0 || ps->device >= PUSH_STATIC_DEVICES) return PS_OK;     // ps_push_noalloc will refuse
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[ps->device]) {
+        void *p = nullptr;
+        PS_HIP(ps, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[ps->device] = p;
+    }
+    return PS_OK;
+}
+
+extern "C" int ps_push_noalloc(ps_handle ps, int32_t worker, const int64_t *keys, int64_t n, const float *deltas, void *stream) {
+    if (!ps || n < 0 || (n > 0 && (!keys || !deltas))) return PS_EINVAL;
+    if (worker < -1 || worker >= ps->W) return PS_EWORKER;
+    if (n == 0) return PS_OK;
+    void *base = ps->device >= 0 && ps->device < PUSH_STATIC_DEVICES ? g_scratch_ptr[ps->device] : nullptr;
+    if (!base) { ps->last_error = "ps_push_noalloc: no fixed scratch on this device"; return PS_EINVAL; }
+    if (n > PS_PUSH_NOALLOC_MAX_KEYS || (n + PUSH_RANGE - 1) / PUSH_RANGE * ps->L > PS_PUSH_NOALLOC_MAX_PARTIAL ||
+        push_layout(ps, n).bytes > PUSH_STATIC_BYTES) {
+        ps->last_error = "ps_push_noalloc: at most 262144 keys and ceil(n / 64) * value_len <= 2^20 per call; use ps_push";
+        return PS_ELIMIT;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    int rc = dpaps_account_push(ps, worker, keys, n, st);
+    if (rc) return rc;
+    rc = push_sort_into(ps, base, keys, n, st);
+    return rc ? rc : dpaps_push_add(ps, n, deltas, st);
 }
 
 // the owner updates and statistics of a localize call, for keys that have been checked

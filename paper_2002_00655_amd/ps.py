@@ -23,7 +23,7 @@ STAT_NAMES = ["pull_local", "pull_remote", "push_local", "push_remote", "relocat
               "cache_hit", "cache_stale"]
 OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES, OPT_MF_PROFILE, OPT_MF_GROUPED, OPT_MF_HEAVY_LEN, OPT_PUSH_SEQUENTIAL, OPT_MF_TEAM_MAX, OPT_MF_CLASSIC, OPT_LOCATION_CACHES = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
 
-EXPORTS = ["ps_create", "ps_destroy", "ps_pull", "ps_push", "ps_localize", "ps_owner", "ps_stats", "ps_status",
+EXPORTS = ["ps_create", "ps_destroy", "ps_pull", "ps_push", "ps_push_noalloc", "ps_localize", "ps_owner", "ps_stats", "ps_status",
            "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_sgd_epoch_handoff", "mf_train_sse",
            "mf_profile_read", "kge_sgd_step", "kge_sgd_epoch"]
 
@@ -44,6 +44,7 @@ def load_library() -> C.CDLL:
     lib.ps_destroy.argtypes = [vp]
     lib.ps_pull.argtypes = [vp, i32, vp, i64, vp, vp]
     lib.ps_push.argtypes = [vp, i32, vp, i64, vp, vp]
+    lib.ps_push_noalloc.argtypes = [vp, i32, vp, i64, vp, vp]
     lib.ps_localize.argtypes = [vp, vp, i64, i32, vp]
     lib.ps_owner.argtypes = [vp, vp, i64, vp, vp]
     lib.ps_stats.argtypes = [vp, vp, vp]
@@ -130,6 +131,13 @@ class ParameterServer:
         if deltas.numel() != keys.numel() * self.L:
             raise ValueError("deltas must hold value_len floats per key")
         self._check(_lib.ps_push(self._h, worker, keys.data_ptr(), keys.numel(), deltas.data_ptr(), _stream()), "ps_push")
+
+    def push_noalloc(self, keys: torch.Tensor, deltas: torch.Tensor, worker: int = -1) -> None:
+        """ps_push with the library's fixed scratch array: no device allocation (see include/dpaps.h)."""
+        keys, deltas = _dev(keys, torch.int64), _dev(deltas, torch.float32)
+        if deltas.numel() != keys.numel() * self.L:
+            raise ValueError("deltas must hold value_len floats per key")
+        self._check(_lib.ps_push_noalloc(self._h, worker, keys.data_ptr(), keys.numel(), deltas.data_ptr(), _stream()), "ps_push_noalloc")
 
     def localize(self, keys: torch.Tensor, worker: int) -> None:
         keys = _dev(keys, torch.int64)
