@@ -56,6 +56,47 @@ __device__ __forceinline__ float bperm_f(float v, int src) {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, v)));
 }
 
+// One step of the triangular solve in sgd_block, with the terms of the new column factor that have become final
+// (see there): with eps_U = acc of lane U of every row of 16 lanes, broadcast by the instruction itself,
+//     hs[cc] += eps_U * w[cc]   (the entry's row, for the new h),     acc += eps_U * nl   (nl = -(lr / c) G[t][U] below
+// the diagonal, zero elsewhere, so lanes t <= U keep their value).  The data hazard "a vector instruction writes a
+// register, a DPP operand reads it" needs two wait states, which no instruction of the step can fill (all three read
+// acc through DPP): hence the s_nop at the head, which also covers whatever the compiler puts in front.
+template <int U, int NV>
+__device__ __forceinline__ void solve_step(float &acc, float (&hs)[NV], const float (&w)[NV], float nl) {
+    static_assert(NV == 1 || NV == 2, "a factor row has at most 128 components here");
+    if constexpr (NV == 2)
+        __asm__ volatile("s_nop 1\n\t"
+                         "v_fmac_f32_dpp %1, %0, %3 row_newbcast:%6 row_mask:0xf bank_mask:0xf\n\t"
+                         "v_fmac_f32_dpp %2, %0, %4 row_newbcast:%6 row_mask:0xf bank_mask:0xf\n\t"
+                         "v_fmac_f32_dpp %0, %0, %5 row_newbcast:%6 row_mask:0xf bank_mask:0xf"
+                         : "+v"(acc), "+v"(hs[0]), "+v"(hs[1])
+                         : "v"(w[0]), "v"(w[1]), "v"(nl), "n"(U));
+    else
+        __asm__ volatile("s_nop 1\n\t"
+                         "v_fmac_f32_dpp %1, %0, %2 row_newbcast:%4 row_mask:0xf bank_mask:0xf\n\t"
+                         "v_fmac_f32_dpp %0, %0, %3 row_newbcast:%4 row_mask:0xf bank_mask:0xf"
+                         : "+v"(acc), "+v"(hs[0])
+                         : "v"(w[0]), "v"(nl), "n"(U));
+}
+// the last entry has nothing below it: only its term of the new h
+template <int U, int NV>
+__device__ __forceinline__ void solve_last(const float &acc, float (&hs)[NV], const float (&w)[NV]) {
+    if constexpr (NV == 2)
+        __asm__ volatile("s_nop 1\n\t"
+                         "v_fmac_f32_dpp %0, %2, %3 row_newbcast:%5 row_mask:0xf bank_mask:0xf\n\t"
+                         "v_fmac_f32_dpp %1, %2, %4 row_newbcast:%5 row_mask:0xf bank_mask:0xf"
+                         : "+v"(hs[0]), "+v"(hs[1])
+                         : "v"(acc), "v"(w[0]), "v"(w[1]), "n"(U));
+    else
+        __asm__ volatile("s_nop 1\n\t"
+                         "v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                         : "+v"(hs[0])
+                         : "v"(acc), "v"(w[0]), "n"(U));
+}
+// in front of the first step: a DPP operand must also keep five wait states from a write of the execution mask
+__device__ __forceinline__ void solve_first() { __asm__ volatile("s_nop 4"); }
+
 // NT = number of 16-component tiles of a factor row (rank <= 16 NT); A4: the rank is a multiple of 4,
 // so every row starts on a 16-byte boundary and is read in 16-byte pieces
 // AGENT_H: the column factors and the owner map are read and written with agent-scope accesses, which the caches
@@ -88,7 +129,8 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     float *stg = lds_f + (size_t)wave * 16 * RS;                       // this wavefront's X: 16 rows (heavy wavefronts only)
     float *cpow = lds_f + (size_t)hwaves * 16 * RS;                    // c^0 .. c^16
     float *cpm1 = cpow + 20;                                           // c^0 - 1 .. c^16 - 1
-    float *hshare = cpow + 40;                                         // DPAPS_HEAVY_MAX x 16 NT: the heavy columns' factors
+    float *cim1 = cpow + 40;                                           // c^-0 - 1 .. c^-16 - 1
+    float *hshare = cpow + 60;                                         // DPAPS_HEAVY_MAX x 16 NT: the heavy columns' factors
     uint32_t *hseq = reinterpret_cast<uint32_t *>(hshare + DPAPS_HEAVY_MAX * 16 * NT);   // and how many groups each has absorbed
     uint32_t *ticket = hseq + DPAPS_HEAVY_MAX;                          // ticket_cap: one per row with several entries
     uint32_t *ctick = ticket + a.ticket_cap;                           // ctick_cap: one per non-heavy column
@@ -108,6 +150,7 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     const int64_t tr0 = a.blk_trun_ptr[b], tr1 = a.blk_trun_ptr[b + 1];
     const float lr = __uint_as_float(lr_), lambda = __uint_as_float(lambda_);
     const float delta = (float)((double)lr * (double)lambda);         // c = 1 - delta
+    const float nlrc = (float)(-(double)lr / (1.0 - (double)lr * (double)lambda));   // -lr / c
     // The factors of the block's rows and of its columns, each as a buffer: an access at an offset past
     // the end reads as zero and writes nothing, which is how lanes without a row are switched off
     // without branching.  (The host has checked that both spans are below 2 GiB.)
@@ -167,7 +210,7 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     if (threadIdx.x == 0) {
         const double cd = 1.0 - (double)lr * (double)lambda;
         double x = 1.0;
-        for (int i = 0; i <= 16; ++i) { cpow[i] = (float)x; cpm1[i] = (float)(x - 1.0); x = x * cd; }
+        for (int i = 0; i <= 16; ++i) { cpow[i] = (float)x; cpm1[i] = (float)(x - 1.0); cim1[i] = (float)(1.0 / x - 1.0); x = x * cd; }
         next_run = 0; next_trow = 0; done_entries = 0; give_up = 0;
     }
     __syncthreads();
@@ -323,18 +366,30 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                     if (j & 1) __builtin_amdgcn_sched_barrier(0);   // two tiles in flight at most: registers are scarce
                 }
                 gm = gm + gm2;
-                // lane (n16, hi) holds G[4 hi + v][n16] in gm[v]; the recurrence below needs lr G[n16][t] in every
-                // lane at step t
-                float gl[CH];
+                // lane (n16, hi) holds G[4 hi + v][n16] in gm[v].  The solve below needs, in every lane of row t = n16,
+                // -(lr / c) G[t][u] for u < t and zero for u >= t: the lane that holds G[u][t] clears what is not below
+                // the diagonal before the exchange
+                float nl[CH - 1];
+                {
+                    float gmm[4];
 #pragma unroll
-                for (int t = 0; t < CH; ++t) gl[t] = lr * bperm_f(gm[t & 3], 16 * (t >> 2) + n16);
+                    for (int v = 0; v < 4; ++v) gmm[v] = 4 * hi + v < n16 ? gm[v] : 0.0f;
+#pragma unroll
+                    for (int u = 0; u < CH - 1; ++u) nl[u] = nlrc * bperm_f(gmm[u & 3], 16 * (u >> 2) + n16);
+                }
 
-                // v_t of the lane's row t = n16 in all four rows of 16 lanes (the per-entry data sits in lanes 0 .. 14)
+                // v_t of the lane's row t = n16 in all four rows of 16 lanes (the per-entry data sits in lanes 0 .. 14),
+                // scaled: v_t c^(-t) = v_t + (c^(-t) - 1) v_t
                 const float v_row = bperm_f(c_val, n16);
+                float vs = __builtin_fmaf(v_row, cim1[n16], v_row);
                 // table entries for the new h, read before the wait as well
-                const int pw_h = k - 1 - n16;
-                const float cpm1_k = cpm1[k];
-                const float coef_h = n16 < k ? lr * cpow[pw_h > 0 ? pw_h : 0] : 0.0f;   // lane s: lr c^(k-1-s), what e_s w_s weighs in the new h
+                float cpm1_k = cpm1[k];
+                float lrck = lr * cpow[k > 0 ? k - 1 : 0];                            // lr c^(k-1): what eps_s w_s weighs in the new h
+                float cpm1_t = cpm1[n16];
+                // (all of this is computed here, ahead of the wait, not where it is first used)
+#pragma unroll
+                for (int u = 0; u < CH - 1; ++u) __asm__ volatile("" : "+v"(nl[u]));
+                __asm__ volatile("" : "+v"(vs), "+v"(cpm1_k), "+v"(lrck), "+v"(cpm1_t));
                 // this lane's quarter of row n16, for the inner products with h below: fetched before the wait
                 f32x4 xr[NT];
 #pragma unroll
@@ -385,60 +440,37 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                 // the vector unit add them up and leave the sum in all four
                 p = add_across_halves(p);
                 p = add_across_row_pairs(p);
-                // The errors: e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t].  Lane (t, any hi) holds v_t (v_row) and p_t, and
-                // e_t reaches the other lanes of its row of 16 by a broadcast inside the vector unit.  Steps past
-                // the group's end work on rows of X that are zero and on values that are finite, so what they
-                // compute changes nothing that is used; they are not skipped, to keep the chain free of branches.
-                float e_vec = 0.0f;                        // e_t in every lane with n16 == t
-                float hn[NV];                              // the new h = c^k h + sum_s lr e_s c^(k-1-s) w_s
+                // The errors.  With p_s = <w_s, h> for the incoming h, the per-entry recursion e_t = v_t - <w_t, h_(t-1)>
+                // is the lower-triangular system
+                //     e_t = v_t - c^t p_t - sum_(u<t) lr c^(t-1-u) G[t][u] e_u,
+                // and in the scaled unknowns eps_t = e_t c^(-t) its coefficients lose their powers of c:
+                //     eps_t = v_t c^(-t) - p_t - sum_(u<t) (lr / c) G[t][u] eps_u.
+                // Lane (t, any hi) starts with acc = v_t c^(-t) - p_t; step u adds -(lr / c) G[t][u] eps_u, eps_u = acc of lane u
+                // (final after step u - 1) broadcast inside each row of 16 lanes by the multiply-add itself: one
+                // dependent instruction per entry.  The new h = c^k h + lr c^(k-1) sum_s eps_s w_s collects its terms
+                // along the way with the same broadcast.  Steps past the group's end work on rows of X that are
+                // zero and on finite values, so what they compute changes nothing that is used; the chain has no
+                // branches.  Lane 15 (the row of X that holds h) computes something finite that is never used.
+                float acc = vs - p;
+                float hs[NV];
 #pragma unroll
-                for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(cpm1_k, ho[cc], ho[cc]);
-#define DPAPS_REC_STEP(t)                                                       \
-                {                                                               \
-                    const float d = v_row - p;                                  \
-                    const float e = row_bcast_lane<t>(d);                       \
-                    e_vec = n16 == t ? d : e_vec;                               \
-                    p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p)); \
-                }
-                if constexpr (LONG_RUNS) {
-                    // A run of very many groups is bound by this part alone.  There the terms of the new h are added
-                    // along the way, a few steps behind their e_t (the rows' components come from LDS, and the first
-                    // steps must not wait for them), with the coefficient broadcast like e_t: 15 instructions more
-                    // than below, but none of the reads of a lane into a scalar, which stall the vector unit.
-                    float as_[CH];
-#define DPAPS_REC_STEP_H(t)                                                     \
-                    {                                                           \
-                        const float d = v_row - p;                              \
-                        const float e = row_bcast_lane<t>(d);                   \
-                        as_[t] = row_bcast_lane<t>(d * coef_h);                 \
-                        e_vec = n16 == t ? d : e_vec;                           \
-                        p = __builtin_fmaf(e, gl[t], __builtin_fmaf(-delta, p, p)); \
-                    }
-#define DPAPS_H_TERM(t)                                                         \
-                    _Pragma("unroll")                                           \
-                    for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(as_[t], wv[t][cc], hn[cc]);
-                    DPAPS_REC_STEP_H(0) DPAPS_REC_STEP_H(1) DPAPS_REC_STEP_H(2) DPAPS_REC_STEP_H(3)
-                    DPAPS_REC_STEP_H(4) DPAPS_H_TERM(0) DPAPS_REC_STEP_H(5) DPAPS_H_TERM(1) DPAPS_REC_STEP_H(6) DPAPS_H_TERM(2)
-                    DPAPS_REC_STEP_H(7) DPAPS_H_TERM(3) DPAPS_REC_STEP_H(8) DPAPS_H_TERM(4) DPAPS_REC_STEP_H(9) DPAPS_H_TERM(5)
-                    DPAPS_REC_STEP_H(10) DPAPS_H_TERM(6) DPAPS_REC_STEP_H(11) DPAPS_H_TERM(7) DPAPS_REC_STEP_H(12) DPAPS_H_TERM(8)
-                    DPAPS_REC_STEP_H(13) DPAPS_H_TERM(9) DPAPS_REC_STEP_H(14) DPAPS_H_TERM(10)
-                    DPAPS_H_TERM(11) DPAPS_H_TERM(12) DPAPS_H_TERM(13) DPAPS_H_TERM(14)
-#undef DPAPS_REC_STEP_H
-#undef DPAPS_H_TERM
-                } else {
-                    DPAPS_REC_STEP(0) DPAPS_REC_STEP(1) DPAPS_REC_STEP(2) DPAPS_REC_STEP(3) DPAPS_REC_STEP(4)
-                    DPAPS_REC_STEP(5) DPAPS_REC_STEP(6) DPAPS_REC_STEP(7) DPAPS_REC_STEP(8) DPAPS_REC_STEP(9)
-                    DPAPS_REC_STEP(10) DPAPS_REC_STEP(11) DPAPS_REC_STEP(12) DPAPS_REC_STEP(13) DPAPS_REC_STEP(14)
-                    const float a_vec = e_vec * coef_h;                           // lane s < 15: coefficient of w_s
+                for (int cc = 0; cc < NV; ++cc) hs[cc] = 0.0f;
+                float hbase[NV];                           // c^k h
 #pragma unroll
-                    for (int s = 0; s < CH; ++s) {
-                        const float as = rl_f(a_vec, s);
+                for (int cc = 0; cc < NV; ++cc) hbase[cc] = __builtin_fmaf(cpm1_k, ho[cc], ho[cc]);
+                solve_first();
+                solve_step<0, NV>(acc, hs, wv[0], nl[0]);   solve_step<1, NV>(acc, hs, wv[1], nl[1]);
+                solve_step<2, NV>(acc, hs, wv[2], nl[2]);   solve_step<3, NV>(acc, hs, wv[3], nl[3]);
+                solve_step<4, NV>(acc, hs, wv[4], nl[4]);   solve_step<5, NV>(acc, hs, wv[5], nl[5]);
+                solve_step<6, NV>(acc, hs, wv[6], nl[6]);   solve_step<7, NV>(acc, hs, wv[7], nl[7]);
+                solve_step<8, NV>(acc, hs, wv[8], nl[8]);   solve_step<9, NV>(acc, hs, wv[9], nl[9]);
+                solve_step<10, NV>(acc, hs, wv[10], nl[10]); solve_step<11, NV>(acc, hs, wv[11], nl[11]);
+                solve_step<12, NV>(acc, hs, wv[12], nl[12]); solve_step<13, NV>(acc, hs, wv[13], nl[13]);
+                solve_last<14, NV>(acc, hs, wv[14]);
+                static_assert(CH == 15, "the solve above is written out for 15 entries");
+                float hn[NV];                              // the new h = c^k h + lr c^(k-1) sum_s eps_s w_s
 #pragma unroll
-                        for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(as, wv[s][cc], hn[cc]);
-                    }
-                }
-#undef DPAPS_REC_STEP
-                static_assert(CH == 15, "the recurrence above is written out for 15 entries");
+                for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(lrck, hs[cc], hbase[cc]);
                 // the new h is complete: into LDS for the next group, which may start at once
                 {
 #pragma unroll
@@ -456,6 +488,9 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                     }
                     __builtin_amdgcn_s_setprio(2);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                // e_t = eps_t c^t in every lane with n16 == t, for the new rows below
+                const float e_vec = __builtin_fmaf(acc, cpm1_t, acc);
                 // read ahead: the rows of this wavefront's next group, the per-entry data of the one after (not
                 // earlier: the registers they arrive in are needed by the part above)
                 {
@@ -785,7 +820,7 @@ static int plan_block_lds(dpaps_ps *ps, SgdArgs &a, size_t *lds_out) {
     }
     if (!f.sweep_ok) { ps->last_error = "the grouped SGD kernel needs rows in ascending order inside the short column runs"; return PS_ELAYOUT; }
     a.ctick_cap = f.max_tail_cols > 1 ? f.max_tail_cols : 1;
-    const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 40 + DPAPS_HEAVY_MAX * 16 * NT + DPAPS_HEAVY_MAX) * 4 +
+    const int64_t fixed = ((int64_t)a.heavy_waves * 16 * (16 * NT + 4) + 60 + DPAPS_HEAVY_MAX * 16 * NT + DPAPS_HEAVY_MAX) * 4 +
                           ((int64_t)a.ticket_cap + a.ctick_cap) * 4;
     const int64_t budget = (int64_t)ps->lds_bytes - 1024;         // static LDS and slack
     if (fixed > budget) { ps->last_error = "not enough LDS for the grouped SGD kernel"; return PS_ELIMIT; }
