@@ -88,7 +88,7 @@ enum {
                                    order, however many there are (one wavefront per key; for bit-for-bit checks
                                    against a sequential server).  0 (default): see ps_push */
     PS_OPT_MF_TEAM_MAX = 8,     /* grouped SGD kernel: the most wavefronts that take the groups of one long column run
-                                   in turn, 1..14 (default 5) */
+                                   in turn, 1..14 (default 4: one per vector unit of a compute unit) */
     PS_OPT_MF_CLASSIC = 9,      /* mf_sgd_epoch as on a classic parameter server (Sec. 2.1, Sec. 4.2, Sec. 4.6): no
                                    relocation, no residency - every entry pulls its two keys from the store and
                                    pushes the update terms back, counted as local or remote by the owner map as it
@@ -190,7 +190,8 @@ int mf_block_ratings(int64_t m, int64_t n, int64_t nnz, const int32_t *rows, con
  * of the rows within a column is accepted and is the processing order) to the
  * server, which keeps its own copy.  ps must have m + n keys.  Limits
  * (PS_ELIMIT): nnz < 2^32; in one block at most 65534 rows with two or more
- * entries, and at most 32767 entries of one row.  Synchronizes the stream. */
+ * entries, at most 32767 entries of one row, and at most 32768 entries of one
+ * column outside the block's 8 longest column runs.  Synchronizes the stream. */
 int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, const int32_t *rows, const int32_t *cols,
                     const float *vals, int32_t d_row, int32_t d_col, const int64_t *row_bounds_host,
                     const int64_t *col_bounds_host, const int64_t *block_ptr_host, void *stream);

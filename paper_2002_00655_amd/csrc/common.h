@@ -44,12 +44,15 @@ struct MfData {
     int64_t num_tail = 0, num_truns = 0;
     int32_t max_tail_cols = 0;        // largest number of non-heavy runs in any block
     uint32_t *t_cinfo = nullptr;      // num_tail: bits 0-15 index of the entry's run among the block's non-heavy runs,
-                                      // bits 16-31 its rank inside that run
+                                      // bits 16-30 its rank inside that run, bit 31: it is the run's last entry
     float *t_val = nullptr;           // num_tail
     uint32_t *trun_start = nullptr;   // num_truns + 1: first entry of a row run
     int32_t *trun_row = nullptr;      // num_truns: global row index
     uint32_t *trun_wait = nullptr;    // num_truns: bits 0-15 ticket slot of the row, bits 16-31 the row's entries in heavy
                                       // runs (the ticket value to wait for); 0xFFFFFFFF: none
+    uint32_t *trun_ci = nullptr;      // num_truns: t_cinfo, value and column of the row run's first entry, so that one
+    float *trun_val = nullptr;        // read brings everything a row with a single entry needs
+    int32_t *trun_col = nullptr;
     int64_t *blk_trun_ptr = nullptr;  // num_blocks + 1, index into row runs
     // where the groups of the heavy runs start: run r has run_gptr[r+1] - run_gptr[r] - 1 groups (none if it is not
     // heavy); gstart[run_gptr[r] + g] is the start of group g relative to the run's first entry, one more entry = length
@@ -96,7 +99,7 @@ struct dpaps_ps {
     int opt_profile = 0;
     int opt_push_sequential = 0;      // 1: ps_push adds each key's terms strictly one after the other
     int opt_classic = 0;              // 1, 2: mf_sgd_epoch as on a classic parameter server (2: updates in place)
-    int opt_team_max = 5;             // most wavefronts that share one heavy run
+    int opt_team_max = 4;             // most wavefronts that share one heavy run
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
     // event pairs around the SGD kernel launches (only while profiling is on)
@@ -138,6 +141,7 @@ struct SgdArgs {
     // second part of a block (grouped kernel only)
     const int32_t *blk_nheavy; const int64_t *blk_trun_ptr;
     const uint32_t *trun_start; const int32_t *trun_row; const uint32_t *trun_wait;
+    const uint32_t *trun_ci; const float *trun_val; const int32_t *trun_col;
     const uint32_t *t_cinfo; const float *t_val;
     const int64_t *run_gptr; const int32_t *gstart;
     int32_t heavy_waves;        // wavefronts that take heavy runs (each has a staging area in LDS)

@@ -172,7 +172,7 @@ done:
 void dpaps_mf_free(dpaps_ps *ps) {
     MfData &f = ps->mf;
     void *ptrs[] = {f.row, f.val, f.info, f.col, f.run_start, f.run_col, f.blk_run_ptr, f.multi_row, f.blk_multi_ptr,
-                    f.row_bounds, f.col_bounds, f.blk_nheavy, f.t_cinfo, f.t_val, f.trun_start, f.trun_row, f.trun_wait,
+                    f.row_bounds, f.col_bounds, f.blk_nheavy, f.t_cinfo, f.t_val, f.trun_start, f.trun_row, f.trun_wait, f.trun_ci, f.trun_val, f.trun_col,
                     f.blk_trun_ptr, f.run_gptr, f.gstart, f.team_plan};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     ps->mf = MfData();
@@ -351,17 +351,22 @@ __global__ void k_tail_fill(const uint32_t *spos, const uint32_t *tq, const uint
                             const uint32_t *seg_slot, const uint32_t *runidx, const uint32_t *blk, const int64_t *blk_run_ptr,
                             const int32_t *nheavy, const int64_t *run_start, const int32_t *rows, const float *vals,
                             int64_t nnz, uint32_t *t_cinfo, float *t_val, uint32_t *trun_start, int32_t *trun_row,
-                            uint32_t *trun_wait, int32_t *err) {
+                            uint32_t *trun_wait, const int32_t *run_col, uint32_t *trun_ci, float *trun_val, int32_t *trun_col,
+                            int32_t *err) {
     int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nnz || !tq[q]) return;
     uint32_t p = spos[q], t = tpos[q], g = runidx[p], b = blk[p];
     int64_t cslot = (int64_t)g - (blk_run_ptr[b] + nheavy[b]);
     int64_t cseq = (int64_t)p - run_start[g];
-    if (cslot >= 65535 || cseq > 65535) { atomicExch(err, PS_ELIMIT); cslot = 0; cseq = 0; }
-    t_cinfo[t] = (uint32_t)cslot | ((uint32_t)cseq << 16);
+    if (cslot >= 65535 || cseq > 32767) { atomicExch(err, PS_ELIMIT); cslot = 0; cseq = 0; }
+    const uint32_t last = (int64_t)p + 1 == run_start[g + 1] ? 0x80000000u : 0u;      // the column's last entry in this block
+    t_cinfo[t] = (uint32_t)cslot | ((uint32_t)cseq << 16) | last;
     t_val[t] = vals[p];
     if (thead[q]) {
         uint32_t j = tri[q], s = seg_idx[q];
+        trun_ci[j] = (uint32_t)cslot | ((uint32_t)cseq << 16) | last;
+        trun_val[j] = vals[p];
+        trun_col[j] = run_col[g];
         uint32_t before = (uint32_t)q - seg_start[s];       // the row's entries in heavy runs
         trun_start[j] = t;
         trun_row[j] = rows[p];
@@ -609,6 +614,9 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     HIPRC(hipMalloc(&f.trun_start, (ntr + 1) * sizeof(uint32_t)));
     HIPRC(hipMalloc(&f.trun_row, std::max<int64_t>(ntr, 1) * sizeof(int32_t)));
     HIPRC(hipMalloc(&f.trun_wait, std::max<int64_t>(ntr, 1) * sizeof(uint32_t)));
+    HIPRC(hipMalloc(&f.trun_ci, std::max<int64_t>(ntr, 1) * sizeof(uint32_t)));
+    HIPRC(hipMalloc(&f.trun_val, std::max<int64_t>(ntr, 1) * sizeof(float)));
+    HIPRC(hipMalloc(&f.trun_col, std::max<int64_t>(ntr, 1) * sizeof(int32_t)));
     {
         const uint32_t end = (uint32_t)nt;
         HIPRC(hipMemcpyAsync(f.trun_start + ntr, &end, sizeof(uint32_t), hipMemcpyHostToDevice, st));
@@ -616,7 +624,8 @@ extern "C" int mf_load_ratings(ps_handle ps, int64_t m, int64_t n, int64_t nnz, 
     if (nnz > 0) {
         k_tail_fill<<<grid_for(nnz, 256), 256, 0, st>>>(pos_b, tq, tpos, head, scan, seg_idx, seg_start, is_multi, seg_slot, runidx,
                                                         blk, f.blk_run_ptr, f.blk_nheavy, f.run_start, f.row, f.val, nnz, f.t_cinfo,
-                                                        f.t_val, f.trun_start, f.trun_row, f.trun_wait, d_err);
+                                                        f.t_val, f.trun_start, f.trun_row, f.trun_wait, f.run_col, f.trun_ci, f.trun_val,
+                                                        f.trun_col, d_err);
     }
     k_blk_ptr_from_scan<<<grid_for(nb + 1, 256), 256, 0, st>>>(d_bp, nb, nnz, scan, ntr, f.blk_trun_ptr);
     HIPRC(hipGetLastError());

@@ -473,6 +473,7 @@ static SgdArgs sgd_args(dpaps_ps *ps, const int32_t *tasks, float lr, float lamb
     a.m = f.m; a.L = ps->L; a.d_col = f.d_col;
     a.blk_nheavy = f.blk_nheavy; a.blk_trun_ptr = f.blk_trun_ptr;
     a.trun_start = f.trun_start; a.trun_row = f.trun_row; a.trun_wait = f.trun_wait;
+    a.trun_ci = f.trun_ci; a.trun_val = f.trun_val; a.trun_col = f.trun_col;
     a.t_cinfo = f.t_cinfo; a.t_val = f.t_val;
     a.run_gptr = f.run_gptr; a.gstart = f.gstart;
     a.lr = lr; a.lambda = lambda; a.stats = ps->stats; a.err = ps->err;

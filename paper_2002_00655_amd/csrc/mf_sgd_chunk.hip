@@ -12,9 +12,10 @@
 //   1. X = [w_0; ...; w_{T-1}; h]  (16 x r with T = 15),  G = X X^T  - one dense 16x16xr
 //      product (matrix cores); G[s][15] = <w_s, h> are the T inner products with the
 //      incoming h, G[s][t] = <w_s, w_t>;
-//   2. with p_s = <w_s, h_t> kept per lane, the errors follow from a scalar recurrence,
-//      e_t = v_t - p_t,  p_s <- c p_s + lr e_t G[s][t],  three dependent vector
-//      instructions per entry instead of a length-r reduction;
+//   2. with p_s = <w_s, h> for the incoming h, the errors solve a lower-triangular system,
+//      e_t = v_t - c^t p_t - sum_(u<t) lr c^(t-1-u) G[t][u] e_u, which in the scaled unknowns
+//      e_t c^(-t) loses its powers of c: one dependent vector instruction per entry instead
+//      of a length-r reduction;
 //   3. all new rows are one more dense product X' = C X with the lower-triangular 16x16
 //      coefficient matrix  C[t][t] = c,  C[t][s<t] = lr^2 e_t e_s c^(t-1-s),
 //      C[t][15] = lr e_t c^t,  C[15][s] = lr e_s c^(T-1-s),  C[15][15] = c^T.
@@ -49,6 +50,13 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define CH 15                    // entries per group (the 16th row of X is the column's row)
 #define AUX_SC1 16               // cache policy of a buffer access: agent scope
 #define DPAPS_LONG_RUN_GROUPS 64 // data with a column run of at least this many groups in a block: see the recurrence
+
+// x, which is the same in all lanes, as a scalar
+__device__ __forceinline__ int64_t uniform_i64(int64_t x) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)x);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)x >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
 
 // value of `v` in lane `src` (any permutation; goes through the LDS crossbar, no memory)
 __device__ __forceinline__ int bperm_i(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }
@@ -140,23 +148,25 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     __shared__ unsigned int done_entries;
     __shared__ uint32_t give_up;
 
+    // (what is the same in all lanes is said to be: a value read from memory otherwise stays in vector registers
+    // for the whole kernel)
     const int64_t b = (int64_t)rb * a.d_col + cb;
-    const int64_t run0 = a.blk_run_ptr[b], run1 = a.blk_run_ptr[b + 1];
-    const int nmulti = (int)(a.blk_multi_ptr[b + 1] - a.blk_multi_ptr[b]);
+    const int64_t run0 = uniform_i64(a.blk_run_ptr[b]), run1 = uniform_i64(a.blk_run_ptr[b + 1]);
+    const int nmulti = __builtin_amdgcn_readfirstlane((int)(a.blk_multi_ptr[b + 1] - a.blk_multi_ptr[b]));
     const int nruns = (int)(run1 - run0);
-    const int nheavy = a.blk_nheavy[b];
+    const int nheavy = __builtin_amdgcn_readfirstlane(a.blk_nheavy[b]);
     const int ntcols = nruns - nheavy;                                 // non-heavy columns
     const int ncached = min(ntcols, a.hcache_cap);
-    const int64_t tr0 = a.blk_trun_ptr[b], tr1 = a.blk_trun_ptr[b + 1];
+    const int64_t tr0 = uniform_i64(a.blk_trun_ptr[b]), tr1 = uniform_i64(a.blk_trun_ptr[b + 1]);
     const float lr = __uint_as_float(lr_), lambda = __uint_as_float(lambda_);
     const float delta = (float)((double)lr * (double)lambda);         // c = 1 - delta
     const float nlrc = (float)(-(double)lr / (1.0 - (double)lr * (double)lambda));   // -lr / c
     // The factors of the block's rows and of its columns, each as a buffer: an access at an offset past
     // the end reads as zero and writes nothing, which is how lanes without a row are switched off
     // without branching.  (The host has checked that both spans are below 2 GiB.)
-    const int64_t blk_r0 = a.row_bounds[rb], blk_c0 = a.col_bounds[cb];
-    const uint32_t wspan = (uint32_t)((a.row_bounds[rb + 1] - blk_r0) * L * 4);
-    const uint32_t hspan = (uint32_t)((a.col_bounds[cb + 1] - blk_c0) * L * 4);
+    const int64_t blk_r0 = uniform_i64(a.row_bounds[rb]), blk_c0 = uniform_i64(a.col_bounds[cb]);
+    const uint32_t wspan = (uint32_t)__builtin_amdgcn_readfirstlane((int)((a.row_bounds[rb + 1] - blk_r0) * L * 4));
+    const uint32_t hspan = (uint32_t)__builtin_amdgcn_readfirstlane((int)((a.col_bounds[cb + 1] - blk_c0) * L * 4));
     const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + blk_r0 * L, 0, (int)wspan, 0x00020000);
     const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(a.val + (a.m + blk_c0) * L, 0, (int)hspan, 0x00020000);
 
@@ -342,23 +352,19 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                 // X: rows 0 .. 14 from the read-ahead (components past the rank are zero) go to the staging
                 // area; both dense products read X from there, so the registers of the read-ahead are free
                 // again at once
+                // (the first product and the inner products with h take them from the registers they are in)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (16 * (NT - 1) + 4 * hi + q >= L) xp[NT - 1][q] = 0.0f;
                 if (n16 < 15) {
 #pragma unroll
-                    for (int j = 0; j < NT; ++j) {
-                        f32x4 x = xp[j];
-                        if (j == NT - 1) {
-#pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                if (16 * (NT - 1) + 4 * hi + q >= L) x[q] = 0.0f;
-                        }
-                        *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = x;
-                    }
+                    for (int j = 0; j < NT; ++j) *reinterpret_cast<f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]) = xp[j];
                 }
                 // ---- <w_s, w_t>: G = X X^T (row 15 of X is an old copy of h here; its products are not used)
                 f32x4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gm2 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
-                    const f32x4 xm = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
+                    const f32x4 xm = xp[j];
                     gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[0], xm[0], gm, 0, 0, 0);
                     gm2 = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[1], xm[1], gm2, 0, 0, 0);
                     gm = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[2], xm[2], gm, 0, 0, 0);
@@ -382,115 +388,116 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                 // scaled: v_t c^(-t) = v_t + (c^(-t) - 1) v_t
                 const float v_row = bperm_f(c_val, n16);
                 float vs = __builtin_fmaf(v_row, cim1[n16], v_row);
-                // table entries for the new h, read before the wait as well
-                float cpm1_k = cpm1[k];
-                float lrck = lr * cpow[k > 0 ? k - 1 : 0];                            // lr c^(k-1): what eps_s w_s weighs in the new h
-                float cpm1_t = cpm1[n16];
-                // (all of this is computed here, ahead of the wait, not where it is first used)
-#pragma unroll
-                for (int u = 0; u < CH - 1; ++u) __asm__ volatile("" : "+v"(nl[u]));
-                __asm__ volatile("" : "+v"(vs), "+v"(cpm1_k), "+v"(lrck), "+v"(cpm1_t));
-                // this lane's quarter of row n16, for the inner products with h below: fetched before the wait
-                f32x4 xr[NT];
-#pragma unroll
-                for (int j = 0; j < NT; ++j) xr[j] = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * j + 4 * hi]);
-                __builtin_amdgcn_sched_barrier(0);
-
-                // ---- the part that needs h as the previous group left it --------------------------------
-                for (uint32_t spins = 0; ticket_read(hsq) != (uint32_t)gi;) {
-                    if constexpr (!LONG_RUNS) __builtin_amdgcn_s_sleep(1);     // (where runs are very long, the wait is all there is)
-                    if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
-                        ticket_write(&give_up, 1u);
-                        atomicExch(a.err, PS_ESTALL);
-                        break;
-                    }
-                }
-                compiler_fence();
-                // from here to the hand-over every other wavefront of the team waits for this one
-                __builtin_amdgcn_s_setprio(3);
-                // p_s = <w_s, h>: every lane its quarter of row n16 (four partial sums), then the four quarters together
-                f32x4 hq[NT];
-#pragma unroll
-                for (int j = 0; j < NT; ++j) hq[j] = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
-                // h as it is now, lane l its components l, l + 64 (lanes past the row's 16 NT floats: any)
-                float ho[NV];
-                int ck[NV];
-#pragma unroll
-                for (int cc = 0; cc < NV; ++cc) {
-                    ck[cc] = ln + 64 * cc < 16 * NT ? ln + 64 * cc : 0;
-                    ho[cc] = hsh[ck[cc]];
-                }
-                __builtin_amdgcn_sched_barrier(0);      // all of h asked for before the first product waits for its piece
-                float pq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xr[j][q], hq[j][q], pq[q]);
-                }
-                // the rows' components for the new h further down: asked for now, so that they arrive while the
-                // errors are being computed
-                float wv[CH][NV];
-#pragma unroll
-                for (int s = 0; s < CH; ++s)
-#pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) wv[s][cc] = stg[s * RS + ck[cc]];
-                __builtin_amdgcn_sched_barrier(0);
-                float p = (pq[0] + pq[1]) + (pq[2] + pq[3]);
-                // the four quarters of a row sit in the same lane of the four rows of 16 lanes: two lane swaps in
-                // the vector unit add them up and leave the sum in all four
-                p = add_across_halves(p);
-                p = add_across_row_pairs(p);
-                // The errors.  With p_s = <w_s, h> for the incoming h, the per-entry recursion e_t = v_t - <w_t, h_(t-1)>
-                // is the lower-triangular system
-                //     e_t = v_t - c^t p_t - sum_(u<t) lr c^(t-1-u) G[t][u] e_u,
-                // and in the scaled unknowns eps_t = e_t c^(-t) its coefficients lose their powers of c:
-                //     eps_t = v_t c^(-t) - p_t - sum_(u<t) (lr / c) G[t][u] eps_u.
-                // Lane (t, any hi) starts with acc = v_t c^(-t) - p_t; step u adds -(lr / c) G[t][u] eps_u, eps_u = acc of lane u
-                // (final after step u - 1) broadcast inside each row of 16 lanes by the multiply-add itself: one
-                // dependent instruction per entry.  The new h = c^k h + lr c^(k-1) sum_s eps_s w_s collects its terms
-                // along the way with the same broadcast.  Steps past the group's end work on rows of X that are
-                // zero and on finite values, so what they compute changes nothing that is used; the chain has no
-                // branches.  Lane 15 (the row of X that holds h) computes something finite that is never used.
-                float acc = vs - p;
-                float hs[NV];
-#pragma unroll
-                for (int cc = 0; cc < NV; ++cc) hs[cc] = 0.0f;
-                float hbase[NV];                           // c^k h
-#pragma unroll
-                for (int cc = 0; cc < NV; ++cc) hbase[cc] = __builtin_fmaf(cpm1_k, ho[cc], ho[cc]);
-                solve_first();
-                solve_step<0, NV>(acc, hs, wv[0], nl[0]);   solve_step<1, NV>(acc, hs, wv[1], nl[1]);
-                solve_step<2, NV>(acc, hs, wv[2], nl[2]);   solve_step<3, NV>(acc, hs, wv[3], nl[3]);
-                solve_step<4, NV>(acc, hs, wv[4], nl[4]);   solve_step<5, NV>(acc, hs, wv[5], nl[5]);
-                solve_step<6, NV>(acc, hs, wv[6], nl[6]);   solve_step<7, NV>(acc, hs, wv[7], nl[7]);
-                solve_step<8, NV>(acc, hs, wv[8], nl[8]);   solve_step<9, NV>(acc, hs, wv[9], nl[9]);
-                solve_step<10, NV>(acc, hs, wv[10], nl[10]); solve_step<11, NV>(acc, hs, wv[11], nl[11]);
-                solve_step<12, NV>(acc, hs, wv[12], nl[12]); solve_step<13, NV>(acc, hs, wv[13], nl[13]);
-                solve_last<14, NV>(acc, hs, wv[14]);
-                static_assert(CH == 15, "the solve above is written out for 15 entries");
-                float hn[NV];                              // the new h = c^k h + lr c^(k-1) sum_s eps_s w_s
-#pragma unroll
-                for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(lrck, hs[cc], hbase[cc]);
-                // the new h is complete: into LDS for the next group, which may start at once
+                float e_vec = 0.0f;                        // e_t in every lane with n16 == t
                 {
+                    // table entries for the new h, read before the wait as well
+                    float cpm1_k = cpm1[k];
+                    float lrck = lr * cpow[k > 0 ? k - 1 : 0];                            // lr c^(k-1): what eps_s w_s weighs in the new h
+                    float cpm1_t = cpm1[n16];
+                    // (all of this is computed here, ahead of the wait, not where it is first used)
+#pragma unroll
+                    for (int u = 0; u < CH - 1; ++u) __asm__ volatile("" : "+v"(nl[u]));
+                    __asm__ volatile("" : "+v"(vs), "+v"(cpm1_k), "+v"(lrck), "+v"(cpm1_t));
+                    // (this lane's quarter of row n16, for the inner products with h below, is xp: still in registers)
+                    __builtin_amdgcn_sched_barrier(0);
+
+                    // ---- the part that needs h as the previous group left it --------------------------------
+                    f32x4 hq[NT];                          // h in quarters, for p_s = <w_s, h>
+                    float ho[NV];                          // h as it is now, lane l its components l, l + 64 (lanes past the row's 16 NT floats: any)
+                    int ck[NV];
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) ck[cc] = ln + 64 * cc < 16 * NT ? ln + 64 * cc : 0;
+                    for (uint32_t spins = 0; ticket_read(hsq) != (uint32_t)gi;) {
+                        if constexpr (!LONG_RUNS) __builtin_amdgcn_s_sleep(1);     // (where runs are very long, the wait is all there is)
+                        if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                            ticket_write(&give_up, 1u);
+                            atomicExch(a.err, PS_ESTALL);
+                            break;
+                        }
+                    }
+                    compiler_fence();
+                    // from here to the hand-over every other wavefront of the team waits for this one
+                    __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) hq[j] = *reinterpret_cast<const f32x4 *>(&hsh[16 * j + 4 * hi]);
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) ho[cc] = hsh[ck[cc]];
+                    __builtin_amdgcn_sched_barrier(0);      // all of h asked for before the first product waits for its piece
+                    float pq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xp[j][q], hq[j][q], pq[q]);
+                    }
+                    // the rows' components for the new h further down: asked for now, so that they arrive while the
+                    // errors are being computed
+                    float wv[CH][NV];
+#pragma unroll
+                    for (int s = 0; s < CH; ++s)
+#pragma unroll
+                        for (int cc = 0; cc < NV; ++cc) wv[s][cc] = stg[s * RS + ck[cc]];
+                    __builtin_amdgcn_sched_barrier(0);
+                    float p = (pq[0] + pq[1]) + (pq[2] + pq[3]);
+                    // the four quarters of a row sit in the same lane of the four rows of 16 lanes: two lane swaps in
+                    // the vector unit add them up and leave the sum in all four
+                    p = add_across_halves(p);
+                    p = add_across_row_pairs(p);
+                    // The errors.  With p_s = <w_s, h> for the incoming h, the per-entry recursion e_t = v_t - <w_t, h_(t-1)>
+                    // is the lower-triangular system
+                    //     e_t = v_t - c^t p_t - sum_(u<t) lr c^(t-1-u) G[t][u] e_u,
+                    // and in the scaled unknowns eps_t = e_t c^(-t) its coefficients lose their powers of c:
+                    //     eps_t = v_t c^(-t) - p_t - sum_(u<t) (lr / c) G[t][u] eps_u.
+                    // Lane (t, any hi) starts with acc = v_t c^(-t) - p_t; step u adds -(lr / c) G[t][u] eps_u, eps_u = acc of lane u
+                    // (final after step u - 1) broadcast inside each row of 16 lanes by the multiply-add itself: one
+                    // dependent instruction per entry.  The new h = c^k h + lr c^(k-1) sum_s eps_s w_s collects its terms
+                    // along the way with the same broadcast.  Steps past the group's end work on rows of X that are
+                    // zero and on finite values, so what they compute changes nothing that is used; the chain has no
+                    // branches.  Lane 15 (the row of X that holds h) computes something finite that is never used.
+                    float acc = vs - p;
+                    float hs[NV];
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) hs[cc] = 0.0f;
+                    float hbase[NV];                           // c^k h
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) hbase[cc] = __builtin_fmaf(cpm1_k, ho[cc], ho[cc]);
+                    solve_first();
+                    solve_step<0, NV>(acc, hs, wv[0], nl[0]);   solve_step<1, NV>(acc, hs, wv[1], nl[1]);
+                    solve_step<2, NV>(acc, hs, wv[2], nl[2]);   solve_step<3, NV>(acc, hs, wv[3], nl[3]);
+                    solve_step<4, NV>(acc, hs, wv[4], nl[4]);   solve_step<5, NV>(acc, hs, wv[5], nl[5]);
+                    solve_step<6, NV>(acc, hs, wv[6], nl[6]);   solve_step<7, NV>(acc, hs, wv[7], nl[7]);
+                    solve_step<8, NV>(acc, hs, wv[8], nl[8]);   solve_step<9, NV>(acc, hs, wv[9], nl[9]);
+                    solve_step<10, NV>(acc, hs, wv[10], nl[10]); solve_step<11, NV>(acc, hs, wv[11], nl[11]);
+                    solve_step<12, NV>(acc, hs, wv[12], nl[12]); solve_step<13, NV>(acc, hs, wv[13], nl[13]);
+                    solve_last<14, NV>(acc, hs, wv[14]);
+                    static_assert(CH == 15, "the solve above is written out for 15 entries");
+                    float hn[NV];                              // the new h = c^k h + lr c^(k-1) sum_s eps_s w_s
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) hn[cc] = __builtin_fmaf(lrck, hs[cc], hbase[cc]);
+                    // the new h is complete: into LDS for the next group, which may start at once
+                    {
+#pragma unroll
+                        for (int cc = 0; cc < NV; ++cc)
+                            if (ln + 64 * cc < L) hsh[ln + 64 * cc] = hn[cc];
+                        compiler_fence();
+                        ticket_write(hsq, (uint32_t)gi + 1u);
+                        compiler_fence();
+                        // to memory as the run's last group leaves it (an offset past the end writes nothing)
+#pragma unroll
+                        for (int cc = 0; cc < NV; ++cc) {
+                            const int off = (int)(ln + 64 * cc < L && gi + 1 == ng ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan);
+                            if constexpr (AGENT_H) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf, off, 0, AUX_SC1);
+                            else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf, off, 0, 0);
+                        }
+                        __builtin_amdgcn_s_setprio(2);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    // e_t = eps_t c^t in every lane with n16 == t, for the new rows below
+                    e_vec = __builtin_fmaf(acc, cpm1_t, acc);
+                    // this wavefront's copy of h as it was (row 15 of X), for the new rows below
 #pragma unroll
                     for (int cc = 0; cc < NV; ++cc)
-                        if (ln + 64 * cc < L) hsh[ln + 64 * cc] = hn[cc];
-                    compiler_fence();
-                    ticket_write(hsq, (uint32_t)gi + 1u);
-                    compiler_fence();
-                    // to memory as the run's last group leaves it (an offset past the end writes nothing)
-#pragma unroll
-                    for (int cc = 0; cc < NV; ++cc) {
-                        const int off = (int)(ln + 64 * cc < L && gi + 1 == ng ? hoff + (uint32_t)(ln + 64 * cc) * 4u : hspan);
-                        if constexpr (AGENT_H) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf, off, 0, AUX_SC1);
-                        else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn[cc]), hbuf, off, 0, 0);
-                    }
-                    __builtin_amdgcn_s_setprio(2);
+                        if (ln + 64 * cc < 16 * NT) stg[15 * RS + ln + 64 * cc] = ho[cc];
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                // e_t = eps_t c^t in every lane with n16 == t, for the new rows below
-                const float e_vec = __builtin_fmaf(acc, cpm1_t, acc);
                 // read ahead: the rows of this wavefront's next group, the per-entry data of the one after (not
                 // earlier: the registers they arrive in are needed by the part above)
                 {
@@ -498,10 +505,6 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                     plan(p2 - p1, n16, hi);
                     meta_load(s0 + gs(gi + 2 * T));
                 }
-                // this wavefront's copy of h as it was (row 15 of X), for the new rows below
-#pragma unroll
-                for (int cc = 0; cc < NV; ++cc)
-                    if (ln + 64 * cc < 16 * NT) stg[15 * RS + ln + 64 * cc] = ho[cc];
 
                 // ---- the new rows: X' = X + (C - I) X, tile by tile; rows 0 .. k-1 go to the store ----------
                 // The product is formed transposed (X'^T = X^T (C - I)^T + X^T), which leaves lane (n16, hi) with
@@ -510,28 +513,46 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                 // row factors (past the end for rows without an entry, row 15 among them):
                 const uint32_t dst = n16 < k ? (uint32_t)((bperm_i(c_row, n16) - (int)blk_r0) * L + 4 * hi) * 4u : wspan;
                 float ca[4];                               // (C - I)[t = n16][s = 4 hi + v]; row 15 is not needed any more
+                {
+                    // (the exchanges and the table reads all first, then the arithmetic: one wait for LDS, not eight)
+                    float es_all[4], cp[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int s = 4 * hi + v;
-                    const float es_all = bperm_f(e_vec, s);   // lane s (< 16) holds e_s (all lanes take part in the exchange)
-                    const float es = s < k ? es_all : 0.0f;
-                    // C[t][s<t] = lr^2 e_t e_s c^(t-1-s),  C[t][t] - 1 = -lr lambda,  C[t][15] = lr e_t c^t
-                    const int t = n16, pw = s == 15 ? t : t - 1 - s;
-                    const float cp = cpow[pw > 0 ? pw : 0];
-                    float x = 0.0f;
-                    if (s < t) x = (lr * e_vec) * (lr * es) * cp;
-                    if (s == t) x = -delta;
-                    if (s == 15) x = lr * e_vec * cp;
-                    ca[v] = t < 15 ? x : 0.0f;
+                    for (int v = 0; v < 4; ++v) es_all[v] = bperm_f(e_vec, 4 * hi + v);   // lane s (< 16) holds e_s (all lanes take part in the exchange)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int s = 4 * hi + v, pw = s == 15 ? n16 : n16 - 1 - s;
+                        cp[v] = cpow[pw > 0 ? pw : 0];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int s = 4 * hi + v, t = n16;
+                        const float es = s < k ? es_all[v] : 0.0f;
+                        // C[t][s<t] = lr^2 e_t e_s c^(t-1-s),  C[t][t] - 1 = -lr lambda,  C[t][15] = lr e_t c^t
+                        float x = 0.0f;
+                        if (s < t) x = (lr * e_vec) * (lr * es) * cp[v];
+                        if (s == t) x = -delta;
+                        if (s == 15) x = lr * e_vec * cp[v];
+                        ca[v] = t < 15 ? x : 0.0f;
+                    }
                 }
+                // all of X is asked for (both layouts) before the first product waits for its operands: a tile's
+                // four matrix instructions depend on each other, and seven trips to LDS in between would double
+                // the time of this part
+                float xn[NT][4];
+                f32x4 xa[NT];
 #pragma unroll
                 for (int tile = 0; tile < NT; ++tile) {
-                    float xn[4];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) xn[v] = stg[(4 * hi + v) * RS + 16 * tile + n16];
-                    f32x4 acc = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * tile + 4 * hi]);   // the X of X + (C - I) X
+                    for (int v = 0; v < 4; ++v) xn[tile][v] = stg[(4 * hi + v) * RS + 16 * tile + n16];
+                    xa[tile] = *reinterpret_cast<const f32x4 *>(&stg[n16 * RS + 16 * tile + 4 * hi]);   // the X of X + (C - I) X
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xn[v], ca[v], acc, 0, 0, 0);
+                for (int tile = 0; tile < NT; ++tile) {
+                    f32x4 acc = xa[tile];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xn[tile][v], ca[v], acc, 0, 0, 0);
                     if constexpr (A4) {
                         const bool comp = tile < NT - 1 || 16 * tile + 4 * hi < L;    // the piece exists (the rank is a multiple of 4)
                         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc), wbuf, (int)(comp ? dst : wspan) + 64 * tile, 0, 0);
@@ -568,36 +589,185 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     // waits for one particular entry, so the lowest unfinished entry of the block is always processed
     // in its wavefront's next round: every wait ends.
     __builtin_amdgcn_s_setprio(1);
-    if (tr1 > tr0) {
-        constexpr int D = 4;
-        const int ntrow = (int)(tr1 - tr0);
-        for (;;) {
-            int jb = 0;
-            if (lane == 0) jb = atomicAdd(&next_trow, D);
-            jb = __builtin_amdgcn_readfirstlane(jb);
-            if (jb >= ntrow) break;
-            // lane i < D: row run jb + i
-            int r_row = -1;
-            uint32_t r_e0 = 0, r_e1 = 0, r_wait = 0xFFFFFFFFu;
-            if (lane < D && jb + lane < ntrow) {
-                r_row = a.trun_row[tr0 + jb + lane]; r_e0 = a.trun_start[tr0 + jb + lane]; r_e1 = a.trun_start[tr0 + jb + lane + 1];
-                r_wait = a.trun_wait[tr0 + jb + lane];
+    if constexpr (!LONG_RUNS) {
+        if (tr1 > tr0) {
+            constexpr int D = 4;
+            const int ntrow = (int)(tr1 - tr0);
+            for (;;) {
+                int jb = 0;
+                if (lane == 0) jb = atomicAdd(&next_trow, D);
+                jb = __builtin_amdgcn_readfirstlane(jb);
+                if (jb >= ntrow) break;
+                // lane i < D: row run jb + i
+                int r_row = -1;
+                uint32_t r_e0 = 0, r_e1 = 0, r_wait = 0xFFFFFFFFu;
+                if (lane < D && jb + lane < ntrow) {
+                    r_row = a.trun_row[tr0 + jb + lane]; r_e0 = a.trun_start[tr0 + jb + lane]; r_e1 = a.trun_start[tr0 + jb + lane + 1];
+                    r_wait = a.trun_wait[tr0 + jb + lane];
+                }
+                // entries of every row (one per lane) and its factor, once the row's entries in heavy runs are done
+                float w[D][NV], ev[D];
+                uint32_t ci[D], pos[D], wb[D];
+                uint32_t pend = 0;
+                bool stalled = false;
+#pragma unroll
+                for (int i = 0; i < D; ++i) {
+                    const int row = rl_i(r_row, i);
+                    const uint32_t e0 = (uint32_t)rl_i((int)r_e0, i), e1 = (uint32_t)rl_i((int)r_e1, i);
+                    const uint32_t wt = (uint32_t)rl_i((int)r_wait, i);
+                    ci[i] = 0; ev[i] = 0.0f; pos[i] = e0; wb[i] = e0;
+#pragma unroll
+                    for (int cc = 0; cc < NV; ++cc) w[i][cc] = 0.0f;
+                    if (e0 + lane < e1) { ci[i] = a.t_cinfo[e0 + lane]; ev[i] = a.t_val[e0 + lane]; }
+                    if (row >= 0 && !stalled) {
+                        if (wt != 0xFFFFFFFFu) {
+                            uint32_t *tk = &ticket[wt & 0xFFFFu];
+                            __builtin_amdgcn_s_setprio(0);
+                            for (uint32_t spins = 0; ticket_read(tk) != (wt >> 16);) {
+                                __builtin_amdgcn_s_sleep(4);
+                                if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                                    ticket_write(&give_up, 1u);
+                                    atomicExch(a.err, PS_ESTALL);
+                                    stalled = true;
+                                    break;
+                                }
+                            }
+                            __builtin_amdgcn_s_setprio(1);
+                        }
+                        if (!stalled) {
+                            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                            load_row_t<NV>(a.val + (int64_t)row * L, lane, tail, w[i]);
+                            pend |= 1u << i;
+                        }
+                    }
+                }
+                // rounds over the rows that still have entries; lane i holds the next entry of row i
+                uint32_t cur_ci = 0;
+#pragma unroll
+                for (int i = 0; i < D; ++i) {
+                    const uint32_t first = (uint32_t)rl_i((int)ci[i], 0);
+                    cur_ci = lane == i ? first : cur_ci;
+                }
+                uint32_t idle_rounds = 0;
+                while (pend != 0) {
+                    // lane i looks at the ticket of the column of row i's next entry
+                    uint32_t tkv = 0;
+                    if (lane < D) tkv = ticket_read(&ctick[cur_ci & 0xFFFFu]);
+                    const uint32_t ready = (uint32_t)__ballot(lane < D && ((pend >> lane) & 1u) != 0u && tkv == ((cur_ci >> 16) & 0x7FFFu));
+                    const bool any = ready != 0u;
+#pragma unroll
+                    for (int i = 0; i < D; ++i) {
+                        if (!((ready >> i) & 1u)) continue;         // done, or the column's earlier entries first
+                        const uint32_t cinfo = (uint32_t)rl_i((int)cur_ci, i);
+                        const uint32_t slot = cinfo & 0xFFFFu, seq = (cinfo >> 16) & 0x7FFFu;
+                        const float v = rl_f(ev[i], (int)(pos[i] - wb[i]));
+                        const uint32_t e1 = (uint32_t)rl_i((int)r_e1, i);
+                        uint32_t *tk = &ctick[slot];
+                        compiler_fence();
+                        // one step on the row's factor (registers) and the column's factor h
+                        auto step = [&](float (&h)[NV]) {
+                            float pr = 0.0f;
+#pragma unroll
+                            for (int cc = 0; cc < NV; ++cc) pr = __builtin_fmaf(w[i][cc], h[cc], pr);
+                            const float e = v - wave_sum(pr);
+#pragma unroll
+                            for (int cc = 0; cc < NV; ++cc) {
+                                const float wo = w[i][cc], ho = h[cc];
+                                w[i][cc] = __builtin_fmaf(lr, __builtin_fmaf(e, ho, -(lambda * wo)), wo);
+                                h[cc] = __builtin_fmaf(lr, __builtin_fmaf(e, wo, -(lambda * ho)), ho);
+                            }
+                        };
+                        float h[NV];
+                        if (slot < (uint32_t)ncached) {            // the column's factor lives in LDS
+                            float *hl = hcache + (size_t)slot * L;
+                            load_row_t<NV>(hl, lane, tail, h);
+                            step(h);
+                            store_row_t<NV>(hl, lane, tail, h);
+                            compiler_fence();
+                        } else {                                   // did not fit: handed over through memory
+                            float *hg = a.val + (a.m + a.run_col[run0 + nheavy + slot]) * (int64_t)L;
+                            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                            load_row_t<NV, AGENT_H>(hg, lane, tail, h);
+                            step(h);
+                            store_row_t<NV, AGENT_H>(hg, lane, tail, h);
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                        }
+                        ticket_write(tk, seq + 1u);
+                        ++pos[i];
+                        ++done;
+                        if (pos[i] == e1) {
+                            store_row_t<NV>(a.val + (int64_t)rl_i(r_row, i) * L, lane, tail, w[i]);
+                            pend &= ~(1u << i);
+                        } else {
+                            if (pos[i] - wb[i] >= 64u) {       // a row with more than 64 entries here: next 64
+                                wb[i] = pos[i];
+                                ci[i] = 0; ev[i] = 0.0f;
+                                if (wb[i] + lane < e1) { ci[i] = a.t_cinfo[wb[i] + lane]; ev[i] = a.t_val[wb[i] + lane]; }
+                            }
+                            const uint32_t nx = (uint32_t)rl_i((int)ci[i], (int)(pos[i] - wb[i]));
+                            cur_ci = lane == i ? nx : cur_ci;
+                        }
+                    }
+                    if (any) {
+                        idle_rounds = 0;
+                    } else {
+                        __builtin_amdgcn_s_sleep(1);
+                        if ((++idle_rounds & 1023u) == 0 && (idle_rounds > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                            ticket_write(&give_up, 1u);
+                            atomicExch(a.err, PS_ESTALL);
+                            break;
+                        }
+                    }
+                }
+                if (stalled) break;
             }
-            // entries of every row (one per lane) and its factor, once the row's entries in heavy runs are done
-            float w[D][NV], ev[D];
-            uint32_t ci[D], pos[D], wb[D];
-            uint32_t pend = 0;
+        }
+    } else {
+        // The same for data whose rows mostly have a single entry in a block.  What counts there is the number of
+        // trips to memory a wavefront makes one after the other, so: batches of 8 rows; a row run's record holds its
+        // first entry, and the records of the next batch are read while the current one is worked on; the column
+        // factor of a first entry that is also its column's first entry in the block (nobody writes it before) is asked
+        // for together with the row's factor; the rows of a round whose column factors are in memory are taken together
+        // (loads, steps, stores); and a column's last entry in the block leaves no ticket and waits for no store.
+        if (tr1 > tr0) {
+            constexpr int D = 8;
+            const int ntrow = (int)(tr1 - tr0);
+            int n_jb = 0, n_row = -1, n_col = 0;
+            uint32_t n_e0 = 0, n_e1 = 0, n_wait = 0xFFFFFFFFu, n_ci = 0;
+            float n_val = 0.0f;
+            auto claim = [&]() {                                 // takes the next batch; lane i < D: the record of row run n_jb + i
+                int j = 0;
+                if (lane == 0) j = atomicAdd(&next_trow, D);
+                n_jb = __builtin_amdgcn_readfirstlane(j);
+                n_row = -1; n_col = 0; n_e0 = 0; n_e1 = 0; n_wait = 0xFFFFFFFFu; n_ci = 0; n_val = 0.0f;
+                if (lane < D && n_jb + lane < ntrow) {
+                    const int64_t q = tr0 + n_jb + lane;
+                    n_row = a.trun_row[q]; n_e0 = a.trun_start[q]; n_e1 = a.trun_start[q + 1]; n_wait = a.trun_wait[q];
+                    n_ci = a.trun_ci[q]; n_val = a.trun_val[q]; n_col = a.trun_col[q];
+                }
+            };
+            claim();
+            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
             bool stalled = false;
+            while (n_jb < ntrow && !stalled) {
+                const int r_row = n_row, f_col = n_col;
+                const uint32_t r_e0 = n_e0, r_e1 = n_e1, r_wait = n_wait, f_ci = n_ci;
+                const float f_val = n_val;
+                claim();
+                // the rows' factors once the heavy runs have passed them, the column factors that can be asked for
+                // already, and the entries of rows that have more than one
+                float w[D][NV], hc[D][NV], ev[D];
+                uint32_t ci[D], pos[D], wb[D];
+                uint32_t pend = 0, spec = 0, first = 0;
 #pragma unroll
-            for (int i = 0; i < D; ++i) {
-                const int row = rl_i(r_row, i);
-                const uint32_t e0 = (uint32_t)rl_i((int)r_e0, i), e1 = (uint32_t)rl_i((int)r_e1, i);
-                const uint32_t wt = (uint32_t)rl_i((int)r_wait, i);
-                ci[i] = 0; ev[i] = 0.0f; pos[i] = e0; wb[i] = e0;
+                for (int i = 0; i < D; ++i) {
+                    const int row = rl_i(r_row, i);
+                    const uint32_t e0 = (uint32_t)rl_i((int)r_e0, i), e1 = (uint32_t)rl_i((int)r_e1, i);
+                    const uint32_t wt = (uint32_t)rl_i((int)r_wait, i);
+                    ci[i] = 0; ev[i] = 0.0f; pos[i] = e0; wb[i] = e0;
 #pragma unroll
-                for (int cc = 0; cc < NV; ++cc) w[i][cc] = 0.0f;
-                if (e0 + lane < e1) { ci[i] = a.t_cinfo[e0 + lane]; ev[i] = a.t_val[e0 + lane]; }
-                if (row >= 0 && !stalled) {
+                    for (int cc = 0; cc < NV; ++cc) { w[i][cc] = 0.0f; hc[i][cc] = 0.0f; }
+                    if (row < 0 || stalled) continue;
                     if (wt != 0xFFFFFFFFu) {
                         uint32_t *tk = &ticket[wt & 0xFFFFu];
                         __builtin_amdgcn_s_setprio(0);
@@ -611,39 +781,64 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                             }
                         }
                         __builtin_amdgcn_s_setprio(1);
+                        if (stalled) continue;
                     }
-                    if (!stalled) {
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                        load_row_t<NV>(a.val + (int64_t)row * L, lane, tail, w[i]);
-                        pend |= 1u << i;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                    load_row_t<NV>(a.val + (int64_t)row * L, lane, tail, w[i]);
+                    pend |= 1u << i;
+                    first |= 1u << i;
+                    const uint32_t fci = (uint32_t)rl_i((int)f_ci, i);
+                    if ((fci & 0xFFFFu) >= (uint32_t)ncached && ((fci >> 16) & 0x7FFFu) == 0u) {
+                        load_row_t<NV, AGENT_H>(a.val + (a.m + rl_i(f_col, i)) * (int64_t)L, lane, tail, hc[i]);
+                        spec |= 1u << i;
                     }
+                    if (e1 - e0 > 1u && e0 + lane < e1) { ci[i] = a.t_cinfo[e0 + lane]; ev[i] = a.t_val[e0 + lane]; }
                 }
-            }
-            // rounds over the rows that still have entries; lane i holds the next entry of row i
-            uint32_t cur_ci = 0;
-#pragma unroll
-            for (int i = 0; i < D; ++i) {
-                const uint32_t first = (uint32_t)rl_i((int)ci[i], 0);
-                cur_ci = lane == i ? first : cur_ci;
-            }
-            uint32_t idle_rounds = 0;
-            while (pend != 0) {
-                // lane i looks at the ticket of the column of row i's next entry
-                uint32_t tkv = 0;
-                if (lane < D) tkv = ticket_read(&ctick[cur_ci & 0xFFFFu]);
-                const uint32_t ready = (uint32_t)__ballot(lane < D && ((pend >> lane) & 1u) != 0u && tkv == (cur_ci >> 16));
-                const bool any = ready != 0u;
-#pragma unroll
-                for (int i = 0; i < D; ++i) {
-                    if (!((ready >> i) & 1u)) continue;         // done, or the column's earlier entries first
-                    const uint32_t cinfo = (uint32_t)rl_i((int)cur_ci, i);
-                    const uint32_t slot = cinfo & 0xFFFFu, seq = cinfo >> 16;
-                    const float v = rl_f(ev[i], (int)(pos[i] - wb[i]));
-                    const uint32_t e1 = (uint32_t)rl_i((int)r_e1, i);
-                    uint32_t *tk = &ctick[slot];
+                // Everything asked for so far is waited for here, once: the counter of outstanding memory operations
+                // also counts stores, and a wait placed inside the rounds would wait for those in every round.
+                __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+                uint32_t cur_ci = f_ci;                       // lane i: the next entry of row i
+                uint32_t idle_rounds = 0;
+                while (pend != 0) {
+                    uint32_t tkv = 0;
+                    if (lane < D) tkv = ticket_read(&ctick[cur_ci & 0xFFFFu]);
+                    const uint32_t ready = (uint32_t)__ballot(lane < D && ((pend >> lane) & 1u) != 0u && tkv == ((cur_ci >> 16) & 0x7FFFu));
+                    if (ready == 0u) {
+                        __builtin_amdgcn_s_sleep(1);
+                        if ((++idle_rounds & 1023u) == 0 && (idle_rounds > (1u << 21) || ticket_read(&give_up) != 0u)) {
+                            ticket_write(&give_up, 1u);
+                            atomicExch(a.err, PS_ESTALL);
+                            stalled = true;
+                            break;
+                        }
+                        continue;
+                    }
+                    idle_rounds = 0;
                     compiler_fence();
-                    // one step on the row's factor (registers) and the column's factor h
-                    auto step = [&](float (&h)[NV]) {
+                    // what a row's entry leaves behind: its place in the row, the row's factor after its last entry
+                    auto advance = [&](int i) {
+                        const uint32_t e1 = (uint32_t)rl_i((int)r_e1, i);
+                        ++pos[i];
+                        ++done;
+                        first &= ~(1u << i);
+                        spec &= ~(1u << i);
+                        if (pos[i] == e1) {
+                            store_row_t<NV>(a.val + (int64_t)rl_i(r_row, i) * L, lane, tail, w[i]);
+                            pend &= ~(1u << i);
+                        } else {
+                            if (pos[i] - wb[i] >= 64u) {       // a row with more than 64 entries here: next 64
+                                wb[i] = pos[i];
+                                ci[i] = 0; ev[i] = 0.0f;
+                                if (wb[i] + lane < e1) { ci[i] = a.t_cinfo[wb[i] + lane]; ev[i] = a.t_val[wb[i] + lane]; }
+                                __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): see above
+                            }
+                            const uint32_t nx = (uint32_t)rl_i((int)ci[i], (int)(pos[i] - wb[i]));
+                            cur_ci = lane == i ? nx : cur_ci;
+                        }
+                    };
+                    // one step on row i's factor (registers) and the column's factor h
+                    auto step = [&](int i, float (&h)[NV]) {
+                        const float v = (first >> i) & 1u ? rl_f(f_val, i) : rl_f(ev[i], (int)(pos[i] - wb[i]));
                         float pr = 0.0f;
 #pragma unroll
                         for (int cc = 0; cc < NV; ++cc) pr = __builtin_fmaf(w[i][cc], h[cc], pr);
@@ -655,49 +850,61 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                             h[cc] = __builtin_fmaf(lr, __builtin_fmaf(e, wo, -(lambda * ho)), ho);
                         }
                     };
-                    float h[NV];
-                    if (slot < (uint32_t)ncached) {            // the column's factor lives in LDS
-                        float *hl = hcache + (size_t)slot * L;
+                    const uint32_t slot_v = cur_ci & 0xFFFFu;
+                    // rows whose column factor did not fit in LDS: it is handed over through memory
+                    const uint32_t in_mem = ready & (uint32_t)__ballot(lane < D && slot_v >= (uint32_t)ncached);
+                    // the columns that live in LDS, one after the other; each is handed on at once
+#pragma unroll
+                    for (int i = 0; i < D; ++i) {
+                        if (!(((ready & ~in_mem) >> i) & 1u)) continue;
+                        const uint32_t cinfo = (uint32_t)rl_i((int)cur_ci, i);
+                        float *hl = hcache + (size_t)(cinfo & 0xFFFFu) * L;
+                        float h[NV];
                         load_row_t<NV>(hl, lane, tail, h);
-                        step(h);
+                        step(i, h);
                         store_row_t<NV>(hl, lane, tail, h);
                         compiler_fence();
-                    } else {                                   // did not fit: handed over through memory
-                        float *hg = a.val + (a.m + a.run_col[run0 + nheavy + slot]) * (int64_t)L;
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                        load_row_t<NV, AGENT_H>(hg, lane, tail, h);
-                        step(h);
-                        store_row_t<NV, AGENT_H>(hg, lane, tail, h);
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                        ticket_write(&ctick[cinfo & 0xFFFFu], ((cinfo >> 16) & 0x7FFFu) + 1u);
+                        advance(i);
                     }
-                    ticket_write(tk, seq + 1u);
-                    ++pos[i];
-                    ++done;
-                    if (pos[i] == e1) {
-                        store_row_t<NV>(a.val + (int64_t)rl_i(r_row, i) * L, lane, tail, w[i]);
-                        pend &= ~(1u << i);
-                    } else {
-                        if (pos[i] - wb[i] >= 64u) {       // a row with more than 64 entries here: next 64
-                            wb[i] = pos[i];
-                            ci[i] = 0; ev[i] = 0.0f;
-                            if (wb[i] + lane < e1) { ci[i] = a.t_cinfo[wb[i] + lane]; ev[i] = a.t_val[wb[i] + lane]; }
+                    if (in_mem != 0u) {
+                        const uint32_t old_ci = cur_ci;
+                        // A column's first entry in the block finds its factor as the last launch left it, and after
+                        // its last entry nobody in this block looks at the factor or its ticket again: the fences and
+                        // the ticket are for the entries in between (a column with one entry needs neither).
+                        const uint32_t to_load = in_mem & ~spec;
+                        const uint32_t not_first = to_load & (uint32_t)__ballot(lane < D && ((cur_ci >> 16) & 0x7FFFu) != 0u);
+                        const uint32_t not_last = in_mem & (uint32_t)__ballot(lane < D && (cur_ci >> 31) == 0u);
+                        // the columns: of a row's first entry from its record, of later entries looked up
+                        int32_t colv = f_col;
+                        if (lane < D && ((in_mem & ~first) >> lane) & 1u) colv = a.run_col[run0 + nheavy + slot_v];
+                        if (not_first != 0u) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                        int32_t col[D];
+#pragma unroll
+                        for (int i = 0; i < D; ++i) {
+                            col[i] = 0;
+                            if (!((in_mem >> i) & 1u)) continue;
+                            col[i] = rl_i(colv, i);
+                            if ((to_load >> i) & 1u) load_row_t<NV, AGENT_H>(a.val + (a.m + col[i]) * (int64_t)L, lane, tail, hc[i]);
                         }
-                        const uint32_t nx = (uint32_t)rl_i((int)ci[i], (int)(pos[i] - wb[i]));
-                        cur_ci = lane == i ? nx : cur_ci;
-                    }
-                }
-                if (any) {
-                    idle_rounds = 0;
-                } else {
-                    __builtin_amdgcn_s_sleep(1);
-                    if ((++idle_rounds & 1023u) == 0 && (idle_rounds > (1u << 21) || ticket_read(&give_up) != 0u)) {
-                        ticket_write(&give_up, 1u);
-                        atomicExch(a.err, PS_ESTALL);
-                        break;
+#pragma unroll
+                        for (int i = 0; i < D; ++i)
+                            if ((in_mem >> i) & 1u) step(i, hc[i]);
+#pragma unroll
+                        for (int i = 0; i < D; ++i)
+                            if ((in_mem >> i) & 1u) store_row_t<NV, AGENT_H>(a.val + (a.m + col[i]) * (int64_t)L, lane, tail, hc[i]);
+                        compiler_fence();
+                        if (not_last != 0u) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+#pragma unroll
+                        for (int i = 0; i < D; ++i) {
+                            if (!((in_mem >> i) & 1u)) continue;
+                            const uint32_t cinfo = (uint32_t)rl_i((int)old_ci, i);
+                            if ((not_last >> i) & 1u) ticket_write(&ctick[cinfo & 0xFFFFu], ((cinfo >> 16) & 0x7FFFu) + 1u);
+                            advance(i);
+                        }
                     }
                 }
             }
-            if (stalled) break;
         }
     }
     __builtin_amdgcn_s_setprio(0);
@@ -807,6 +1014,13 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_handoff(SgdArgs a) {
     }
 }
 
+// Which variant of the kernels the loaded data gets (LONG_RUNS): a column run of very many groups in some block, or
+// rows that mostly have a single entry per block - there the second part is bound by trips to memory, not by
+// the order of a row's entries.
+static bool dpaps_wide_like(const MfData &f) {
+    return f.max_run_groups >= DPAPS_LONG_RUN_GROUPS || (f.num_truns > 0 && 2 * f.num_tail < 3 * f.num_truns);
+}
+
 // LDS plan of sgd_block: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters,
 // then as many other column factors as fit.  Fills in a.ctick_cap, a.hcache_cap.
 template <int NT>
@@ -850,7 +1064,7 @@ static int launch_chunk_t(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStr
 
 template <int NT, bool A4>
 static int launch_chunk(dpaps_ps *ps, SgdArgs a, int ntasks, int waves, hipStream_t st) {
-    if (ps->mf.max_run_groups >= DPAPS_LONG_RUN_GROUPS)
+    if (dpaps_wide_like(ps->mf))
         return waves <= 12 ? launch_chunk_t<NT, A4, 768, true>(ps, a, ntasks, waves, st) : launch_chunk_t<NT, A4, 1024, true>(ps, a, ntasks, waves, st);
     return waves <= 12 ? launch_chunk_t<NT, A4, 768, false>(ps, a, ntasks, waves, st) : launch_chunk_t<NT, A4, 1024, false>(ps, a, ntasks, waves, st);
 }
@@ -903,7 +1117,7 @@ static int launch_handoff_t(dpaps_ps *ps, SgdArgs a, int workers, hipStream_t st
 
 template <int NT, bool A4>
 static int launch_handoff(dpaps_ps *ps, SgdArgs a, int workers, hipStream_t st) {
-    return ps->mf.max_run_groups >= DPAPS_LONG_RUN_GROUPS ? launch_handoff_t<NT, A4, true>(ps, a, workers, st)
+    return dpaps_wide_like(ps->mf) ? launch_handoff_t<NT, A4, true>(ps, a, workers, st)
                                                           : launch_handoff_t<NT, A4, false>(ps, a, workers, st);
 }
 

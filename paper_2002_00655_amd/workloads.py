@@ -269,15 +269,17 @@ def _split_by_weight(cum: np.ndarray, lo: int, hi: int, parts: int) -> np.ndarra
     return np.clip(b, lo, hi).astype(np.int64)
 
 
-def balanced_bounds(ids: np.ndarray, size: int, d: int, per_id: float = 0.0) -> np.ndarray:
+def balanced_bounds(ids: np.ndarray, size: int, d: int, per_id: float = 0.0, solo_frac: float = 1.0) -> np.ndarray:
     """Contiguous ranges holding roughly equal numbers of entries each.  per_id > 0: ranges of roughly equal
     weight, where an index weighs its number of entries plus per_id (for blocks whose processing time has a
-    part per row or column on top of the part per entry).  An index with more entries than an average range has
-    gets a range of its own - next to anything else it would only make the heaviest range heavier -, and the
-    other ranges are dealt out to the stretches between such indices in proportion to their weights."""
+    part per row or column on top of the part per entry).  An index with more entries than solo_frac times what
+    an average range has gets a range of its own - next to anything else it would only make the heaviest range
+    heavier (a range is cut where the running weight passes a multiple of the average, so an index of that
+    size makes its range that much larger) -, and the other ranges are dealt out to the stretches between such
+    indices in proportion to their weights."""
     deg = np.bincount(ids, minlength=size).astype(np.float64) + float(per_id)
     cum = np.concatenate([[0], np.cumsum(deg)])
-    solo = np.flatnonzero(deg - float(per_id) > ids.size / d)          # by entries alone, whatever else weighs
+    solo = np.flatnonzero(deg - float(per_id) > float(solo_frac) * ids.size / d)   # by entries alone, whatever else weighs
     if solo.size:
         # the stretches between the heavy indices, and how many ranges each gets: one each, the rest by weight
         starts = np.concatenate([[0], solo + 1])
