@@ -7,7 +7,10 @@ inputs (entries, factors, schedule) are resident in device memory before the
 timed region starts.  Prints ONE JSON line on stdout; everything else goes to
 stderr.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|medium|tiny|wide|complex] [--scale S]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload wide|large|medium|tiny|complex] [--scale S]
+
+The default workload is the largest configuration, wide (10M x 1M, 500M entries, rank 100); the large one
+(480,189 x 17,770, 100M entries) is run in the same call and reported under "other_workloads".
 """
 from __future__ import annotations
 
@@ -26,10 +29,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 
 # HBM bytes per launch of the SGD kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same
-# counters read for a plain 1 GiB copy; summary under profiles/).  Only valid for the kernel sources it was taken with.
+# counters read for a plain 1 GiB copy; summaries under profiles/).  Only valid for the kernel sources they were
+# taken with and for the default settings of the workload: bytes read, bytes written.
 KERNEL_SOURCES = ("mf_sgd_chunk.hip", "mf_sgd.hip", "mf_device.h", "common.h")
-TRAFFIC = {"kernel_sha256_16": "775275c2e86a7aaa", "workload": ("large", 1.0, "balanced", 8.0, 16, -1, 0, False),
-           "bytes_per_launch": 148.1e6 + 126.2e6}
+TRAFFIC = {"kernel_sha256_16": "", "bytes_per_launch": {"large": (0.0, 0.0), "wide": (0.0, 0.0)}}
+
+# block boundaries per workload: a column of a block weighs this many entries on top of its own (see --col-cost)
+COL_COST = {"wide": 4.0}
 
 
 def kernel_sources_hash():
@@ -40,42 +46,103 @@ def kernel_sources_hash():
     return h.hexdigest()[:16]
 
 
-def measured_traffic(args):
-    key = (args.workload, args.scale, args.bounds, args.col_cost, args.waves, args.cache_rows, args.heavy_len, args.entry_kernel or args.team_max > 0 or args.classic > 0 or args.handoff)
-    if kernel_sources_hash() == TRAFFIC["kernel_sha256_16"] and key == TRAFFIC["workload"]:
-        return TRAFFIC["bytes_per_launch"]
-    return None     # the kernel (or the workload) is not the one the counters were taken with
+def measured_traffic(args, name):
+    """(bytes read, bytes written) per launch from the committed counter runs, or None when the kernel sources or
+    the settings are not the ones the counters were taken with."""
+    default = (args.scale == 1.0 and args.bounds == "balanced" and args.col_cost is None and args.waves == 16 and args.cache_rows == -1
+               and args.heavy_len == 0 and args.team_max == 0 and not (args.entry_kernel or args.classic or args.handoff))
+    rw = TRAFFIC["bytes_per_launch"].get(name)
+    if default and rw and rw[0] > 0 and kernel_sources_hash() == TRAFFIC["kernel_sha256_16"]:
+        return rw
+    return None
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, rb, cb, d, target_seconds=15.0):
-    """The CPU oracle (fp32, one thread) timed on a bounded sample: the first
-    strata of one epoch, as many as fit the time target."""
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, rb, cb, d, target_seconds=10.0):
+    """The CPU oracle timed on a bounded sample of one epoch: the entries of the first K row blocks, i.e. K of the d
+    workers in every one of the d subepochs, K sized to the time target.  Once on one core - the oracle as it stands -
+    and once with the workers of a subepoch side by side on all cores (same result bit for bit: Sec. 2.2.2)."""
     from oracle.oracle import Oracle, mf_block_ratings
     from paper_2002_00655_amd import workloads as wl
-    sched = wl.cyclic_schedule(d)
-    rblk = np.searchsorted(rb, w.rows, side="right") - 1
-    cblk = np.searchsorted(cb, w.cols, side="right") - 1
-    shift = (cblk - rblk) % d                     # stratum of each entry under the cyclic schedule
-    per_stratum = np.bincount(shift, minlength=d)
-    assumed_rate = 4e6                            # only used to size the sample
-    ns = 1
-    while ns < d and per_stratum[:ns + 1].sum() <= assumed_rate * target_seconds:
-        ns += 1
-    sel = shift < ns
-    rows, cols, vals = w.rows[sel], w.cols[sel], w.vals[sel]
+    assumed_rate = 4e6                            # updates/s of one core, only used to size the sample
+    cores = os.cpu_count() or 1
+    K = int(round(assumed_rate * target_seconds / (w.nnz / d)))
+    K = max(1, min(d, max(K, min(cores, 16))))
+    hi = int(np.searchsorted(w.rows, rb[K], side="left"))      # the entries come sorted by (row, column)
+    rows, cols, vals = w.rows[:hi], w.cols[:hi], w.vals[:hi]
     br, bc, bv, bp = mf_block_ratings(w.m, w.n, rows, cols, vals, rb, cb)
-    orc = Oracle("f32", w.m + w.n, w.rank, d)
-    orc.push(np.arange(w.m), w.W0)
-    orc.push(w.m + np.arange(w.n), w.H0)
-    t0 = time.perf_counter()
-    orc.mf_sgd_epoch(w.m, w.n, br, bc, bv, rb, cb, bp, sched[:ns], w.lr, w.lam)
-    dt = time.perf_counter() - t0
-    return {"value": rows.size / dt, "unit": "updates/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {ns} of {d} strata of one epoch ({rows.size} updates, {dt:.1f} s), fp32 oracle, gcc -O2"}
+    sched = wl.cyclic_schedule(d)[:, :K]
+    out = {}
+    check = None
+    for leg in ("one_core", "all_cores"):
+        orc = Oracle("f32", w.m + w.n, w.rank, d)
+        orc.push(np.arange(w.m), w.W0)
+        orc.push(w.m + np.arange(w.n), w.H0)
+        t0 = time.perf_counter()
+        if leg == "one_core":
+            orc.mf_sgd_epoch(w.m, w.n, br, bc, bv, rb, cb, bp, sched, w.lr, w.lam)
+            used = 1
+        else:
+            used = orc.mf_sgd_epoch_workers(w.m, w.n, br, bc, bv, rb, cb, bp, sched, w.lr, w.lam)
+        dt = time.perf_counter() - t0
+        probe = orc.pull(np.arange(0, min(w.m, 4096)))
+        if check is None:
+            check = probe
+        elif not np.array_equal(check, probe):
+            raise RuntimeError("the all-core oracle run differs from the one-core run")
+        out[leg] = {"value": rows.size / dt, "cores": used, "seconds": dt}
+        del orc
+    return {"value": out["one_core"]["value"], "unit": "updates/s", "cores": 1, "kind": "oracle",
+            "sample": f"sample, not a full epoch: the first {K} of {d} row blocks (= {K} of the {d} workers) through all {d} subepochs "
+                      f"of one epoch, {rows.size} updates, {out['one_core']['seconds']:.1f} s on one core, fp32 oracle, gcc -O2",
+            "all_cores": {"value": out["all_cores"]["value"], "unit": "updates/s", "cores": out["all_cores"]["cores"],
+                          "seconds": out["all_cores"]["seconds"],
+                          "note": "same sample, the workers of a subepoch side by side (OpenMP), result identical to the one-core run"},
+            "nproc": cores, "cpu_model": cpu_model()}
+
+
+def chain_latency(P, torch, dev, rank, lr, lam):
+    """Measured time per update along one dependency chain of the SGD kernel: all entries of one column (one after
+    the other through that column's factor) and all entries of one row, each as a block of its own.  Every blocking
+    of a matrix leaves these chains intact, so (largest column degree) x (column figure) and (largest row degree) x
+    (row figure) bound an epoch from below whatever the bandwidth."""
+    out = []
+    for kind, nnz in (("column", 61440), ("row", 8000)):
+        idx = torch.arange(nnz, dtype=torch.int32, device=dev)
+        zero = torch.zeros(nnz, dtype=torch.int32, device=dev)
+        rows, cols = (idx, zero) if kind == "column" else (zero, idx)
+        m, n = (nnz, 1) if kind == "column" else (1, nnz)
+        g = torch.Generator(device=dev); g.manual_seed(1)
+        vals = torch.rand(nnz, device=dev, generator=g)
+        rb, cb = np.array([0, m], np.int64), np.array([0, n], np.int64)
+        br, bc, bv, bp = P.mf_block_ratings(m, n, rows, cols, vals, rb, cb)
+        srv = P.ParameterServer(m + n, rank, 1)
+        srv.push(torch.arange(m + n, device=dev), (torch.rand((m + n, rank), device=dev, generator=g) - 0.5) / rank ** 0.5)
+        srv.mf_load_ratings(m, n, br, bc, bv, rb, cb, bp)
+        sched = np.zeros((1, 1, 3), np.int32)
+        srv.mf_sgd_epoch(sched, lr, lam)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            srv.mf_sgd_epoch(sched, lr, lam)
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) / 5 / nnz * 1e9)
+        srv.status()
+        del srv
+    return out[0], out[1]
 
 
 def bench_kge(args, torch, dev) -> int:
@@ -259,13 +326,16 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "wide", "complex"])
+    ap.add_argument("--workload", default="wide", choices=["tiny", "medium", "large", "wide", "complex"])
+    ap.add_argument("--no-also-large", dest="also_large", action="store_false",
+                    help="with the default workload (wide): do not also run the large one")
     ap.add_argument("--batch", type=int, default=8192, help="positive triples per step (complex only)")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--bounds", default="balanced", choices=["equal", "balanced"],
                     help="block boundaries: ranges with equal numbers of entries (default; see --col-cost) or of equal length")
-    ap.add_argument("--col-cost", type=float, default=8.0,
-                    help="balanced bounds: a column of a block weighs this many entries on top of its own (0: entries only)")
+    ap.add_argument("--col-cost", type=float, default=None,
+                    help="balanced bounds: a column of a block weighs this many entries on top of its own (0: entries only; "
+                         "default: 8, wide 4)")
     ap.add_argument("--waves", type=int, default=16)
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
@@ -277,7 +347,7 @@ def main() -> int:
     ap.add_argument("--col-blocks", type=int, default=0, help="column blocks (0: as many as row blocks; other values need --handoff)")
     ap.add_argument("--entry-kernel", action="store_true", help="use the entry-by-entry SGD kernel instead of the grouped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="size of the CPU oracle's sample, in seconds of one core")
     ap.add_argument("--kge-epoch", action="store_true", help="only time knowledge-graph epochs over 1..8 workers (kge_sgd_epoch)")
     ap.add_argument("--ps-micro", action="store_true", help="only time the stand-alone pull / push / localize primitives")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -310,17 +380,38 @@ def main() -> int:
     if args.workload == "complex":
         return bench_kge(args, torch, dev)
 
+    primary = run_mf(args, args.workload, torch, dev, full=True)
+    if primary is None:
+        return 2
+    if args.workload == "wide" and args.also_large and args.scale == 1.0 and not (args.handoff or args.classic or args.entry_kernel):
+        # the other rank-100 configuration, in the same call (boundaries and kernel settings: its own defaults)
+        other = run_mf(args, "large", torch, dev, full=False)
+        if other is not None:
+            keep = ("value", "unit", "ms_per_step", "config", "model_frac_of_hbm_peak", "train_rmse", "roofline", "critical_path")
+            primary["other_workloads"] = {"large_mf": {k: other[k] for k in keep if k in other}}
+    print(json.dumps(primary), flush=True)
+    return 0
+
+
+def run_mf(args, name, torch, dev, full):
+    """One matrix-factorization workload: set-up, warm-up, the timed epochs, the roofline entry; with `full` also the
+    pull / push figure, the dependency-chain bound and the CPU oracle.  Returns the result (a dict), or None."""
+    from paper_2002_00655_amd import workloads as wl
+    from paper_2002_00655_amd import ps as P
     t0 = time.perf_counter()
-    w = wl.make_mf(args.workload, scale=args.scale)
+    w = wl.make_mf(name, scale=args.scale)
     d = w.d_row
     d_col = args.col_blocks if args.col_blocks > 0 else d
     if d_col != d and not args.handoff:
         print("bench.py: --col-blocks needs --handoff (the rotating schedule has as many column blocks as workers)", file=sys.stderr)
-        return 2
+        return None
+    col_cost = args.col_cost if args.col_cost is not None else COL_COST.get(name, 8.0)
     if args.bounds == "balanced":
-        rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d_col, per_id=args.col_cost * d)
+        rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d_col, per_id=col_cost * d)
     else:
         rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d_col)
+    max_col_deg = int(np.bincount(w.cols, minlength=w.n).max())
+    max_row_deg = int(np.bincount(w.rows, minlength=w.m).max())
     t_gen = time.perf_counter() - t0
     log(f"workload {w.name}: {w.m} x {w.n}, nnz {w.nnz}, rank {w.rank}, {d} x {d_col} blocks ({args.bounds}); generated in {t_gen:.1f} s")
 
@@ -368,12 +459,19 @@ def main() -> int:
 
     for _ in range(args.warmup):
         epoch()
+    # The timed region, between a synchronize on each side; an event at each end on the stream the kernels are
+    # launched on gives the stream's own time for the same region (no per-launch events: they cost a few
+    # microseconds each and would be timing themselves).
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev0.record()
     for _ in range(args.steps):
         epoch()
+    ev1.record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    stream_s = ev0.elapsed_time(ev1) * 1e-3
     srv.status()
     ms_per_step = dt / args.steps * 1e3
     updates_per_s = w.nnz * args.steps / dt
@@ -381,65 +479,78 @@ def main() -> int:
     log(f"{args.steps} epochs in {dt:.3f} s: {ms_per_step:.2f} ms/epoch, {updates_per_s / 1e9:.3f} G updates/s; "
         f"train rmse {rmse0:.4f} -> {rmse1:.4f}")
 
-    # duration of the dominant kernel (one launch per stratum), HIP events on the launch stream
-    prof_epochs = max(1, min(args.steps, 3))
-    if args.handoff:                               # one launch is one epoch
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ev0.record()
-        for _ in range(prof_epochs):
-            epoch()
-        ev1.record()
-        torch.cuda.synchronize()
-        sgd_ms, launches = ev0.elapsed_time(ev1), prof_epochs
-    else:
-        srv.set_option(P.OPT_MF_PROFILE, 1)
-        for _ in range(prof_epochs):
-            epoch()
-        sgd_ms, launches = srv.mf_profile_read()
-        srv.set_option(P.OPT_MF_PROFILE, 0)
+    # The dominant kernel: one launch per subepoch (per epoch with hand-over), nothing else on the stream in the timed
+    # region, so its average duration is the stream time of the region over the launches (it includes the gap
+    # between two launches, a microsecond or two: an upper bound of what a kernel trace shows).
+    launches = args.steps * (1 if args.handoff else d)
     bytes_per_update = 16 * w.rank + 12            # two rank-r fp32 rows read and written + the 12-byte entry
-    units_per_launch = w.nnz * prof_epochs / launches
-    avg_launch_s = sgd_ms * 1e-3 / launches
+    units_per_launch = w.nnz * args.steps / launches
+    avg_launch_s = stream_s / launches
     achieved = bytes_per_update * units_per_launch / avg_launch_s / 1e9
+    rw = measured_traffic(args, name)
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": measured_traffic(args), "traffic_unit": "bytes per launch", "kernel": kernel_name, "avg_launch_us": avg_launch_s * 1e6,
-                "bytes_per_update": bytes_per_update, "updates_per_launch": units_per_launch,
-                "note": "algorithmic bytes (model: 16r+12 per update), not bus traffic"}
-    log(f"{kernel_name}: {launches} launches, avg {avg_launch_s * 1e6:.1f} us, model {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
-
-    # pull + push rows per second through the C ABI (uniform random keys, value_len = rank)
-    n_keys = 1 << 22
-    g = torch.Generator(device=dev); g.manual_seed(0)
-    keys = torch.randint(0, w.m + w.n, (n_keys,), device=dev, generator=g)
-    deltas = torch.zeros((n_keys, w.rank), device=dev)
-    out = torch.empty((n_keys, w.rank), device=dev)
-    for rep in range(2):
-        torch.cuda.synchronize(); t0 = time.perf_counter()
-        for _ in range(5):
-            srv.pull(keys, 0, out=out)
-            srv.push(keys, deltas, 0)
-        torch.cuda.synchronize(); t_pp = (time.perf_counter() - t0) / 5
-    rows_per_s = 2 * n_keys / t_pp
+                "traffic": None if rw is None else rw[0] + rw[1], "traffic_unit": "bytes per launch", "kernel": kernel_name,
+                "avg_launch_us": avg_launch_s * 1e6, "launches": launches, "bytes_per_update": bytes_per_update,
+                "updates_per_launch": units_per_launch,
+                "model": "achieved = algorithmic bytes (16 r + 12 per update: two rank-r fp32 rows read and written, the 12-byte entry) "
+                         "per launch over the launch's duration; traffic = bytes the memory bus really moved per launch (rocprofv3 "
+                         "FETCH_SIZE + WRITE_SIZE), less than the algorithmic bytes where factors stay in LDS or in cache"}
+    if rw is not None:
+        roofline["traffic_read_write"] = list(rw)
+        roofline["measured_bus_gbs"] = (rw[0] + rw[1]) / avg_launch_s / 1e9
+        roofline["measured_bus_frac"] = roofline["measured_bus_gbs"] / HBM_PEAK_GBS
+    log(f"{kernel_name}: {launches} launches, avg {avg_launch_s * 1e6:.1f} us, model {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)"
+        + ("" if rw is None else f", memory bus {roofline['measured_bus_gbs']:.0f} GB/s ({100 * roofline['measured_bus_frac']:.1f}%)"))
 
     result = {
         "metric": "SGD updates/sec, MF rank %d" % w.rank, "value": updates_per_s, "unit": "updates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}_mf", "m": w.m, "n": w.n, "nnz": w.nnz, "rank": w.rank, "blocks": f"{d}x{d_col}",
-                   "bounds": args.bounds, "col_cost": args.col_cost, "lr": w.lr, "lambda": w.lam, "waves": args.waves, "kernel": kernel_name},
+                   "bounds": args.bounds, "col_cost": col_cost, "lr": w.lr, "lambda": w.lam, "waves": args.waves, "kernel": kernel_name},
         "model_gbs": updates_per_s * bytes_per_update / 1e9,
         "model_frac_of_hbm_peak": updates_per_s * bytes_per_update / 1e9 / HBM_PEAK_GBS,
-        "pull_push_rows_per_s": rows_per_s, "pull_push_keys_per_call": n_keys,
         "setup_ms": {"generate_host": t_gen * 1e3, "block_ratings": t_block * 1e3, "load_ratings": t_load * 1e3},
         "train_rmse": [rmse0, rmse1],
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+
+    if not (args.classic or args.entry_kernel) and w.rank <= 128:
+        # the dependency-chain bound: every entry of a column goes through that column's factor, one after the other,
+        # whatever the blocking, and likewise for a row
+        col_ns, row_ns = chain_latency(P, torch, dev, w.rank, w.lr, w.lam)
+        bound_s = max(max_col_deg * col_ns, max_row_deg * row_ns) * 1e-9
+        result["critical_path"] = {"max_col_degree": max_col_deg, "max_row_degree": max_row_deg, "ns_per_update_along_a_column": col_ns,
+                                   "ns_per_update_along_a_row": row_ns, "bound_ms_per_epoch": bound_s * 1e3,
+                                   "bound_updates_per_s": w.nnz / bound_s, "epoch_over_bound": ms_per_step / (bound_s * 1e3)}
+        log(f"dependency chains: busiest column {max_col_deg} entries x {col_ns:.1f} ns, busiest row {max_row_deg} x {row_ns:.1f} ns: "
+            f"an epoch takes at least {bound_s * 1e3:.1f} ms ({w.nnz / bound_s / 1e9:.2f} G updates/s); measured {ms_per_step:.1f} ms")
+
+    if full:
+        # pull + push rows per second through the C ABI (uniform random keys, value_len = rank)
+        n_keys = 1 << 22
+        g = torch.Generator(device=dev); g.manual_seed(0)
+        keys = torch.randint(0, w.m + w.n, (n_keys,), device=dev, generator=g)
+        deltas = torch.zeros((n_keys, w.rank), device=dev)
+        out = torch.empty((n_keys, w.rank), device=dev)
+        for rep in range(2):
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            for _ in range(5):
+                srv.pull(keys, 0, out=out)
+                srv.push(keys, deltas, 0)
+            torch.cuda.synchronize(); t_pp = (time.perf_counter() - t0) / 5
+        result["pull_push_rows_per_s"] = 2 * n_keys / t_pp
+        result["pull_push_keys_per_call"] = n_keys
+        del keys, deltas, out
+    del srv
+    torch.cuda.empty_cache()
+    if full and not args.no_cpu_baseline:
         log("timing the CPU oracle on a sample ...")
         result["cpu_baseline"] = cpu_baseline(w, rb, cb, d, args.cpu_seconds)
-        log(f"cpu oracle: {result['cpu_baseline']['value'] / 1e6:.2f} M updates/s ({result['cpu_baseline']['sample']})")
-    print(json.dumps(result), flush=True)
-    return 0
+        cbl = result["cpu_baseline"]
+        log(f"cpu oracle: {cbl['value'] / 1e6:.2f} M updates/s on one core, {cbl['all_cores']['value'] / 1e6:.2f} M on {cbl['all_cores']['cores']} "
+            f"({cbl['cpu_model']}, {cbl['nproc']} cores; {cbl['sample']})")
+    return result
 
 
 if __name__ == "__main__":

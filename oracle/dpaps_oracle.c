@@ -1,8 +1,9 @@
 /*
  * TEST INFRASTRUCTURE - NOT PART OF THE PRODUCT.
  *
- * Plain, slow, single-threaded CPU statement of what the parameter-server path
- * computes.  Only tests, the smoke check and the benchmark's CPU-baseline leg
+ * Plain, slow CPU statement of what the parameter-server path computes,
+ * single-threaded except for orc_mf_sgd_epoch_workers (a timing baseline that
+ * runs the independent workers of a subepoch on all cores).  Only tests, the smoke check and the benchmark's CPU-baseline leg
  * may load this file; the HIP library never does, and shares no code with it.
  *
  * Compiled twice: -DREAL=float (values and arithmetic in fp32, the precision
@@ -40,6 +41,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #ifndef REAL
 #define REAL float
@@ -386,6 +390,81 @@ int orc_mf_sgd_epoch(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, cons
                      int32_t num_strata, double lr_in, double lambda_in) {
     return mf_epoch(ps, m, n, rows, cols, vals, d_row, d_col, row_bounds, col_bounds, block_ptr, tasks, stratum_ptr,
                     num_strata, lr_in, lambda_in, 1);
+}
+
+/* The same epoch with the workers of a subepoch running side by side on the host's cores, as the workers of the
+ * paper do (Sec. 2.2.2: the blocks of a subepoch share no parameters, so their workers need not wait for each
+ * other; Appendix A: a barrier after each subepoch).  A timing baseline, kept equal to orc_mf_sgd_epoch bit for
+ * bit by tests: the relocation step is the same sequential code; a worker's entry loop is the loop above with
+ * pull (copy the two rows out), step and push (one addition per term) written out on the store - every access
+ * is checked to be local, which is all the routing there is to count - and its four access counters kept per
+ * thread and added up at the barrier.  threads <= 0: as many as the runtime offers. */
+int orc_mf_sgd_epoch_workers(orc_ps *ps, int64_t m, int64_t n, const int32_t *rows, const int32_t *cols, const float *vals,
+                             int32_t d_row, int32_t d_col, const int64_t *row_bounds, const int64_t *col_bounds,
+                             const int64_t *block_ptr, const int32_t *tasks, const int32_t *stratum_ptr,
+                             int32_t num_strata, double lr_in, double lambda_in, int32_t threads, int32_t *threads_used) {
+    if (!ps || m + n != ps->K || num_strata < 0) return ORC_EINVAL;
+    const int32_t L = ps->L;
+    const REAL lr = (REAL)lr_in, lambda = (REAL)lambda_in;
+    int rc = ORC_OK;
+    int used = 1;
+    for (int32_t s = 0; s < num_strata && rc == ORC_OK; ++s) {
+        int32_t t0 = stratum_ptr[s], t1 = stratum_ptr[s + 1];
+        /* validation and relocation: the sequential epoch's, with no entries to process */
+        {
+            int32_t one[2] = { 0, t1 - t0 };
+            int64_t *zero_ptr = (int64_t *)calloc((size_t)d_row * d_col + 1, sizeof(int64_t));
+            if (!zero_ptr) return ORC_ENOMEM;
+            rc = mf_epoch(ps, m, n, rows, cols, vals, d_row, d_col, row_bounds, col_bounds, zero_ptr, tasks + 3 * (int64_t)t0, one, 1,
+                          lr_in, lambda_in, 1);
+            free(zero_ptr);
+            if (rc) break;
+        }
+        int64_t pulls = 0, pushes = 0;
+        int bad = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads > 0 ? threads : omp_get_max_threads()) reduction(+ : pulls, pushes) reduction(| : bad)
+#endif
+        {
+            REAL *wh = (REAL *)malloc((size_t)4 * L * sizeof(REAL));
+            REAL *dwh = wh ? wh + 2 * L : NULL;
+            if (!wh) bad |= 2;
+#ifdef _OPENMP
+#pragma omp single
+            used = omp_get_num_threads();
+#pragma omp for schedule(dynamic, 1)
+#endif
+            for (int32_t t = t0; t < t1; ++t) {
+                if (!wh) continue;
+                int32_t w = tasks[3 * t], rb = tasks[3 * t + 1], cb = tasks[3 * t + 2];
+                int64_t b = (int64_t)rb * d_col + cb;
+                for (int64_t p = block_ptr[b]; p < block_ptr[b + 1]; ++p) {
+                    int64_t ki = rows[p], kj = m + cols[p];
+                    if (ps->owner[ki] != w || ps->owner[kj] != w) { bad |= 1; break; }      /* Sec. 4.1: all access is local */
+                    REAL *vw = ps->val + ki * L, *vh = ps->val + kj * L;
+                    for (int32_t k = 0; k < L; ++k) { wh[k] = vw[k]; wh[L + k] = vh[k]; }   /* pull */
+                    pulls += 2;
+                    const REAL *wv = wh, *hv = wh + L;
+                    REAL dot = 0;
+                    for (int32_t k = 0; k < L; ++k) dot = dot + wv[k] * hv[k];
+                    REAL e = (REAL)vals[p] - dot;
+                    for (int32_t k = 0; k < L; ++k) {
+                        dwh[k]     = lr * (e * hv[k] - lambda * wv[k]);
+                        dwh[L + k] = lr * (e * wv[k] - lambda * hv[k]);
+                    }
+                    for (int32_t k = 0; k < L; ++k) { vw[k] = vw[k] + dwh[k]; vh[k] = vh[k] + dwh[L + k]; }   /* push */
+                    pushes += 2;
+                }
+            }
+            free(wh);
+        }
+        ps->stats[ST_PULL_LOCAL] += pulls;
+        ps->stats[ST_PUSH_LOCAL] += pushes;
+        if (bad & 2) rc = ORC_ENOMEM;
+        else if (bad & 1) rc = ORC_EREMOTE;
+    }
+    if (threads_used) *threads_used = used;
+    return rc;
 }
 
 /* The same epoch on a classic parameter server (Sec. 2.1 "Basic PS Architectures": parameters are allocated

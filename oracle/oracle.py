@@ -14,7 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = [os.path.join(_HERE, "dpaps_oracle.c"), os.path.join(_HERE, "kge_oracle.c")]
-CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-std=c99", "-Wall"]
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-std=c99", "-Wall", "-fopenmp"]
 
 STAT_NAMES = ["pull_local", "pull_remote", "push_local", "push_remote", "relocated", "localize_keys",
               "msg_acc_req", "msg_acc_fwd", "msg_acc_reply", "msg_loc_req", "msg_loc_instruct", "msg_loc_transfer",
@@ -147,6 +147,29 @@ class Oracle:
             C.c_double(float(np.float32(lr))), C.c_double(float(np.float32(lam))))
         if rc:
             raise OracleError(rc, "mf_sgd_epoch")
+
+    def mf_sgd_epoch_workers(self, m, n, rows, cols, vals, row_bounds, col_bounds, block_ptr, schedule, lr, lam, threads: int = 0) -> int:
+        """The epoch with the workers of a subepoch on all host cores (same result as mf_sgd_epoch bit for bit);
+        returns the number of threads that ran."""
+        strata = [np.ascontiguousarray(s, dtype=np.int32).reshape(-1, 3) for s in schedule]
+        tasks = np.concatenate(strata) if strata else np.zeros((0, 3), np.int32)
+        sptr = np.concatenate([[0], np.cumsum([s.shape[0] for s in strata])]).astype(np.int32)
+        rb = np.ascontiguousarray(row_bounds, dtype=np.int64)
+        cb = np.ascontiguousarray(col_bounds, dtype=np.int64)
+        bp = np.ascontiguousarray(block_ptr, dtype=np.int64)
+        assert bp.size == (rb.size - 1) * (cb.size - 1) + 1
+        rows = np.ascontiguousarray(rows, dtype=np.int32)
+        cols = np.ascontiguousarray(cols, dtype=np.int32)
+        vals = np.ascontiguousarray(vals, dtype=np.float32)
+        used = C.c_int32(0)
+        rc = self.lib.orc_mf_sgd_epoch_workers(
+            C.c_void_p(self.h), C.c_int64(m), C.c_int64(n), _p(rows, C.c_int32), _p(cols, C.c_int32), _p(vals, C.c_float),
+            C.c_int32(rb.size - 1), C.c_int32(cb.size - 1), _p(rb, C.c_int64), _p(cb, C.c_int64), _p(bp, C.c_int64),
+            _p(tasks, C.c_int32), _p(sptr, C.c_int32), C.c_int32(len(strata)),
+            C.c_double(float(np.float32(lr))), C.c_double(float(np.float32(lam))), C.c_int32(threads), C.byref(used))
+        if rc:
+            raise OracleError(rc, "mf_sgd_epoch_workers")
+        return int(used.value)
 
     def mf_train_sse(self, m, rows, cols, vals) -> float:
         rows = np.ascontiguousarray(rows, dtype=np.int32)

@@ -263,6 +263,38 @@ def test_workers_of_a_subepoch_are_independent():
     assert not np.array_equal(a.pull(np.arange(w.m + w.n)), c.pull(np.arange(w.m + w.n)))
 
 
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+@pytest.mark.parametrize("threads", [1, 3, 0])
+def test_workers_on_all_cores_equal_the_sequential_epoch(prec, threads):
+    """The timing baseline that runs the workers of a subepoch side by side (Sec. 2.2.2: their blocks share no
+    parameters) leaves the server exactly as the sequential epoch does: values bit for bit, owner map, every
+    counter - over two epochs, with ragged blocks, an idle worker and a permuted schedule."""
+    d = 5
+    w = wl.make_mf("tiny", scale=0.4, seed=3)
+    rng = np.random.default_rng(7)
+    rb = np.concatenate([[0], np.sort(rng.choice(np.arange(1, w.m), d - 1, replace=False)), [w.m]])
+    cb = np.concatenate([[0], np.sort(rng.choice(np.arange(1, w.n), d - 1, replace=False)), [w.n]])
+    br, bc, bv, bp = mf_block_ratings(w.m, w.n, w.rows, w.cols, w.vals, rb, cb)
+    sched = [s[rng.permutation(d)][: d - (i % 2)] for i, s in enumerate(wl.cyclic_schedule(d)[rng.permutation(d)])]
+    a, b = Oracle(prec, w.m + w.n, w.rank, d + 1), Oracle(prec, w.m + w.n, w.rank, d + 1)
+    for o in (a, b):
+        _install(o, w.W0, w.H0)
+    for _ in range(2):
+        a.mf_sgd_epoch(w.m, w.n, br, bc, bv, rb, cb, bp, sched, w.lr, w.lam)
+        used = b.mf_sgd_epoch_workers(w.m, w.n, br, bc, bv, rb, cb, bp, sched, w.lr, w.lam, threads=threads)
+        assert used >= 1 and (threads == 0 or used == threads)
+    keys = np.arange(w.m + w.n)
+    assert np.array_equal(a.pull(keys), b.pull(keys))
+    assert np.array_equal(a.owner(), b.owner())
+    assert a.stats() == b.stats()
+    # a conflicting stratum is rejected by it as well, and changes nothing
+    bad = [np.array([[0, 0, 0], [1, 0, 1]], np.int32)]
+    with pytest.raises(OracleError) as e:
+        b.mf_sgd_epoch_workers(w.m, w.n, br, bc, bv, rb, cb, bp, bad, w.lr, w.lam)
+    assert e.value.code == ECONFLICT
+    assert np.array_equal(a.pull(keys), b.pull(keys)) and a.stats() == b.stats()
+
+
 def test_relocation_counts_of_the_rotating_assignment():
     """With worker b keeping row block b and taking column block (b+s) mod d:
     every stratum after the first relocates all n column keys and no row key;
