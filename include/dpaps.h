@@ -96,6 +96,9 @@ enum {
                                    are copied out of and back into the server); 2: the rows are updated in place.
                                    0 (default): dynamic parameter allocation.  The values are the same in all
                                    three; honours PS_OPT_MF_EXACT.  A comparison mode: one wavefront per task */
+    PS_OPT_KGE_EXACT = 11,      /* 1: kge_sgd_step / kge_sgd_epoch sum every score in index order and take the AdaGrad root in
+                                   double with a correctly rounded division (slow; together with PS_OPT_PUSH_SEQUENTIAL
+                                   the step then gives, bit for bit, what a sequential fp32 program gives).  default 0 */
     PS_OPT_LOCATION_CACHES = 10 /* 1: every node keeps a location cache, key -> node (Sec. 3.3 "Location caching", Fig.
                                    "routing" (c), (d)), for the message counts of remote pulls and pushes: with a
                                    correct entry the request goes straight to the owner (2 messages), with a stale
@@ -241,21 +244,24 @@ int mf_profile_read(ps_handle ps, double *sgd_ms_host_out, int64_t *launches_hos
 /* One mini-batch step of ComplEx training with AdaGrad and negative sampling, the AdaGrad accumulators stored in
  * the server next to the embeddings.  Entity e is key e, relation r is key num_entities + r; value_len = 4 * dim:
  * [0, dim) real parts, [dim, 2 dim) imaginary parts, [2 dim, 4 dim) the accumulators of those 2 dim numbers.
- * The batch has `batch` positive triples (subj, rel, obj: device arrays of int32 indices); triple b also has
- * n_neg_subj negatives that replace its subject by neg_subj[b * n_neg_subj + j] and n_neg_obj that replace its
- * object by neg_obj[b * n_neg_obj + j] (device; the paper perturbs both, 10 times).  The step pulls every key
- * occurrence (values as they are before the step), computes for every scored triple - label +1 for the positive,
- * -1 for a negative - score = Re sum_k e_s[k] w_r[k] conj(e_o[k]), loss = log(1 + exp(-label score)), its gradient g
- * for the 2 dim numbers of each of the three keys, and per occurrence dtheta = -lr g / sqrt(G + g^2 + eps) and
- * dG = g^2 (G: the pulled accumulator).  These are cumulative updates.  The terms one positive triple and its
- * negatives have for the same key slot (its subject: 1 + n_neg_obj terms, its relation: all, its object:
- * 1 + n_neg_subj) are added up in the order of their occurrences, and the batch then pushes 3 + n_neg_subj +
- * n_neg_obj rows per positive triple, in the order (triple of the batch; subject, relation, object, subject
- * negatives, object negatives) with ps_push's rule for repeated keys: the result depends on the arguments only.
- * Pull and push statistics count every key occurrence (3 per scored triple), as separate calls would.
+ * The batch has `batch` data points: positive triples (subj, rel, obj: device arrays of int32 indices), data point
+ * b with n_neg_subj negatives that replace its subject by neg_subj[b * n_neg_subj + j] and n_neg_obj that replace
+ * its object by neg_obj[b * n_neg_obj + j] (device; the paper perturbs both, 10 times).  A data point has
+ * 3 + n_neg_subj + n_neg_obj key slots: subject, relation, object, subject negatives, object negatives.  The step
+ * pulls the keys of all slots (values as they are before the step).  Per data point the loss is the sum over its
+ * scored triples - label +1 for the positive, -1 for a negative - of log(1 + exp(-label score)), score = Re sum_k
+ * e_s[k] w_r[k] conj(e_o[k]); the gradient g of that loss for the 2 dim numbers of a slot is the sum of the terms
+ * of the triples the slot occurs in (subject: the positive and every object negative; relation: all; object: the
+ * positive and every subject negative; a negative: its own), in the order positive, subject negatives, object
+ * negatives; and the slot takes one AdaGrad step, dtheta = -lr g / sqrt(G + g^2 + eps), dG = g^2 (G: the pulled
+ * accumulator) - AdaGrad per data point (Appendix A).  These are cumulative updates: the batch pushes one row per
+ * slot, in the order (data point; subject, relation, object, subject negatives, object negatives), with ps_push's
+ * rule for keys that fill several slots: the result depends on the arguments only.  Pull and push statistics
+ * count every slot, as a ps_pull and a ps_push of those keys would.
  * worker: as for ps_pull / ps_push (locality statistics).  loss_host_out (may be NULL): sum of the losses of all
  * scored triples; asking for it synchronizes the stream.  dim <= 256, 1 + n_neg_subj + n_neg_obj <= 64
- * (PS_ELIMIT).  Scratch is allocated by the library and grows with the batch. */
+ * (PS_ELIMIT).  Scratch is allocated by the library and grows with the batch (a call that outgrows it waits
+ * for the stream, frees and allocates). */
 int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, int32_t dim, int64_t batch, const int32_t *subj,
                  const int32_t *rel, const int32_t *obj, int32_t n_neg_subj, const int32_t *neg_subj, int32_t n_neg_obj,
                  const int32_t *neg_obj, float lr, float eps, double *loss_host_out, void *stream);

@@ -13,17 +13,22 @@
  * 4 D numbers: [0, D) real parts, [D, 2D) imaginary parts of the embedding,
  * [2D, 4D) the AdaGrad accumulators of those 2 D numbers.
  *
- * One step (a mini-batch of B positive triples (s, r, o), each with ns negatives
- * that replace the subject and no negatives that replace the object):
- *   1. pull every key occurrence of the batch (values as they are before the step);
- *   2. for every scored triple (positive: label +1, negative: label -1):
- *        score = Re sum_k e_s[k] w_r[k] conj(e_o[k])
- *        loss  = log(1 + exp(-label * score)),  dloss/dscore = -label * sigmoid(-label * score)
- *        g     = dloss/dscore * dscore/dtheta   for the 2 D numbers of each of its three keys;
- *        the occurrence's update is  dtheta = -lr * g / sqrt(G + g*g + eps),  dG = g*g
- *        with G the pulled accumulator (AdaGrad with the occurrence's own gradient);
- *   3. push all occurrences as cumulative deltas, in the order (triple of the
- *      batch, positive then subject-negatives then object-negatives, role s, r, o).
+ * One step (a mini-batch of B data points; a data point is a positive triple (s, r, o) with ns negatives that
+ * replace its subject and no negatives that replace its object - Appendix A: the negatives are derived from the
+ * data point, and the parameters a worker needs for a data point include those of its negatives).  A data point
+ * has 3 + ns + no key slots: subject, relation, object, each subject negative, each object negative.
+ *   1. pull the keys of all slots of the batch (values as they are before the step);
+ *   2. per data point, the loss is the sum over its scored triples (positive: label +1, negative: label -1) of
+ *        loss  = log(1 + exp(-label * score)),   score = Re sum_k e_s[k] w_r[k] conj(e_o[k]),
+ *        dloss/dscore = -label * sigmoid(-label * score);
+ *      the gradient g of that loss for the 2 D numbers of a slot is the sum, in the order of the scored triples
+ *      (positive, subject negatives, object negatives), of the terms of the triples the slot occurs in - the
+ *      subject in the positive triple and every object negative, the relation in all, the object in the positive
+ *      triple and every subject negative, a negative in its own triple;
+ *      AdaGrad, once per slot:  dtheta = -lr * g / sqrt(G + g*g + eps),  dG = g*g,  G the pulled accumulator;
+ *   3. push all slots as cumulative deltas, in the order (data point; subject, relation, object, subject
+ *      negatives, object negatives).  A key that fills several slots of the batch (in one data point or in
+ *      several) gets one term per slot, each from the accumulator as pulled.
  * Negatives are passed in (no random numbers are drawn here).
  *
  * Compiled twice: -DREAL=float and -DREAL=double.
@@ -53,62 +58,66 @@ REAL orc_kge_score(int32_t D, const REAL *es, const REAL *wr, const REAL *eo) {
     return acc;
 }
 
-/* number of key occurrences of a step */
-int64_t orc_kge_occurrences(int64_t B, int32_t ns, int32_t no) { return B * (1 + ns + no) * 3; }
+/* number of keys a step pulls (and pushes): the slots of its data points */
+int64_t orc_kge_occurrences(int64_t B, int32_t ns, int32_t no) { return B * (3 + ns + no); }
 
 /* One step.  loss_out (may be NULL): sum of the losses of all scored triples.  Returns the push's status. */
 int orc_kge_step(orc_ps *ps, int32_t worker, int64_t num_entities, int32_t D, int64_t B, const int32_t *subj, const int32_t *rel,
                  const int32_t *obj, int32_t ns, const int32_t *neg_subj, int32_t no, const int32_t *neg_obj, REAL lr, REAL eps,
                  double *loss_out) {
-    const int32_t L = 4 * D, per = 1 + ns + no;
-    const int64_t nocc = B * per * 3;
-    int64_t *keys = (int64_t *)malloc((size_t)(nocc > 0 ? nocc : 1) * sizeof(int64_t));
-    REAL *vals = (REAL *)malloc((size_t)(nocc > 0 ? nocc : 1) * L * sizeof(REAL));
-    REAL *delta = (REAL *)calloc((size_t)(nocc > 0 ? nocc : 1) * L, sizeof(REAL));
-    if (!keys || !vals || !delta) { free(keys); free(vals); free(delta); return -4; }
-    /* the occurrences, in the stated order */
+    const int32_t L = 4 * D, per = 1 + ns + no, slots = 3 + ns + no;
+    const int64_t nkeys = B * slots;
+    int64_t *keys = (int64_t *)calloc((size_t)(nkeys > 0 ? nkeys : 1), sizeof(int64_t));
+    REAL *vals = (REAL *)malloc((size_t)(nkeys > 0 ? nkeys : 1) * L * sizeof(REAL));
+    REAL *delta = (REAL *)calloc((size_t)(nkeys > 0 ? nkeys : 1) * L, sizeof(REAL));
+    REAL *grad = (REAL *)malloc((size_t)slots * 2 * D * sizeof(REAL));
+    if (!keys || !vals || !delta || !grad) { free(keys); free(vals); free(delta); free(grad); return -4; }
+    /* the slots, in the stated order */
     for (int64_t b = 0; b < B; ++b) {
-        for (int32_t j = 0; j < per; ++j) {
-            int64_t s = subj[b], o = obj[b];
-            if (j >= 1 && j <= ns) s = neg_subj[b * ns + (j - 1)];
-            if (j > ns) o = neg_obj[b * no + (j - 1 - ns)];
-            int64_t *k3 = keys + (b * per + j) * 3;
-            k3[0] = s; k3[1] = num_entities + rel[b]; k3[2] = o;
-        }
+        int64_t *kb = keys + b * slots;
+        kb[0] = subj[b]; kb[1] = num_entities + rel[b]; kb[2] = obj[b];
+        for (int32_t j = 0; j < ns; ++j) kb[3 + j] = neg_subj[b * ns + j];
+        for (int32_t j = 0; j < no; ++j) kb[3 + ns + j] = neg_obj[b * no + j];
     }
-    int rc = orc_ps_pull(ps, worker, keys, nocc, vals);
+    int rc = orc_ps_pull(ps, worker, keys, nkeys, vals);
     double loss = 0.0;
     if (rc == 0) {
-        for (int64_t t = 0; t < B * per; ++t) {
-            const REAL label = (t % per) == 0 ? (REAL)1 : (REAL)-1;
-            const REAL *es = vals + (t * 3 + 0) * L, *wr = vals + (t * 3 + 1) * L, *eo = vals + (t * 3 + 2) * L;
-            const REAL score = orc_kge_score(D, es, wr, eo);
-            const REAL z = -label * score;
-            /* log(1 + exp(z)) and sigmoid(z), written so that neither overflows */
-            const REAL sig = z >= 0 ? (REAL)1 / ((REAL)1 + (REAL)exp((double)-z)) : (REAL)exp((double)z) / ((REAL)1 + (REAL)exp((double)z));
-            loss += z >= 0 ? (double)z + log1p(exp((double)-z)) : log1p(exp((double)z));
-            const REAL dl = -label * sig;                         /* dloss / dscore */
-            for (int32_t k = 0; k < D; ++k) {
-                const REAL sr = es[k], si = es[D + k], rr = wr[k], ri = wr[D + k], or_ = eo[k], oi = eo[D + k];
-                REAL g[3][2];
-                g[0][0] = dl * (rr * or_ + ri * oi);  g[0][1] = dl * (rr * oi - ri * or_);      /* d/d Re e_s, d/d Im e_s */
-                g[1][0] = dl * (sr * or_ + si * oi);  g[1][1] = dl * (sr * oi - si * or_);      /* d/d Re w_r, d/d Im w_r */
-                g[2][0] = dl * (sr * rr - si * ri);   g[2][1] = dl * (si * rr + sr * ri);       /* d/d Re e_o, d/d Im e_o */
-                for (int role = 0; role < 3; ++role) {
-                    const REAL *v = vals + (t * 3 + role) * L;
-                    REAL *d = delta + (t * 3 + role) * L;
-                    for (int part = 0; part < 2; ++part) {
-                        const REAL gg = g[role][part], G = v[2 * D + part * D + k];
-                        d[part * D + k] = -lr * gg / (REAL)sqrt((double)(G + gg * gg + eps));
-                        d[2 * D + part * D + k] = gg * gg;
-                    }
+        for (int64_t b = 0; b < B; ++b) {
+            const REAL *vb = vals + b * slots * L;
+            for (int32_t i = 0; i < slots * 2 * D; ++i) grad[i] = 0;
+            for (int32_t j = 0; j < per; ++j) {                      /* the scored triples of the data point */
+                const int32_t slot_s = (j >= 1 && j <= ns) ? 3 + (j - 1) : 0;
+                const int32_t slot_o = j > ns ? 3 + ns + (j - 1 - ns) : 2;
+                const REAL label = j == 0 ? (REAL)1 : (REAL)-1;
+                const REAL *es = vb + slot_s * L, *wr = vb + 1 * L, *eo = vb + slot_o * L;
+                const REAL score = orc_kge_score(D, es, wr, eo);
+                const REAL z = -label * score;
+                /* log(1 + exp(z)) and sigmoid(z), written so that neither overflows */
+                const REAL sig = z >= 0 ? (REAL)1 / ((REAL)1 + (REAL)exp((double)-z)) : (REAL)exp((double)z) / ((REAL)1 + (REAL)exp((double)z));
+                loss += z >= 0 ? (double)z + log1p(exp((double)-z)) : log1p(exp((double)z));
+                const REAL dl = -label * sig;                         /* dloss / dscore */
+                REAL *gs = grad + slot_s * 2 * D, *gr = grad + 1 * 2 * D, *go = grad + slot_o * 2 * D;
+                for (int32_t k = 0; k < D; ++k) {
+                    const REAL sr = es[k], si = es[D + k], rr = wr[k], ri = wr[D + k], or_ = eo[k], oi = eo[D + k];
+                    gs[k] = gs[k] + dl * (rr * or_ + ri * oi);  gs[D + k] = gs[D + k] + dl * (rr * oi - ri * or_);   /* d/d Re e_s, d/d Im e_s */
+                    gr[k] = gr[k] + dl * (sr * or_ + si * oi);  gr[D + k] = gr[D + k] + dl * (sr * oi - si * or_);   /* d/d Re w_r, d/d Im w_r */
+                    go[k] = go[k] + dl * (sr * rr - si * ri);   go[D + k] = go[D + k] + dl * (si * rr + sr * ri);    /* d/d Re e_o, d/d Im e_o */
+                }
+            }
+            for (int32_t sl = 0; sl < slots; ++sl) {                  /* AdaGrad, once per slot */
+                const REAL *v = vb + sl * L;
+                REAL *d = delta + (b * slots + sl) * L;
+                for (int32_t i = 0; i < 2 * D; ++i) {
+                    const REAL gg = grad[sl * 2 * D + i], G = v[2 * D + i];
+                    d[i] = -lr * gg / (REAL)sqrt((double)(G + gg * gg + eps));
+                    d[2 * D + i] = gg * gg;
                 }
             }
         }
-        rc = orc_ps_push(ps, worker, keys, nocc, delta);
+        rc = orc_ps_push(ps, worker, keys, nkeys, delta);
     }
     if (loss_out) *loss_out = loss;
-    free(keys); free(vals); free(delta);
+    free(keys); free(vals); free(delta); free(grad);
     return rc;
 }
 

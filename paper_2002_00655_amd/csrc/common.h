@@ -101,6 +101,7 @@ struct dpaps_ps {
     int opt_classic = 0;              // 1, 2: mf_sgd_epoch as on a classic parameter server (2: updates in place)
     int opt_team_max = 4;             // most wavefronts that share one heavy run
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
+    int opt_kge_exact = 0;            // 1: the knowledge-graph step sums and divides in the order of a sequential fp32 program
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
     // event pairs around the SGD kernel launches (only while profiling is on)
     std::vector<hipEvent_t> ev_pool;

@@ -20,49 +20,49 @@
 
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
 
-// the key occurrences of the batch, in push order: triple of the batch, then positive /
-// subject-negatives / object-negatives, then role (subject, relation, object); and, if asked for, the keys of
-// the update rows (per positive triple: subject, relation, object, subject negatives, object negatives)
+// the keys of the batch, in pull and push order: per data point its slots - subject, relation, object, subject
+// negatives, object negatives
 __global__ void k_kge_keys(int64_t num_entities, int64_t batch, const int32_t *subj, const int32_t *rel, const int32_t *obj,
-                           int32_t ns, const int32_t *neg_subj, int32_t no, const int32_t *neg_obj, int64_t *keys, int64_t *upd_keys) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // scored triple
-    const int32_t per = 1 + ns + no;
-    if (t >= batch * per) return;
-    const int64_t b = t / per;
-    const int32_t j = (int32_t)(t - b * per);
-    int64_t s = subj[b], o = obj[b];
-    if (j >= 1 && j <= ns) s = neg_subj[b * ns + (j - 1)];
-    if (j > ns) o = neg_obj[b * no + (j - 1 - ns)];
-    keys[3 * t + 0] = s;
-    keys[3 * t + 1] = num_entities + rel[b];
-    keys[3 * t + 2] = o;
-    if (upd_keys) {
-        int64_t *u = upd_keys + b * (3 + ns + no);
-        if (j == 0) { u[0] = s; u[1] = num_entities + rel[b]; u[2] = o; }
-        else u[2 + j] = j <= ns ? s : o;                               // the entity that replaced subject or object
-    }
+                           int32_t ns, const int32_t *neg_subj, int32_t no, const int32_t *neg_obj, int64_t *keys) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int32_t rows = 3 + ns + no;
+    if (i >= batch * rows) return;
+    const int64_t b = i / rows;
+    const int32_t j = (int32_t)(i - b * rows);
+    int64_t k;
+    if (j == 0) k = subj[b];
+    else if (j == 1) k = num_entities + rel[b];
+    else if (j == 2) k = obj[b];
+    else if (j < 3 + ns) k = neg_subj[b * ns + (j - 3)];
+    else k = neg_obj[b * no + (j - 3 - ns)];
+    keys[i] = k;
 }
 
-// AdaGrad with the occurrence's own gradient g and the accumulator G as pulled:
+// AdaGrad with the gradient g of a key slot and the accumulator G as pulled:
 //   dtheta = -lr g / sqrt(G + g^2 + eps),  dG = g^2
-// (the reciprocal square root is the hardware's, good to one unit in the last place; G + g^2 + eps >= eps > 0)
+// EXACT: root in double and a correctly rounded division, operation by operation what a sequential fp32 program
+// does; otherwise the hardware's reciprocal square root, good to one unit in the last place (G + g^2 + eps >= eps > 0).
 struct Upd { float dt, dg; };
+template <bool EXACT>
 __device__ __forceinline__ Upd adagrad(float g, float G, float lr, float eps) {
-    return {(-lr * g) * __builtin_amdgcn_rsqf(G + g * g + eps), g * g};
+    if constexpr (EXACT) return {-lr * g / (float)sqrt((double)(G + g * g + eps)), g * g};
+    else return {(-lr * g) * __builtin_amdgcn_rsqf(G + g * g + eps), g * g};
 }
 
-// One wavefront per positive triple and its negatives (lane l handles components l, l + 64, ...).
-// The values come from the store as it holds them (the pull).  The positive triple first, then
-// every negative in one go: its row, its score, the derivative of its loss (the same in all
-// lanes), its AdaGrad update.  The occurrences of the subject (in the positive triple and the
-// ones with a replaced object), of the relation (in all of them) and of the object (in the
-// positive triple and the ones with a replaced subject) are added up, in the order of the
-// occurrences, before they are pushed: the data point's push has one row per key slot -
-// subject, relation, object, every negative - instead of one per occurrence.  Score t is also
-// kept in lane t, and the losses of all scored triples are evaluated together at the end.
+// One wavefront per data point - a positive triple and its negatives (Appendix A: the negatives are derived from
+// the data point) -, lane l the components l, l + 64, ...  The values come from the store as it holds them (the
+// pull).  The data point's loss is the sum over its scored triples; the gradient of a key slot - subject,
+// relation, object, each negative - is the sum of the terms of the triples the slot occurs in, added in the order of
+// the triples (positive, subject negatives, object negatives), and every slot takes one AdaGrad step on it: the
+// data point pushes one row per slot.  The positive triple first, then every negative in one go: its row, its
+// score, the derivative of its loss (the same in all lanes), its terms for the two slots it shares with the
+// positive triple, its own AdaGrad step.  Score t is also kept in lane t, and the losses of all scored triples
+// are evaluated together at the end.
 //   loss = log(1 + exp(-label score)),  g = dloss/dscore * dscore/dtheta
-// rows: (3 + ns + no) per positive triple in upd and in upd_keys (NULL: the caller has the keys already).  1 + ns + no <= 64.
-template <int NC>
+// EXACT: every score is summed in index order (the lanes' terms one after the other), for bit-for-bit comparisons
+// with a sequential program; otherwise per lane and then across the lanes.
+// rows: (3 + ns + no) per data point in upd and in upd_keys (NULL: the caller has the keys already).  1 + ns + no <= 64.
+template <int NC, bool EXACT>
 __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_entities, int32_t D, const int32_t *subj, const int32_t *rel,
                                                     const int32_t *obj, int32_t ns, const int32_t *neg_subj, int32_t no,
                                                     const int32_t *neg_obj, float lr, float eps, const float *__restrict__ store,
@@ -77,10 +77,28 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
     const float *vs = store + ks * L, *vr = store + kr * L, *vo = store + ko * L;
     float *u0 = upd + b * rows * L;
     if (lane == 0 && upd_keys) { upd_keys[b * rows + 0] = ks; upd_keys[b * rows + 1] = kr; upd_keys[b * rows + 2] = ko; }
+    // the sum of the lanes' terms: term[c] belongs to component lane + 64 c
+    auto total = [&](const float (&term)[NC]) {
+        if constexpr (EXACT) {
+            float acc = 0.0f;
+            for (int k = 0; k < D; ++k) {
+                float t = 0.0f;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) t = (k >> 6) == c ? rl_f(term[c], k & 63) : t;
+                acc = acc + t;
+            }
+            return acc;
+        } else {
+            float part = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) part += term[c];
+            return wave_sum(part);
+        }
+    };
     float sr[NC], si[NC], rr[NC], ri[NC], orl[NC], oi[NC];
     float score = 0.0f;                                              // lane t: score of scored triple t
     {
-        float part = 0.0f;
+        float term[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const int k = lane + 64 * c;
@@ -89,9 +107,9 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
             rr[c] = in ? vr[k] : 0.0f; ri[c] = in ? vr[D + k] : 0.0f;
             orl[c] = in ? vo[k] : 0.0f; oi[c] = in ? vo[D + k] : 0.0f;
             // Re((sr + i si)(rr + i ri)(or - i oi))
-            part += sr[c] * rr[c] * orl[c] + si[c] * rr[c] * oi[c] + sr[c] * ri[c] * oi[c] - si[c] * ri[c] * orl[c];
+            term[c] = sr[c] * rr[c] * orl[c] + si[c] * rr[c] * oi[c] + sr[c] * ri[c] * oi[c] - si[c] * ri[c] * orl[c];
         }
-        const float sc = wave_sum(part);
+        const float sc = total(term);
         score = lane == 0 ? sc : score;
     }
     // dloss/dscore of one scored triple (the same value in every lane): -label sigmoid(-label score), written so that
@@ -102,74 +120,47 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
         const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
         return -label * sig;
     };
-    // the accumulators of subject, relation and object as pulled: read once, used by every triple they occur in
-    float Gs[NC][2], Gr[NC][2], Go[NC][2];
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-        const int k = lane + 64 * c;
-        const bool in = k < D;
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            Gs[c][p] = in ? vs[2 * D + p * D + k] : 0.0f;
-            Gr[c][p] = in ? vr[2 * D + p * D + k] : 0.0f;
-            Go[c][p] = in ? vo[2 * D + p * D + k] : 0.0f;
-        }
-    }
-    // the running sums of the subject's, the relation's and the object's updates, started by the positive triple
-    float as_t[NC][2], as_g[NC][2], ar_t[NC][2], ar_g[NC][2], ao_t[NC][2], ao_g[NC][2];
+    // the gradients of the subject's, the relation's and the object's slot, started by the positive triple
+    float gs[NC][2], gr[NC][2], go[NC][2];
     {
         const float dl = dloss(1.0f, rl_f(score, 0));
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
-                                   {dl * (sr[c] * orl[c] + si[c] * oi[c]), dl * (sr[c] * oi[c] - si[c] * orl[c])},
-                                   {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const Upd us = adagrad(g[0][p], Gs[c][p], lr, eps);
-                const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
-                const Upd uo = adagrad(g[2][p], Go[c][p], lr, eps);
-                as_t[c][p] = us.dt; as_g[c][p] = us.dg; ar_t[c][p] = ur.dt; ar_g[c][p] = ur.dg; ao_t[c][p] = uo.dt; ao_g[c][p] = uo.dg;
-            }
+            gs[c][0] = 0.0f + dl * (rr[c] * orl[c] + ri[c] * oi[c]); gs[c][1] = 0.0f + dl * (rr[c] * oi[c] - ri[c] * orl[c]);
+            gr[c][0] = 0.0f + dl * (sr[c] * orl[c] + si[c] * oi[c]); gr[c][1] = 0.0f + dl * (sr[c] * oi[c] - si[c] * orl[c]);
+            go[c][0] = 0.0f + dl * (sr[c] * rr[c] - si[c] * ri[c]);  go[c][1] = 0.0f + dl * (si[c] * rr[c] + sr[c] * ri[c]);
         }
     }
     // The negatives, each in one go - its row (values and accumulators) is asked for at once, then its score, the
-    // derivative of its loss, its own update row and its terms for the two keys it shares with the positive triple.
+    // derivative of its loss, its terms for the two slots it shares with the positive triple, and its own step.
     // subject replaced by n: the triple (n, r, o), label -1
     for (int j = 0; j < ns; ++j) {
         const int64_t kn = neg_subj[b * ns + j];
         const float *vn = store + kn * L;
         float *un = u0 + (int64_t)(3 + j) * L;
         if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + j] = kn;
-        float nr[NC], ni[NC], Gn[NC][2];
-        float pn = 0.0f;
+        float nr[NC], ni[NC], Gn[NC][2], term[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const int k = lane + 64 * c;
             const bool in = k < D;
             nr[c] = in ? vn[k] : 0.0f; ni[c] = in ? vn[D + k] : 0.0f;
             Gn[c][0] = in ? vn[2 * D + k] : 0.0f; Gn[c][1] = in ? vn[3 * D + k] : 0.0f;
-            pn += nr[c] * rr[c] * orl[c] + ni[c] * rr[c] * oi[c] + nr[c] * ri[c] * oi[c] - ni[c] * ri[c] * orl[c];
+            term[c] = nr[c] * rr[c] * orl[c] + ni[c] * rr[c] * oi[c] + nr[c] * ri[c] * oi[c] - ni[c] * ri[c] * orl[c];
         }
-        const float sc = wave_sum(pn);
+        const float sc = total(term);
         score = lane == 1 + j ? sc : score;
         const float dl = dloss(-1.0f, sc);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const int k = lane + 64 * c;
             if (k >= D) continue;
-            const float g[3][2] = {{dl * (rr[c] * orl[c] + ri[c] * oi[c]), dl * (rr[c] * oi[c] - ri[c] * orl[c])},
-                                   {dl * (nr[c] * orl[c] + ni[c] * oi[c]), dl * (nr[c] * oi[c] - ni[c] * orl[c])},
-                                   {dl * (nr[c] * rr[c] - ni[c] * ri[c]), dl * (ni[c] * rr[c] + nr[c] * ri[c])}};
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const Upd un_ = adagrad(g[0][p], Gn[c][p], lr, eps);
-                un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
-                const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
-                ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
-                const Upd uo = adagrad(g[2][p], Go[c][p], lr, eps);
-                ao_t[c][p] = ao_t[c][p] + uo.dt; ao_g[c][p] = ao_g[c][p] + uo.dg;
-            }
+            const float g0 = 0.0f + dl * (rr[c] * orl[c] + ri[c] * oi[c]), g1 = 0.0f + dl * (rr[c] * oi[c] - ri[c] * orl[c]);   // its own slot
+            gr[c][0] = gr[c][0] + dl * (nr[c] * orl[c] + ni[c] * oi[c]); gr[c][1] = gr[c][1] + dl * (nr[c] * oi[c] - ni[c] * orl[c]);
+            go[c][0] = go[c][0] + dl * (nr[c] * rr[c] - ni[c] * ri[c]);  go[c][1] = go[c][1] + dl * (ni[c] * rr[c] + nr[c] * ri[c]);
+            const Upd u_0 = adagrad<EXACT>(g0, Gn[c][0], lr, eps), u_1 = adagrad<EXACT>(g1, Gn[c][1], lr, eps);
+            un[k] = u_0.dt; un[2 * D + k] = u_0.dg;
+            un[D + k] = u_1.dt; un[3 * D + k] = u_1.dg;
         }
     }
     // object replaced by n: the triple (s, r, n), label -1
@@ -178,35 +169,28 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
         const float *vn = store + kn * L;
         float *un = u0 + (int64_t)(3 + ns + j) * L;
         if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + ns + j] = kn;
-        float nr[NC], ni[NC], Gn[NC][2];
-        float pn = 0.0f;
+        float nr[NC], ni[NC], Gn[NC][2], term[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const int k = lane + 64 * c;
             const bool in = k < D;
             nr[c] = in ? vn[k] : 0.0f; ni[c] = in ? vn[D + k] : 0.0f;
             Gn[c][0] = in ? vn[2 * D + k] : 0.0f; Gn[c][1] = in ? vn[3 * D + k] : 0.0f;
-            pn += sr[c] * rr[c] * nr[c] + si[c] * rr[c] * ni[c] + sr[c] * ri[c] * ni[c] - si[c] * ri[c] * nr[c];
+            term[c] = sr[c] * rr[c] * nr[c] + si[c] * rr[c] * ni[c] + sr[c] * ri[c] * ni[c] - si[c] * ri[c] * nr[c];
         }
-        const float sc = wave_sum(pn);
+        const float sc = total(term);
         score = lane == 1 + ns + j ? sc : score;
         const float dl = dloss(-1.0f, sc);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const int k = lane + 64 * c;
             if (k >= D) continue;
-            const float g[3][2] = {{dl * (rr[c] * nr[c] + ri[c] * ni[c]), dl * (rr[c] * ni[c] - ri[c] * nr[c])},
-                                   {dl * (sr[c] * nr[c] + si[c] * ni[c]), dl * (sr[c] * ni[c] - si[c] * nr[c])},
-                                   {dl * (sr[c] * rr[c] - si[c] * ri[c]), dl * (si[c] * rr[c] + sr[c] * ri[c])}};
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const Upd us = adagrad(g[0][p], Gs[c][p], lr, eps);
-                as_t[c][p] = as_t[c][p] + us.dt; as_g[c][p] = as_g[c][p] + us.dg;
-                const Upd ur = adagrad(g[1][p], Gr[c][p], lr, eps);
-                ar_t[c][p] = ar_t[c][p] + ur.dt; ar_g[c][p] = ar_g[c][p] + ur.dg;
-                const Upd un_ = adagrad(g[2][p], Gn[c][p], lr, eps);
-                un[p * D + k] = un_.dt; un[2 * D + p * D + k] = un_.dg;
-            }
+            gs[c][0] = gs[c][0] + dl * (rr[c] * nr[c] + ri[c] * ni[c]); gs[c][1] = gs[c][1] + dl * (rr[c] * ni[c] - ri[c] * nr[c]);
+            gr[c][0] = gr[c][0] + dl * (sr[c] * nr[c] + si[c] * ni[c]); gr[c][1] = gr[c][1] + dl * (sr[c] * ni[c] - si[c] * nr[c]);
+            const float g0 = 0.0f + dl * (sr[c] * rr[c] - si[c] * ri[c]), g1 = 0.0f + dl * (si[c] * rr[c] + sr[c] * ri[c]);     // its own slot
+            const Upd u_0 = adagrad<EXACT>(g0, Gn[c][0], lr, eps), u_1 = adagrad<EXACT>(g1, Gn[c][1], lr, eps);
+            un[k] = u_0.dt; un[2 * D + k] = u_0.dg;
+            un[D + k] = u_1.dt; un[3 * D + k] = u_1.dg;
         }
     }
     // the losses of all scored triples at once (lane t: triple t; the positive one is triple 0)
@@ -224,15 +208,19 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
         }
         if (lane == 0) loss[b] = loss_sum;
     }
+    // subject, relation, object: one AdaGrad step each on the summed gradient, with the accumulators as pulled
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int k = lane + 64 * c;
         if (k >= D) continue;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            u0[p * D + k] = as_t[c][p]; u0[2 * D + p * D + k] = as_g[c][p];
-            u0[L + p * D + k] = ar_t[c][p]; u0[L + 2 * D + p * D + k] = ar_g[c][p];
-            u0[2 * L + p * D + k] = ao_t[c][p]; u0[2 * L + 2 * D + p * D + k] = ao_g[c][p];
+            const Upd us = adagrad<EXACT>(gs[c][p], vs[2 * D + p * D + k], lr, eps);
+            const Upd ur = adagrad<EXACT>(gr[c][p], vr[2 * D + p * D + k], lr, eps);
+            const Upd uo = adagrad<EXACT>(go[c][p], vo[2 * D + p * D + k], lr, eps);
+            u0[p * D + k] = us.dt; u0[2 * D + p * D + k] = us.dg;
+            u0[L + p * D + k] = ur.dt; u0[L + 2 * D + p * D + k] = ur.dg;
+            u0[2 * L + p * D + k] = uo.dt; u0[2 * L + 2 * D + p * D + k] = uo.dg;
         }
     }
 }
@@ -260,15 +248,11 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     if (batch > 0 && (!subj || !rel || !obj || (n_neg_subj > 0 && !neg_subj) || (n_neg_obj > 0 && !neg_obj))) return PS_EINVAL;
     if (loss_host_out) *loss_host_out = 0.0;
     if (batch == 0) return PS_OK;
-    const int32_t per = 1 + n_neg_subj + n_neg_obj;
-    const int64_t ntr = batch * per, nocc = 3 * ntr;
-    if (nocc >= ((int64_t)1 << 31)) return PS_ELIMIT;
+    const int64_t rows = batch * (3 + n_neg_subj + n_neg_obj);        // keys pulled and pushed: the slots of the data points
+    if (rows >= ((int64_t)1 << 31)) return PS_ELIMIT;
     hipStream_t st = (hipStream_t)stream;
-    // scratch of the step: the keys of all occurrences (for the statistics of the pull and the push), the
-    // update rows and their keys (3 + negatives per positive triple), the losses
-    const int64_t rows = batch * (3 + n_neg_subj + n_neg_obj);
-    const size_t off_ukeys = (size_t)((nocc * 8 + 255) / 256 * 256);
-    const size_t off_upd = off_ukeys + (size_t)((rows * 8 + 255) / 256 * 256);
+    // scratch of the step: the keys of all slots, the update rows (one per slot), the losses
+    const size_t off_upd = (size_t)((rows * 8 + 255) / 256 * 256);
     const size_t off_loss = off_upd + (size_t)((rows * ps->L * 4 + 255) / 256 * 256);
     const size_t bytes = off_loss + (size_t)(batch + 1) * 8;
     if (bytes > ps->kge_ws_bytes) {
@@ -279,17 +263,16 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
         if (e != hipSuccess) { (void)hipGetLastError(); ps->last_error = "out of device memory for the step's scratch"; return PS_ENOMEM; }
         ps->kge_ws_bytes = bytes;
     }
-    int64_t *keys = (int64_t *)ps->kge_ws;
-    int64_t *ukeys = (int64_t *)((char *)ps->kge_ws + off_ukeys);
+    int64_t *ukeys = (int64_t *)ps->kge_ws;
     float *upd = (float *)((char *)ps->kge_ws + off_upd);
     double *loss = (double *)((char *)ps->kge_ws + off_loss);
-    k_kge_keys<<<grid_for(ntr, 256), 256, 0, st>>>(num_entities, batch, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, keys, ukeys);
+    k_kge_keys<<<grid_for(rows, 256), 256, 0, st>>>(num_entities, batch, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, ukeys);
     PS_HIP(ps, hipGetLastError());
-    int rc = dpaps_check_keys(ps, keys, nocc, st);                      // before anything indexes the store with them
+    int rc = dpaps_check_keys(ps, ukeys, rows, st);                     // before anything indexes the store with them
     if (rc) return rc;
-    // What needs the keys only - the sort of the push, and the statistics of the pull and of the push (every
-    // occurrence is pulled, and pushed below) - runs on the library's second stream beside the kernel that computes
-    // the update rows; the sums wait for the sort, the end of the step for the statistics.
+    // What needs the keys only - the sort of the push, and the statistics of the pull and of the push (every slot
+    // is pulled, and pushed below) - runs on the library's second stream beside the kernel that computes the
+    // update rows; the sums wait for the sort, the end of the step for the statistics.
     rc = dpaps_side_stream(ps);
     if (rc) return rc;
     hipStream_t bs = ps->side_stream;
@@ -298,12 +281,17 @@ extern "C" int kge_sgd_step(ps_handle ps, int32_t worker, int64_t num_entities, 
     rc = dpaps_push_sort(ps, ukeys, rows, bs);
     if (rc) return rc;
     PS_HIP(ps, hipEventRecord(ps->ev_sorted, bs));
-    rc = dpaps_route_pull_push(ps, worker, keys, nocc, bs);
+    rc = dpaps_route_pull_push(ps, worker, ukeys, rows, bs);
     if (rc) return rc;
     PS_HIP(ps, hipEventRecord(ps->ev_join, bs));
     const unsigned blocks = grid_for(batch * 64, 256);
-#define KGE_GROUP(NC) k_kge_group<NC><<<blocks, 256, 0, st>>>(batch, num_entities, dim, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj, \
-                                                              lr, eps, ps->val, upd, nullptr, loss, ps->err)
+#define KGE_GROUP(NC)                                                                                                                          \
+    do {                                                                                                                                       \
+        if (ps->opt_kge_exact) k_kge_group<NC, true><<<blocks, 256, 0, st>>>(batch, num_entities, dim, subj, rel, obj, n_neg_subj, neg_subj,     \
+                                                                             n_neg_obj, neg_obj, lr, eps, ps->val, upd, nullptr, loss, ps->err); \
+        else k_kge_group<NC, false><<<blocks, 256, 0, st>>>(batch, num_entities, dim, subj, rel, obj, n_neg_subj, neg_subj, n_neg_obj, neg_obj,  \
+                                                            lr, eps, ps->val, upd, nullptr, loss, ps->err);                                      \
+    } while (0)
     switch ((dim + 63) / 64) {
     case 1: KGE_GROUP(1); break;
     case 2: KGE_GROUP(2); break;
@@ -355,6 +343,8 @@ __global__ void k_kge_relation_keys(int64_t num_entities, int64_t t0, int64_t t1
     if (t < t1) keys[t - t0] = num_entities + rel[t];
 }
 
+__global__ void k_kge_zero(double *x) { *x = 0.0; }
+
 // *acc += the sum of loss[0 .. n)
 __global__ __launch_bounds__(256) void k_kge_loss_add(const double *loss, int64_t n, double *acc) {
     __shared__ double s[256];
@@ -388,17 +378,17 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
     if (num_triples == 0) return PS_OK;
     const int32_t ns = n_neg_subj, no = n_neg_obj, per = 1 + ns + no, ent = 2 + ns + no;
     const int64_t bmax = std::min(batch, longest);
-    if (3 * bmax * per >= ((int64_t)1 << 31) || longest * ent >= ((int64_t)1 << 31)) return PS_ELIMIT;
+    if (bmax * (per + 2) >= ((int64_t)1 << 31) || longest * ent >= ((int64_t)1 << 31)) return PS_ELIMIT;
     hipStream_t vs = (hipStream_t)stream;                  // the work on the values
     {
         const int rc = dpaps_side_stream(ps);
         if (rc) return rc;
     }
     hipStream_t bs = ps->side_stream;                      // localize calls and statistics: owner map and counters only
-    // scratch: occurrence keys and localize keys (second stream), update rows, their keys and the losses (first)
+    // scratch: localize keys (second stream), the slots' keys, update rows and the losses (first)
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     const int64_t rows_max = bmax * (3 + ns + no);
-    const size_t off_loc = up((size_t)3 * bmax * per * 8);
+    const size_t off_loc = 0;
     const size_t off_ukeys = off_loc + up((size_t)std::max(longest, bmax * ent) * 8);
     const size_t off_upd = off_ukeys + up((size_t)rows_max * 8);
     const size_t off_loss = off_upd + up((size_t)rows_max * ps->L * 4);
@@ -411,7 +401,6 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
         if (e != hipSuccess) { (void)hipGetLastError(); ps->last_error = "out of device memory for the epoch's scratch"; return PS_ENOMEM; }
         ps->kge_ws_bytes = bytes;
     }
-    int64_t *okeys = (int64_t *)ps->kge_ws;
     int64_t *lkeys = (int64_t *)((char *)ps->kge_ws + off_loc);
     int64_t *ukeys = (int64_t *)((char *)ps->kge_ws + off_ukeys);
     float *upd = (float *)((char *)ps->kge_ws + off_upd);
@@ -422,7 +411,8 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
     k_kge_validate<<<grid_for(num_triples, 256), 256, 0, vs>>>(num_entities, ps->K - num_entities, num_triples, subj, rel, obj, ns, neg_subj,
                                                              no, neg_obj, ps->err);
     PS_HIP(ps, hipGetLastError());
-    PS_HIP(ps, hipMemsetAsync(loss_acc, 0, sizeof(double), vs));
+    k_kge_zero<<<1, 1, 0, vs>>>(loss_acc);
+    PS_HIP(ps, hipGetLastError());
     PS_HIP(ps, hipEventRecord(ps->ev_fork, vs));
     PS_HIP(ps, hipStreamWaitEvent(bs, ps->ev_fork, 0));
     int rc = PS_OK;
@@ -452,10 +442,10 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
             // second stream: the next batch's entities come to this worker, then this batch's accesses are counted
             if (lookahead && t1 < end) rc = localize_entities(t1, std::min(t1 + batch, end), w);
             if (rc) break;
-            k_kge_keys<<<grid_for(nb * per, 256), 256, 0, bs>>>(num_entities, nb, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no,
-                                                                neg_obj + t0 * no, okeys, ukeys);
+            k_kge_keys<<<grid_for(nb * (3 + ns + no), 256), 256, 0, bs>>>(num_entities, nb, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns,
+                                                                          no, neg_obj + t0 * no, ukeys);
             PS_HIP(ps, hipGetLastError());
-            rc = dpaps_route_pull_push(ps, w, okeys, 3 * nb * per, bs);
+            rc = dpaps_route_pull_push(ps, w, ukeys, nb * (3 + ns + no), bs);
             if (rc) break;
             // ... and the push's sort, which needs the keys only, once the previous step's sums have read theirs
             if (steps_done > 0) PS_HIP(ps, hipStreamWaitEvent(bs, ps->ev_added, 0));
@@ -464,8 +454,14 @@ extern "C" int kge_sgd_epoch(ps_handle ps, int64_t num_entities, int32_t dim, in
             PS_HIP(ps, hipEventRecord(ps->ev_sorted, bs));
             // first stream: the values
             const unsigned blocks = grid_for(nb * 64, 256);
-#define KGE_GROUP(NC) k_kge_group<NC><<<blocks, 256, 0, vs>>>(nb, num_entities, dim, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no, \
-                                                              neg_obj + t0 * no, lr, eps, ps->val, upd, nullptr, loss, ps->err)
+#define KGE_GROUP(NC)                                                                                                                              \
+    do {                                                                                                                                           \
+        if (ps->opt_kge_exact) k_kge_group<NC, true><<<blocks, 256, 0, vs>>>(nb, num_entities, dim, subj + t0, rel + t0, obj + t0, ns,               \
+                                                                             neg_subj + t0 * ns, no, neg_obj + t0 * no, lr, eps, ps->val, upd, nullptr, \
+                                                                             loss, ps->err);                                                        \
+        else k_kge_group<NC, false><<<blocks, 256, 0, vs>>>(nb, num_entities, dim, subj + t0, rel + t0, obj + t0, ns, neg_subj + t0 * ns, no,         \
+                                                            neg_obj + t0 * no, lr, eps, ps->val, upd, nullptr, loss, ps->err);                      \
+    } while (0)
             switch ((dim + 63) / 64) {
             case 1: KGE_GROUP(1); break;
             case 2: KGE_GROUP(2); break;

@@ -806,6 +806,7 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
         }
         return PS_OK;
     }
+    case PS_OPT_KGE_EXACT: ps->opt_kge_exact = value != 0; return PS_OK;
     case PS_OPT_MF_TEAM_MAX: if (value < 1 || value > 14) return PS_EINVAL; ps->opt_team_max = (int)value; return PS_OK;
     case PS_OPT_MF_HEAVY_LEN:
         if (value < 1 || value > (1 << 30)) return PS_EINVAL;

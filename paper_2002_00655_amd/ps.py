@@ -21,7 +21,7 @@ PS_OK, PS_EINVAL, PS_EKEY, PS_EWORKER, PS_ECONFLICT, PS_ENOMEM, PS_EHIP, PS_EREM
 STAT_NAMES = ["pull_local", "pull_remote", "push_local", "push_remote", "relocated", "localize_keys",
               "msg_acc_req", "msg_acc_fwd", "msg_acc_reply", "msg_loc_req", "msg_loc_instruct", "msg_loc_transfer",
               "cache_hit", "cache_stale"]
-OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES, OPT_MF_PROFILE, OPT_MF_GROUPED, OPT_MF_HEAVY_LEN, OPT_PUSH_SEQUENTIAL, OPT_MF_TEAM_MAX, OPT_MF_CLASSIC, OPT_LOCATION_CACHES = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
+OPT_MF_EXACT, OPT_MF_CACHE_ROWS, OPT_MF_WAVES, OPT_MF_PROFILE, OPT_MF_GROUPED, OPT_MF_HEAVY_LEN, OPT_PUSH_SEQUENTIAL, OPT_MF_TEAM_MAX, OPT_MF_CLASSIC, OPT_LOCATION_CACHES, OPT_KGE_EXACT = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11
 
 EXPORTS = ["ps_create", "ps_destroy", "ps_pull", "ps_push", "ps_push_noalloc", "ps_localize", "ps_owner", "ps_stats", "ps_status",
            "ps_set_option", "ps_last_error", "mf_block_ratings", "mf_load_ratings", "mf_sgd_epoch", "mf_sgd_epoch_handoff", "mf_train_sse",

@@ -94,7 +94,7 @@ def test_knowledge_graph_epoch_with_location_caches(parts, batch, lookahead):
     from test_gpu_kge import _pair, LR, EPS
     w = wl.make_kge(num_entities=400, num_relations=9, triples=150, dim=8, n_neg_s=2, n_neg_o=3, seed=parts)
     wp, part_ptr = wl.partition_by_relation(w, parts)
-    orc, o64, srv = _pair(wp, num_workers=4)
+    orc, srv = _pair(wp, num_workers=4)
     orc.location_caches(True)
     srv.set_option(P.OPT_LOCATION_CACHES, 1)
     dev = torch.device("cuda")

@@ -74,10 +74,14 @@ def test_one_triple_step_is_adagrad_on_the_gradient_of_the_logistic_loss(G0):
     assert np.array_equal(after[untouched], before[untouched])
 
 
-def test_negatives_have_label_minus_one_and_every_occurrence_is_its_own_adagrad_term():
+def test_negatives_have_label_minus_one_and_a_slot_takes_one_adagrad_step_on_its_summed_gradient():
+    """Appendix A: SGD with AdaGrad per data point, the negatives derived from the data point.  The data point's
+    loss is the sum over its scored triples; a key slot (subject, relation, object, each negative) gets the gradient
+    of that loss - the sum of the terms of the triples it occurs in - and one AdaGrad step on it."""
     rng = np.random.default_rng(3)
     ne, nr, lr, eps = 8, 1, 0.1, 1e-10
-    o = _server("f64", ne, nr, rng)
+    G0 = 0.2
+    o = _server("f64", ne, nr, rng, G0)
     before = o.pull(np.arange(ne + nr))
     theta = before[:, :2 * D]
     s, r, ob, s_neg, o_neg = 0, 0, 1, 5, 6
@@ -86,21 +90,60 @@ def test_negatives_have_label_minus_one_and_every_occurrence_is_its_own_adagrad_
     scored = [(s, ne + r, ob, +1.0), (s_neg, ne + r, ob, -1.0), (s, ne + r, o_neg, -1.0)]
     h = 1e-6
 
-    def grad(trip, key, c):
+    def grad(key, c):                                                  # of the data point's whole loss
+        tp, tm = theta.copy(), theta.copy()
+        tp[key, c] += h
+        tm[key, c] -= h
+        return (_loss(tp, scored) - _loss(tm, scored)) / (2 * h)
+
+    def grad_one(trip, key, c):
         tp, tm = theta.copy(), theta.copy()
         tp[key, c] += h
         tm[key, c] -= h
         return (_loss(tp, [trip]) - _loss(tm, [trip])) / (2 * h)
     for c in range(2 * D):
-        # the perturbed subject occurs once, with the negative label
-        g = grad(scored[1], s_neg, c)
-        assert abs(after[s_neg, 2 * D + c] - g * g) < 1e-8
-        assert abs((after[s_neg, c] - before[s_neg, c]) + lr * g / np.sqrt(g * g + eps)) < 1e-7
-        # the relation occurs in all three scored triples: three separate terms, all from the pulled accumulator (0)
-        gs = [grad(t, ne + r, c) for t in scored]
-        assert abs(after[ne + r, 2 * D + c] - sum(x * x for x in gs)) < 1e-8
-        want = sum(-lr * x / np.sqrt(x * x + eps) for x in gs)
-        assert abs((after[ne + r, c] - before[ne + r, c]) - want) < 1e-7
+        # every key of the data point: one AdaGrad step on the gradient of the data point's loss
+        for key in (s, ne + r, ob, s_neg, o_neg):
+            g = grad(key, c)
+            assert abs((after[key, 2 * D + c] - before[key, 2 * D + c]) - g * g) < 1e-8
+            assert abs((after[key, c] - before[key, c]) + lr * g / np.sqrt(G0 + g * g + eps)) < 1e-7
+        # the perturbed subject occurs once, with the negative label; the relation in all three scored triples,
+        # the subject in the positive triple and the one with the replaced object
+        assert abs(grad(s_neg, c) - grad_one(scored[1], s_neg, c)) < 1e-8
+        assert abs(grad(ne + r, c) - sum(grad_one(t, ne + r, c) for t in scored)) < 1e-8
+        assert abs(grad(s, c) - grad_one(scored[0], s, c) - grad_one(scored[2], s, c)) < 1e-8
+    # not one step per occurrence: three steps of the relation from the same accumulator would have moved it further
+    c = 0
+    gs = [grad_one(t, ne + r, c) for t in scored]
+    per_occurrence = sum(-lr * x / np.sqrt(G0 + x * x + eps) for x in gs)
+    assert abs((after[ne + r, c] - before[ne + r, c]) - per_occurrence) > 1e-4
+
+
+def test_a_key_in_two_slots_gets_one_term_per_slot_from_the_pulled_accumulator():
+    """A negative that happens to be the positive triple's own subject fills a slot of its own: two terms for that key,
+    both normalised with the accumulator as pulled, added by the cumulative push."""
+    rng = np.random.default_rng(11)
+    ne, nr, lr, eps = 6, 1, 0.1, 1e-10
+    G0 = 0.05
+    o = _server("f64", ne, nr, rng, G0)
+    before = o.pull(np.arange(ne + nr))
+    theta = before[:, :2 * D]
+    s, r, ob = 2, 0, 4
+    o.kge_step(ne, D, [s], [r], [ob], [[s]], np.zeros((1, 0)), lr, eps)     # the subject "replaced" by itself
+    after = o.pull(np.arange(ne + nr))
+    h = 1e-6
+    pos, neg = (s, ne + r, ob, +1.0), (s, ne + r, ob, -1.0)
+
+    def grad_one(trip, key, c):
+        tp, tm = theta.copy(), theta.copy()
+        tp[key, c] += h
+        tm[key, c] -= h
+        return (_loss(tp, [trip]) - _loss(tm, [trip])) / (2 * h)
+    for c in range(2 * D):
+        g1, g2 = grad_one(pos, s, c), grad_one(neg, s, c)              # subject slot, negative's slot
+        want = -lr * g1 / np.sqrt(G0 + g1 * g1 + eps) - lr * g2 / np.sqrt(G0 + g2 * g2 + eps)
+        assert abs((after[s, c] - before[s, c]) - want) < 1e-7
+        assert abs((after[s, 2 * D + c] - before[s, 2 * D + c]) - (g1 * g1 + g2 * g2)) < 1e-8
 
 
 def test_a_batch_is_the_sum_of_its_triples_steps_from_the_same_state():
@@ -122,7 +165,7 @@ def test_a_batch_is_the_sum_of_its_triples_steps_from_the_same_state():
     assert np.allclose(total, acc, rtol=0, atol=1e-12)
 
 
-def test_large_scores_do_not_overflow_and_counters_see_every_occurrence():
+def test_large_scores_do_not_overflow_and_counters_see_every_slot():
     ne, nr = 4, 1
     for prec in ("f32", "f64"):
         o = Oracle(prec, ne + nr, 4 * D, 2)
@@ -134,8 +177,8 @@ def test_large_scores_do_not_overflow_and_counters_see_every_occurrence():
         assert np.isfinite(loss) and loss > 1e5                         # two confidently wrong negatives
         assert np.isfinite(o.pull(np.arange(ne + nr))).all()
         st = o.stats()
-        assert st["pull_local"] + st["pull_remote"] - st0["pull_local"] - st0["pull_remote"] == 9
-        assert st["push_local"] + st["push_remote"] - st0["push_local"] - st0["push_remote"] == 9
+        assert st["pull_local"] + st["pull_remote"] - st0["pull_local"] - st0["pull_remote"] == 5      # s, r, o, two negatives
+        assert st["push_local"] + st["push_remote"] - st0["push_local"] - st0["push_remote"] == 5
 
 
 def test_training_on_a_small_planted_graph_lowers_the_loss_and_ranks_true_triples_first():
@@ -243,19 +286,16 @@ def test_relations_are_always_local_and_entities_remote_only_after_a_conflict():
             t1 = min(t0 + B, end)
             for k in ents(t1, min(t1 + B, end)):
                 owner[k] = p
-            for t in range(t0, t1):
-                s_list = [wp.subj[t]] + list(wp.neg_subj[t]) + [wp.subj[t]] * wp.neg_obj.shape[1]
-                o_list = [wp.obj[t]] * (1 + wp.neg_subj.shape[1]) + list(wp.neg_obj[t])
-                for s_, o_ in zip(s_list, o_list):
-                    for k in (s_, ne + wp.rel[t], o_):
-                        if owner[k] == p:
-                            local += 1
-                        else:
-                            remote += 1
+            for t in range(t0, t1):                             # the slots of the data point
+                for k in [wp.subj[t], ne + wp.rel[t], wp.obj[t], *wp.neg_subj[t], *wp.neg_obj[t]]:
+                    if owner[k] == p:
+                        local += 1
+                    else:
+                        remote += 1
         r += 1
     st = o.stats()
     assert st["pull_local"] == st["push_local"] == local and st["pull_remote"] == st["push_remote"] == remote
-    assert local + remote == 3 * per * wp.subj.size
+    assert local + remote == (2 + per) * wp.subj.size
     assert 0 < remote < local / 2                                       # conflicts exist (popular entities) but are the exception
     # one worker: never a conflict
     wp1, pp1, init1 = _epoch_setup(1, seed=9)
