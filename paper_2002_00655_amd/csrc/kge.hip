@@ -17,6 +17,7 @@
 #include "mf_device.h"
 
 #include <algorithm>
+#include <type_traits>
 
 static inline unsigned grid_for(int64_t n, int block) { return (unsigned)((n + block - 1) / block); }
 
@@ -70,9 +71,12 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
                                                     int64_t *upd_keys, double *loss, const int32_t *err) {
     if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     const int lane = threadIdx.x & 63;
-    const int64_t b = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    // the data point is the same for all lanes of a wavefront: said so, its keys and row addresses stay in scalar registers
+    const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (b >= batch) return;
+    constexpr int CH = NC <= 2 ? 5 : 1;                              // negatives whose rows are in flight together
     const int L = 4 * D, rows = 3 + ns + no;
+    const uint32_t Du = (uint32_t)D;                                 // row addresses and field offsets are scalars, k the only lane offset
     const int64_t ks = subj[b], kr = num_entities + rel[b], ko = obj[b];
     const float *vs = store + ks * L, *vr = store + kr * L, *vo = store + ko * L;
     float *u0 = upd + b * rows * L;
@@ -101,11 +105,11 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
         float term[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            const int k = lane + 64 * c;
-            const bool in = k < D;
-            sr[c] = in ? vs[k] : 0.0f; si[c] = in ? vs[D + k] : 0.0f;
-            rr[c] = in ? vr[k] : 0.0f; ri[c] = in ? vr[D + k] : 0.0f;
-            orl[c] = in ? vo[k] : 0.0f; oi[c] = in ? vo[D + k] : 0.0f;
+            const uint32_t k = (uint32_t)lane + 64u * c;
+            const bool in = k < Du;
+            sr[c] = in ? vs[k] : 0.0f; si[c] = in ? (vs + Du)[k] : 0.0f;
+            rr[c] = in ? vr[k] : 0.0f; ri[c] = in ? (vr + Du)[k] : 0.0f;
+            orl[c] = in ? vo[k] : 0.0f; oi[c] = in ? (vo + Du)[k] : 0.0f;
             // Re((sr + i si)(rr + i ri)(or - i oi))
             term[c] = sr[c] * rr[c] * orl[c] + si[c] * rr[c] * oi[c] + sr[c] * ri[c] * oi[c] - si[c] * ri[c] * orl[c];
         }
@@ -113,10 +117,13 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
         score = lane == 0 ? sc : score;
     }
     // dloss/dscore of one scored triple (the same value in every lane): -label sigmoid(-label score), written so that
-    // nothing overflows, the exponential in double as in the oracle
+    // nothing overflows; EXACT: the exponential in double and rounded to float, as a sequential fp32 program has it
     auto dloss = [](float label, float sc) {
         const float z = -label * sc;
-        const float ex = (float)exp((double)(z >= 0.0f ? -z : z));
+        const float na = z >= 0.0f ? -z : z;                         // -|z|
+        float ex;
+        if constexpr (EXACT) ex = (float)exp((double)na);
+        else ex = __builtin_amdgcn_exp2f(na * 1.44269504088896340736f);   // the hardware's 2^x, good to one unit in the last place
         const float sig = z >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
         return -label * sig;
     };
@@ -131,68 +138,66 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
             go[c][0] = 0.0f + dl * (sr[c] * rr[c] - si[c] * ri[c]);  go[c][1] = 0.0f + dl * (si[c] * rr[c] + sr[c] * ri[c]);
         }
     }
-    // The negatives, each in one go - its row (values and accumulators) is asked for at once, then its score, the
-    // derivative of its loss, its terms for the two slots it shares with the positive triple, and its own step.
-    // subject replaced by n: the triple (n, r, o), label -1
-    for (int j = 0; j < ns; ++j) {
-        const int64_t kn = neg_subj[b * ns + j];
-        const float *vn = store + kn * L;
-        float *un = u0 + (int64_t)(3 + j) * L;
-        if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + j] = kn;
-        float nr[NC], ni[NC], Gn[NC][2], term[NC];
+    // The negatives, CH at a time: their rows (values and accumulators) are asked for together, so that a wavefront
+    // waits for memory once per CH negatives, then per negative in order its score, the derivative of its loss,
+    // its terms for the two slots it shares with the positive triple, and its own step.
+    // OBJ false: subject replaced by n, the triple (n, r, o); true: object replaced by n, the triple (s, r, n); label -1
+    auto negatives = [&](auto obj_tag, const int32_t *list, int n_list, int slot0) {
+        constexpr bool OBJ = decltype(obj_tag)::value;
+        for (int j0 = 0; j0 < n_list; j0 += CH) {
+            float nr[CH][NC], ni[CH][NC], Gn[CH][NC][2], sc[CH];
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int k = lane + 64 * c;
-            const bool in = k < D;
-            nr[c] = in ? vn[k] : 0.0f; ni[c] = in ? vn[D + k] : 0.0f;
-            Gn[c][0] = in ? vn[2 * D + k] : 0.0f; Gn[c][1] = in ? vn[3 * D + k] : 0.0f;
-            term[c] = nr[c] * rr[c] * orl[c] + ni[c] * rr[c] * oi[c] + nr[c] * ri[c] * oi[c] - ni[c] * ri[c] * orl[c];
-        }
-        const float sc = total(term);
-        score = lane == 1 + j ? sc : score;
-        const float dl = dloss(-1.0f, sc);
+            for (int q = 0; q < CH; ++q) {
+                const bool valid = j0 + q < n_list;
+                const int64_t kn = valid ? (int64_t)list[b * n_list + j0 + q] : ks;
+                const float *vn = store + kn * L;
+                if (lane == 0 && upd_keys && valid) upd_keys[b * rows + slot0 + j0 + q] = kn;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int k = lane + 64 * c;
-            if (k >= D) continue;
-            const float g0 = 0.0f + dl * (rr[c] * orl[c] + ri[c] * oi[c]), g1 = 0.0f + dl * (rr[c] * oi[c] - ri[c] * orl[c]);   // its own slot
-            gr[c][0] = gr[c][0] + dl * (nr[c] * orl[c] + ni[c] * oi[c]); gr[c][1] = gr[c][1] + dl * (nr[c] * oi[c] - ni[c] * orl[c]);
-            go[c][0] = go[c][0] + dl * (nr[c] * rr[c] - ni[c] * ri[c]);  go[c][1] = go[c][1] + dl * (ni[c] * rr[c] + nr[c] * ri[c]);
-            const Upd u_0 = adagrad<EXACT>(g0, Gn[c][0], lr, eps), u_1 = adagrad<EXACT>(g1, Gn[c][1], lr, eps);
-            un[k] = u_0.dt; un[2 * D + k] = u_0.dg;
-            un[D + k] = u_1.dt; un[3 * D + k] = u_1.dg;
-        }
-    }
-    // object replaced by n: the triple (s, r, n), label -1
-    for (int j = 0; j < no; ++j) {
-        const int64_t kn = neg_obj[b * no + j];
-        const float *vn = store + kn * L;
-        float *un = u0 + (int64_t)(3 + ns + j) * L;
-        if (lane == 0 && upd_keys) upd_keys[b * rows + 3 + ns + j] = kn;
-        float nr[NC], ni[NC], Gn[NC][2], term[NC];
+                for (int c = 0; c < NC; ++c) {
+                    const uint32_t k = (uint32_t)lane + 64u * c;
+                    const bool in = valid && k < Du;
+                    nr[q][c] = in ? vn[k] : 0.0f; ni[q][c] = in ? (vn + Du)[k] : 0.0f;
+                    Gn[q][c][0] = in ? (vn + 2 * Du)[k] : 0.0f; Gn[q][c][1] = in ? (vn + 3 * Du)[k] : 0.0f;
+                }
+            }
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int k = lane + 64 * c;
-            const bool in = k < D;
-            nr[c] = in ? vn[k] : 0.0f; ni[c] = in ? vn[D + k] : 0.0f;
-            Gn[c][0] = in ? vn[2 * D + k] : 0.0f; Gn[c][1] = in ? vn[3 * D + k] : 0.0f;
-            term[c] = sr[c] * rr[c] * nr[c] + si[c] * rr[c] * ni[c] + sr[c] * ri[c] * ni[c] - si[c] * ri[c] * nr[c];
-        }
-        const float sc = total(term);
-        score = lane == 1 + ns + j ? sc : score;
-        const float dl = dloss(-1.0f, sc);
+            for (int q = 0; q < CH; ++q) {
+                float term[NC];
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int k = lane + 64 * c;
-            if (k >= D) continue;
-            gs[c][0] = gs[c][0] + dl * (rr[c] * nr[c] + ri[c] * ni[c]); gs[c][1] = gs[c][1] + dl * (rr[c] * ni[c] - ri[c] * nr[c]);
-            gr[c][0] = gr[c][0] + dl * (sr[c] * nr[c] + si[c] * ni[c]); gr[c][1] = gr[c][1] + dl * (sr[c] * ni[c] - si[c] * nr[c]);
-            const float g0 = 0.0f + dl * (sr[c] * rr[c] - si[c] * ri[c]), g1 = 0.0f + dl * (si[c] * rr[c] + sr[c] * ri[c]);     // its own slot
-            const Upd u_0 = adagrad<EXACT>(g0, Gn[c][0], lr, eps), u_1 = adagrad<EXACT>(g1, Gn[c][1], lr, eps);
-            un[k] = u_0.dt; un[2 * D + k] = u_0.dg;
-            un[D + k] = u_1.dt; un[3 * D + k] = u_1.dg;
+                for (int c = 0; c < NC; ++c)
+                    term[c] = OBJ ? sr[c] * rr[c] * nr[q][c] + si[c] * rr[c] * ni[q][c] + sr[c] * ri[c] * ni[q][c] - si[c] * ri[c] * nr[q][c]
+                                  : nr[q][c] * rr[c] * orl[c] + ni[q][c] * rr[c] * oi[c] + nr[q][c] * ri[c] * oi[c] - ni[q][c] * ri[c] * orl[c];
+                sc[q] = total(term);
+            }
+#pragma unroll
+            for (int q = 0; q < CH; ++q) {
+                if (j0 + q >= n_list) break;
+                float *un = u0 + (int64_t)(slot0 + j0 + q) * L;
+                score = lane == slot0 - 2 + j0 + q ? sc[q] : score;
+                const float dl = dloss(-1.0f, sc[q]);
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const uint32_t k = (uint32_t)lane + 64u * c;
+                    if (k >= Du) continue;
+                    float g0, g1;                                      // the negative's own slot
+                    if constexpr (OBJ) {
+                        gs[c][0] = gs[c][0] + dl * (rr[c] * nr[q][c] + ri[c] * ni[q][c]); gs[c][1] = gs[c][1] + dl * (rr[c] * ni[q][c] - ri[c] * nr[q][c]);
+                        gr[c][0] = gr[c][0] + dl * (sr[c] * nr[q][c] + si[c] * ni[q][c]); gr[c][1] = gr[c][1] + dl * (sr[c] * ni[q][c] - si[c] * nr[q][c]);
+                        g0 = 0.0f + dl * (sr[c] * rr[c] - si[c] * ri[c]); g1 = 0.0f + dl * (si[c] * rr[c] + sr[c] * ri[c]);
+                    } else {
+                        g0 = 0.0f + dl * (rr[c] * orl[c] + ri[c] * oi[c]); g1 = 0.0f + dl * (rr[c] * oi[c] - ri[c] * orl[c]);
+                        gr[c][0] = gr[c][0] + dl * (nr[q][c] * orl[c] + ni[q][c] * oi[c]); gr[c][1] = gr[c][1] + dl * (nr[q][c] * oi[c] - ni[q][c] * orl[c]);
+                        go[c][0] = go[c][0] + dl * (nr[q][c] * rr[c] - ni[q][c] * ri[c]);  go[c][1] = go[c][1] + dl * (ni[q][c] * rr[c] + nr[q][c] * ri[c]);
+                    }
+                    const Upd u_0 = adagrad<EXACT>(g0, Gn[q][c][0], lr, eps), u_1 = adagrad<EXACT>(g1, Gn[q][c][1], lr, eps);
+                    un[k] = u_0.dt; (un + 2 * Du)[k] = u_0.dg;
+                    (un + Du)[k] = u_1.dt; (un + 3 * Du)[k] = u_1.dg;
+                }
+            }
         }
-    }
+    };
+    negatives(std::false_type{}, neg_subj, ns, 3);
+    negatives(std::true_type{}, neg_obj, no, 3 + ns);
     // the losses of all scored triples at once (lane t: triple t; the positive one is triple 0)
     {
         const float label = lane == 0 ? 1.0f : -1.0f;
@@ -211,16 +216,17 @@ __global__ __launch_bounds__(256) void k_kge_group(int64_t batch, int64_t num_en
     // subject, relation, object: one AdaGrad step each on the summed gradient, with the accumulators as pulled
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int k = lane + 64 * c;
-        if (k >= D) continue;
+        const uint32_t k = (uint32_t)lane + 64u * c;
+        if (k >= Du) continue;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            const Upd us = adagrad<EXACT>(gs[c][p], vs[2 * D + p * D + k], lr, eps);
-            const Upd ur = adagrad<EXACT>(gr[c][p], vr[2 * D + p * D + k], lr, eps);
-            const Upd uo = adagrad<EXACT>(go[c][p], vo[2 * D + p * D + k], lr, eps);
-            u0[p * D + k] = us.dt; u0[2 * D + p * D + k] = us.dg;
-            u0[L + p * D + k] = ur.dt; u0[L + 2 * D + p * D + k] = ur.dg;
-            u0[2 * L + p * D + k] = uo.dt; u0[2 * L + 2 * D + p * D + k] = uo.dg;
+            const uint32_t ft = p * Du, fg = (2 + p) * Du;              // the field of the values and that of their accumulators
+            const Upd us = adagrad<EXACT>(gs[c][p], (vs + fg)[k], lr, eps);
+            const Upd ur = adagrad<EXACT>(gr[c][p], (vr + fg)[k], lr, eps);
+            const Upd uo = adagrad<EXACT>(go[c][p], (vo + fg)[k], lr, eps);
+            (u0 + ft)[k] = us.dt; (u0 + fg)[k] = us.dg;
+            (u0 + L + ft)[k] = ur.dt; (u0 + L + fg)[k] = ur.dg;
+            (u0 + 2 * L + ft)[k] = uo.dt; (u0 + 2 * L + fg)[k] = uo.dg;
         }
     }
 }
