@@ -216,6 +216,49 @@ def test_large_config_full_size():
     assert abs(r_gpu - r_32) <= 1e-5 * r_32
 
 
+def test_wide_config_full_size_first_subepochs():
+    """10,000,000 x 1,000,000, 500M entries, rank 100, 256 x 256 blocks with the boundaries bench.py uses for it (equal
+    numbers of entries per row range; column ranges of equal weight, a column as its entries + 4 per block, a column
+    heavier than an average range alone in its range) - the configuration and launch shape that bench.py times.  The
+    oracle needs about three minutes for a whole epoch of it, so the test takes the first 6 of the 256 sub-epochs:
+    every sub-epoch holds every column block once, so these 1,536 blocks - with all their entries, the entries of all
+    other blocks are left out on both sides - have everything the whole epoch has: column ranges of a single column
+    whose run in a block has more than 1,000 groups of 15, blocks with far more columns than fit into LDS, rows with
+    one entry per block.  Every value of every key against the fp32 oracle; owner map and counters exact."""
+    import dataclasses
+    import time
+    t0 = time.time()
+    w = wl.make_mf("wide")
+    d, S = 256, 6
+    print(f"case wide nnz={w.nnz} generated in {time.time() - t0:.0f} s", flush=True)
+    rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d, per_id=4.0 * d)
+    rblk = (np.searchsorted(rb, w.rows, side="right") - 1).astype(np.int16)
+    cblk = (np.searchsorted(cb, w.cols, side="right") - 1).astype(np.int16)
+    keep = ((cblk - rblk) % d) < S
+    del rblk, cblk
+    w = dataclasses.replace(w, rows=w.rows[keep], cols=w.cols[keep], vals=w.vals[keep])
+    del keep
+    print(f"  kept {w.nnz} entries of the first {S} sub-epochs ({time.time() - t0:.0f} s)", flush=True)
+    blocked = _blocked_oracle(w, rb, cb)
+    br, bc, bv, bp = blocked
+    # what the sample is there for
+    widths = np.diff(cb)
+    singles = np.flatnonzero(widths == 1)
+    assert singles.size >= 8, "column ranges of a single column"
+    longest = int(np.diff(bp)[np.arange(d)[:, None] * d + singles[None, :]].max())      # a block of such a range is one run
+    assert longest >= 1000 * 15, longest
+    assert widths.max() * w.rank * 4 > 4 * 160 * 1024, "blocks with more columns than LDS holds"
+    sched = wl.cyclic_schedule(d)[:S]
+    t1 = time.time()
+    o32 = oracle_epochs("f32", w, rb, cb, blocked, sched)
+    print(f"  oracle {time.time() - t1:.0f} s; longest column run in a block {longest} entries, widest column range {widths.max()}", flush=True)
+    srv = gpu_epochs(w, rb, cb, blocked, sched)
+    compare_state(o32, srv, exact=False, atol=1e-4)
+    r_gpu, r_32 = _rmse(srv.mf_train_sse(), w.nnz), _rmse(o32.mf_train_sse(w.m, br, bc, bv), w.nnz)
+    print(f"  rmse gpu {r_gpu:.6f} oracle {r_32:.6f}", flush=True)
+    assert abs(r_gpu - r_32) <= 1e-5 * r_32
+
+
 def test_wide_shape_scaled():
     """The wide configuration's shape at 1/100 of its size (rank 100, uniform rows, heavy columns)."""
     w = wl.make_mf("wide", scale=0.01)
