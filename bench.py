@@ -35,7 +35,7 @@ KERNEL_SOURCES = ("mf_sgd_chunk.hip", "mf_sgd.hip", "mf_device.h", "common.h")
 TRAFFIC = {"kernel_sha256_16": "", "bytes_per_launch": {"large": (0.0, 0.0), "wide": (0.0, 0.0)}}
 
 # block boundaries per workload: a column of a block weighs this many entries on top of its own (see --col-cost)
-COL_COST = {"wide": 4.0}
+COL_COST = {"wide": 3.0}
 
 
 def kernel_sources_hash():
@@ -49,7 +49,7 @@ def kernel_sources_hash():
 def measured_traffic(args, name):
     """(bytes read, bytes written) per launch from the committed counter runs, or None when the kernel sources or
     the settings are not the ones the counters were taken with."""
-    default = (args.scale == 1.0 and args.bounds == "balanced" and args.col_cost is None and args.waves == 16 and args.cache_rows == -1
+    default = (args.scale == 1.0 and args.bounds == "balanced" and args.col_cost is None and args.waves == 0 and args.cache_rows == -1
                and args.heavy_len == 0 and args.team_max == 0 and not (args.entry_kernel or args.classic or args.handoff))
     rw = TRAFFIC["bytes_per_launch"].get(name)
     if default and rw and rw[0] > 0 and kernel_sources_hash() == TRAFFIC["kernel_sha256_16"]:
@@ -346,7 +346,7 @@ def main() -> int:
     ap.add_argument("--col-cost", type=float, default=None,
                     help="balanced bounds: a column of a block weighs this many entries on top of its own (0: entries only; "
                          "default: 8, wide 4)")
-    ap.add_argument("--waves", type=int, default=16)
+    ap.add_argument("--waves", type=int, default=0, help="wavefronts per workgroup of the SGD kernel (0: library default)")
     ap.add_argument("--cache-rows", type=int, default=-1)
     ap.add_argument("--heavy-len", type=int, default=0, help="column runs at least this long are processed in groups (0: library default)")
     ap.add_argument("--team-max", type=int, default=0, help="most wavefronts per long column run (0: library default)")
@@ -435,7 +435,8 @@ def run_mf(args, name, torch, dev, full):
     del rows_d, cols_d, vals_d
 
     srv = P.ParameterServer(w.m + w.n, w.rank, d)
-    srv.set_option(P.OPT_MF_WAVES, args.waves)
+    if args.waves > 0:
+        srv.set_option(P.OPT_MF_WAVES, args.waves)
     srv.set_option(P.OPT_MF_CACHE_ROWS, args.cache_rows)
     if args.heavy_len > 0:
         srv.set_option(P.OPT_MF_HEAVY_LEN, args.heavy_len)

@@ -77,7 +77,9 @@ enum {
     PS_OPT_MF_EXACT = 1,        /* 1: the SGD kernel sums each inner product in index order with separately
                                    rounded multiplies and adds (slow; for bit-for-bit checks).  default 0 */
     PS_OPT_MF_CACHE_ROWS = 2,   /* upper bound on row factors a workgroup keeps in LDS (-1 = as many as fit) */
-    PS_OPT_MF_WAVES = 3,        /* wavefronts per workgroup in the SGD kernel: 1..16 (default 16) */
+    PS_OPT_MF_WAVES = 3,        /* wavefronts per workgroup in the SGD kernel: 1..16, or 0 (default): 16, but 12 for the
+                                   grouped kernel on data with very long column runs or mostly one entry per row
+                                   and block */
     PS_OPT_MF_PROFILE = 4,      /* 1: bracket every SGD kernel launch with a pair of events (see mf_profile_read) */
     PS_OPT_MF_GROUPED = 5,      /* 1 (default): where rank <= 128 and PS_OPT_MF_EXACT is off, process the long column
                                    runs of a block in groups of up to 15 entries with dense 16x16xr products and
@@ -88,7 +90,8 @@ enum {
                                    order, however many there are (one wavefront per key; for bit-for-bit checks
                                    against a sequential server).  0 (default): see ps_push */
     PS_OPT_MF_TEAM_MAX = 8,     /* grouped SGD kernel: the most wavefronts that take the groups of one long column run
-                                   in turn, 1..14 (default 4: one per vector unit of a compute unit) */
+                                   in turn, 1..14, or 0 (default): 4, one per vector unit of a compute unit - 8 on data
+                                   with very long column runs, where the workgroup has 12 wavefronts */
     PS_OPT_MF_CLASSIC = 9,      /* mf_sgd_epoch as on a classic parameter server (Sec. 2.1, Sec. 4.2, Sec. 4.6): no
                                    relocation, no residency - every entry pulls its two keys from the store and
                                    pushes the update terms back, counted as local or remote by the owner map as it

@@ -95,11 +95,11 @@ struct dpaps_ps {
     // options
     int opt_exact = 0;
     int64_t opt_cache_rows = -1;
-    int opt_waves = 16;
+    int opt_waves = 0;              // wavefronts per workgroup of the SGD kernels; 0: chosen by the library (dpaps_mf_waves)
     int opt_profile = 0;
     int opt_push_sequential = 0;      // 1: ps_push adds each key's terms strictly one after the other
     int opt_classic = 0;              // 1, 2: mf_sgd_epoch as on a classic parameter server (2: updates in place)
-    int opt_team_max = 4;             // most wavefronts that share one heavy run
+    int opt_team_max = 0;             // most wavefronts that share one heavy run; 0: chosen by the library (plan_teams)
     int opt_grouped = 1;              // 1: use the grouped SGD kernel where it applies
     int opt_kge_exact = 0;            // 1: the knowledge-graph step sums and divides in the order of a sequential fp32 program
     int opt_heavy_len = 48;           // column runs of a block at least this long are processed in groups
@@ -163,6 +163,7 @@ struct SgdArgs {
 // mf_sgd_chunk.hip: the kernel that processes a column's entries in groups (see there)
 int dpaps_launch_sgd_chunk(dpaps_ps *ps, const SgdArgs &a, int ntasks, int waves, hipStream_t st);
 int dpaps_launch_sgd_handoff(dpaps_ps *ps, const SgdArgs &a, int workers, hipStream_t st);
+int dpaps_mf_waves(const dpaps_ps *ps);
 
 // ps_store.hip: the two halves of ps_pull and ps_push, for steps that read the store where they use the values
 // and add up the update terms of one data point before they push them

@@ -533,7 +533,8 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
     cache_cap = std::min<int64_t>(cache_cap, f.max_multi_in_block);
     if (ps->opt_cache_rows >= 0) cache_cap = std::min<int64_t>(cache_cap, ps->opt_cache_rows);
     const size_t lds = (size_t)cache_cap * L * 4 + (size_t)ticket_cap * 4;
-    const int threads = 64 * ps->opt_waves;
+    const int waves = dpaps_mf_waves(ps);
+    const int threads = 64 * waves;
     const size_t loc_lds = (DPAPS_LOC_SLOTS + 1) * (size_t)((ps->W + 31) / 32) * sizeof(uint32_t);
 
     for (int32_t s = 0; s < num_strata; ++s) {
@@ -572,7 +573,7 @@ extern "C" int mf_sgd_epoch(ps_handle ps, const int32_t *tasks_host, const int32
             default: rc = launch_classic<4>(ps, ca, ntasks, st); break;
             }
         } else if (grouped) {
-            rc = dpaps_launch_sgd_chunk(ps, a, ntasks, ps->opt_waves, st);
+            rc = dpaps_launch_sgd_chunk(ps, a, ntasks, waves, st);
         } else if (ps->opt_exact) {
             switch (NV) {
             case 1: rc = launch_sgd<1, true>(ps, a, ntasks, threads, lds, st); break;

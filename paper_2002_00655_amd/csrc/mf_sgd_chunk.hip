@@ -113,7 +113,9 @@ __device__ __forceinline__ void solve_first() { __asm__ volatile("s_nop 4"); }
 // of that: they stay with this workgroup).  Off: plain accesses; the kernel's end publishes everything.
 // One call processes the block (rb, cb) for `worker`; all threads of the workgroup take part.
 // LONG_RUNS: the variant of the recurrence for data with column runs of very many groups (see there).
-template <int NT, bool A4, bool AGENT_H, bool LONG_RUNS>
+// RICH: compiled for at most 12 wavefronts, so with a third more registers: what does not depend on the column's
+// factor is then read ahead of the wait for it.
+template <int NT, bool A4, bool AGENT_H, bool LONG_RUNS, bool RICH = false>
 __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const int32_t worker, const int32_t rb, const int32_t cb) {
     if constexpr (!AGENT_H) {     // (in the loop, the caller looks: there all threads must take the same way)
         if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
@@ -407,6 +409,18 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                     int ck[NV];
 #pragma unroll
                     for (int cc = 0; cc < NV; ++cc) ck[cc] = ln + 64 * cc < 16 * NT ? ln + 64 * cc : 0;
+                    // the rows' components for the new h further down (lane l: components l, l + 64 of every row)
+                    float wv[CH][NV];
+                    if constexpr (RICH) {
+#pragma unroll
+                        for (int s = 0; s < CH; ++s)
+#pragma unroll
+                            for (int cc = 0; cc < NV; ++cc) wv[s][cc] = stg[s * RS + ck[cc]];
+#pragma unroll
+                        for (int s = 0; s < CH; ++s)
+#pragma unroll
+                            for (int cc = 0; cc < NV; ++cc) __asm__ volatile("" : "+v"(wv[s][cc]));
+                    }
                     for (uint32_t spins = 0; ticket_read(hsq) != (uint32_t)gi;) {
                         if constexpr (!LONG_RUNS) __builtin_amdgcn_s_sleep(1);     // (where runs are very long, the wait is all there is)
                         if ((++spins & 1023u) == 0 && (spins > (1u << 21) || ticket_read(&give_up) != 0u)) {
@@ -429,13 +443,13 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
 #pragma unroll
                         for (int q = 0; q < 4; ++q) pq[q] = __builtin_fmaf(xp[j][q], hq[j][q], pq[q]);
                     }
-                    // the rows' components for the new h further down: asked for now, so that they arrive while the
-                    // errors are being computed
-                    float wv[CH][NV];
+                    // (with fewer registers they are asked for now, so that they arrive while the errors are being computed)
+                    if constexpr (!RICH) {
 #pragma unroll
-                    for (int s = 0; s < CH; ++s)
+                        for (int s = 0; s < CH; ++s)
 #pragma unroll
-                        for (int cc = 0; cc < NV; ++cc) wv[s][cc] = stg[s * RS + ck[cc]];
+                            for (int cc = 0; cc < NV; ++cc) wv[s][cc] = stg[s * RS + ck[cc]];
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                     float p = (pq[0] + pq[1]) + (pq[2] + pq[3]);
                     // the four quarters of a row sit in the same lane of the four rows of 16 lanes: two lane swaps in
@@ -933,7 +947,7 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
 template <int NT, bool A4, int MAXT, bool LONG_RUNS>
 __global__ __launch_bounds__(MAXT) void k_mf_sgd_chunk(SgdArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
-    sgd_block<NT, A4, false, LONG_RUNS>(a, lds_f, a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1], a.tasks[3 * blockIdx.x + 2]);
+    sgd_block<NT, A4, false, LONG_RUNS, MAXT <= 768>(a, lds_f, a.tasks[3 * blockIdx.x], a.tasks[3 * blockIdx.x + 1], a.tasks[3 * blockIdx.x + 2]);
 }
 
 // ---- an epoch without barriers: column blocks handed from worker to worker ----------------------------------
@@ -1019,6 +1033,16 @@ __global__ __launch_bounds__(1024) void k_mf_sgd_handoff(SgdArgs a) {
 // the order of a row's entries.
 static bool dpaps_wide_like(const MfData &f) {
     return f.max_run_groups >= DPAPS_LONG_RUN_GROUPS || (f.num_truns > 0 && 2 * f.num_tail < 3 * f.num_truns);
+}
+
+// Wavefronts per workgroup of the SGD kernels: what PS_OPT_MF_WAVES says, else 16 - or 12 where the grouped kernel
+// runs on data of that kind: its second part has little to wait for there, and with 12 wavefronts each has a third
+// more registers, which the first part uses to read ahead of its wait for the column's factor (measured on the
+// 10M x 1M configuration: 2 % less time per launch than with 16).
+int dpaps_mf_waves(const dpaps_ps *ps) {
+    if (ps->opt_waves > 0) return ps->opt_waves;
+    const bool grouped = !ps->opt_classic && ps->opt_grouped && !ps->opt_exact && ps->L <= 128 && ps->mf.sweep_ok;
+    return grouped && dpaps_wide_like(ps->mf) ? 12 : 16;
 }
 
 // LDS plan of sgd_block: staging areas, tables and the heavy columns' factors, the two kinds of ticket counters,
@@ -1129,12 +1153,17 @@ static int plan_teams(dpaps_ps *ps, SgdArgs &a, int waves, hipStream_t st) {
     a.team_plan = nullptr;
     if (a.team == 2) {
         MfData &f = ps->mf;
+        // Most wavefronts per run: what PS_OPT_MF_TEAM_MAX says, else one per vector unit - or two where runs are
+        // very long and the workgroup has 12 wavefronts: a wavefront then has the registers to overlap its own
+        // work with its neighbour's, and a run of a thousand groups is all its block has (measured on the
+        // 10M x 1M configuration: 4 % less time per launch than with 4, while 6 is no better than 4).
+        const int tmax = ps->opt_team_max > 0 ? ps->opt_team_max : (dpaps_wide_like(f) && waves <= 12 ? 8 : 4);
         if (!f.team_plan) PS_HIP(ps, hipMalloc(&f.team_plan, (size_t)f.num_blocks * 16 * sizeof(uint32_t)));
-        if (f.team_plan_waves != a.heavy_waves * 100 + ps->opt_team_max) {
+        if (f.team_plan_waves != a.heavy_waves * 100 + tmax) {
             k_team_plan<<<(unsigned)((f.num_blocks + 255) / 256), 256, 0, st>>>(f.blk_run_ptr, f.blk_nheavy, f.run_gptr, f.num_blocks, a.heavy_waves,
-                                                                               ps->opt_team_max, f.team_plan);
+                                                                               tmax, f.team_plan);
             PS_HIP(ps, hipGetLastError());
-            f.team_plan_waves = a.heavy_waves * 100 + ps->opt_team_max;
+            f.team_plan_waves = a.heavy_waves * 100 + tmax;
         }
         a.team_plan = f.team_plan;
     }

@@ -788,7 +788,7 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
     switch (option) {
     case PS_OPT_MF_EXACT: ps->opt_exact = value != 0; return PS_OK;
     case PS_OPT_MF_CACHE_ROWS: if (value < -1) return PS_EINVAL; ps->opt_cache_rows = value; return PS_OK;
-    case PS_OPT_MF_WAVES: if (value < 1 || value > 16) return PS_EINVAL; ps->opt_waves = (int)value; return PS_OK;
+    case PS_OPT_MF_WAVES: if (value < 0 || value > 16) return PS_EINVAL; ps->opt_waves = (int)value; return PS_OK;
     case PS_OPT_MF_PROFILE: ps->opt_profile = value != 0; return PS_OK;
     case PS_OPT_MF_GROUPED: ps->opt_grouped = value != 0; return PS_OK;
     case PS_OPT_PUSH_SEQUENTIAL: ps->opt_push_sequential = value != 0; return PS_OK;
@@ -807,7 +807,7 @@ extern "C" int ps_set_option(ps_handle ps, int32_t option, int64_t value) {
         return PS_OK;
     }
     case PS_OPT_KGE_EXACT: ps->opt_kge_exact = value != 0; return PS_OK;
-    case PS_OPT_MF_TEAM_MAX: if (value < 1 || value > 14) return PS_EINVAL; ps->opt_team_max = (int)value; return PS_OK;
+    case PS_OPT_MF_TEAM_MAX: if (value < 0 || value > 14) return PS_EINVAL; ps->opt_team_max = (int)value; return PS_OK;
     case PS_OPT_MF_HEAVY_LEN:
         if (value < 1 || value > (1 << 30)) return PS_EINVAL;
         ps->opt_heavy_len = (int)value; return PS_OK;

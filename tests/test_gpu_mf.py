@@ -142,7 +142,7 @@ def test_duplicate_cells_and_empty_blocks():
 # ---------------------------------------------------------------------------
 # the configurations, normal arithmetic: tolerance of the stated bar
 # ---------------------------------------------------------------------------
-def _config_parity(w, d, epochs, schedule=None, rmse_each_epoch=False):
+def _config_parity(w, d, epochs, schedule=None, rmse_each_epoch=False, options=()):
     rb, cb = wl.equal_bounds(w.m, d), wl.equal_bounds(w.n, d)
     blocked = _blocked_oracle(w, rb, cb)
     sched = wl.cyclic_schedule(d) if schedule is None else schedule
@@ -151,7 +151,7 @@ def _config_parity(w, d, epochs, schedule=None, rmse_each_epoch=False):
     print(f"  oracle fp64 ...", flush=True)
     o64 = oracle_epochs("f64", w, rb, cb, blocked, sched, epochs=1)
     print(f"  gpu ...", flush=True)
-    srv = gpu_epochs(w, rb, cb, blocked, sched, epochs=1)
+    srv = gpu_epochs(w, rb, cb, blocked, sched, epochs=1, options=options)
     got, _ = compare_state(o32, srv, exact=False, atol=1e-4)           # after one epoch, vs fp32 oracle
     want64 = o64.pull(np.arange(w.m + w.n))
     print(f"  max abs difference to the fp64 oracle: {np.abs(got - want64).max():.3e}", flush=True)
@@ -218,7 +218,7 @@ def test_large_config_full_size():
 
 def test_wide_config_full_size_first_subepochs():
     """10,000,000 x 1,000,000, 500M entries, rank 100, 256 x 256 blocks with the boundaries bench.py uses for it (equal
-    numbers of entries per row range; column ranges of equal weight, a column as its entries + 4 per block, a column
+    numbers of entries per row range; column ranges of equal weight, a column as its entries + 3 per block, a column
     heavier than an average range alone in its range) - the configuration and launch shape that bench.py times.  The
     oracle needs about three minutes for a whole epoch of it, so the test takes the first 6 of the 256 sub-epochs:
     every sub-epoch holds every column block once, so these 1,536 blocks - with all their entries, the entries of all
@@ -231,7 +231,7 @@ def test_wide_config_full_size_first_subepochs():
     w = wl.make_mf("wide")
     d, S = 256, 6
     print(f"case wide nnz={w.nnz} generated in {time.time() - t0:.0f} s", flush=True)
-    rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d, per_id=4.0 * d)
+    rb, cb = wl.balanced_bounds(w.rows, w.m, d), wl.balanced_bounds(w.cols, w.n, d, per_id=3.0 * d)
     rblk = (np.searchsorted(rb, w.rows, side="right") - 1).astype(np.int16)
     cblk = (np.searchsorted(cb, w.cols, side="right") - 1).astype(np.int16)
     keep = ((cblk - rblk) % d) < S
@@ -266,15 +266,18 @@ def test_wide_shape_scaled():
     _config_parity(w, 256, epochs=1)
 
 
-def test_very_long_column_runs():
+@pytest.mark.parametrize("waves,team", [(0, 0), (16, 0), (12, 3), (16, 14), (5, 0)])
+def test_very_long_column_runs(waves, team):
     """Columns with half of all rows, few row blocks: column runs of 2,500 entries (167 groups) in a block, which the
-    grouped kernel takes with the variant of its recurrence for runs of 64 groups and more."""
+    grouped kernel takes with the variant of its recurrence for runs of 64 groups and more - with the workgroup and
+    team sizes the library chooses for such data (12 wavefronts, up to 8 per run) and with others."""
+    OPT_TEAM_MAX = 8
     w = wl.make_mf("wide", scale=0.002)
     d = 4
     counts = np.bincount(w.cols, minlength=w.n)
     print(f"case wide@0.002 {w.m} x {w.n} nnz={w.nnz} longest column {counts.max()}", flush=True)
     assert counts.max() // d >= 64 * 15
-    _config_parity(w, d, epochs=2)
+    _config_parity(w, d, epochs=2, options=[(OPT_WAVES, waves), (OPT_TEAM_MAX, team)])
 
 
 @pytest.mark.parametrize("rank,waves,grouped", [(1, 16, 1), (16, 3, 1), (50, 16, 1), (64, 8, 1), (100, 16, 1), (100, 1, 1), (128, 16, 1),
