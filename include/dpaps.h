@@ -16,11 +16,27 @@
  * the order seen on `stream` is unchanged.
  *
  * Keys are 0 .. num_keys-1; each key holds a vector of value_len fp32 values
- * (Sec. 4.1 "Settings and measures": "each key held a vector of parameter
- * values"; dense storage, Sec. 3.7).  There are num_workers workers, each its
- * own node.  Every key has a static home node, home(k) = k / ceil(num_keys /
+ * (Sec. 4.1 "Settings and measures": the experiments keep one vector of
+ * parameter values under every key; dense storage, Sec. 3.7).  There are
+ * num_workers workers, each its own node.  Every key has a static home node, home(k) = k / ceil(num_keys /
  * num_workers) (range partitioning, Sec. 3.5), and a dynamic owner node,
  * initially its home (Sec. 3.1 "Location management").
+ *
+ * Where a call waits.  "Asynchronous" holds for the steady state; these calls wait for
+ * `stream` (hipStreamSynchronize) or for the device, and may allocate device memory:
+ *   ps_create, ps_destroy, mf_load_ratings, mf_block_ratings   set-up calls: allocate, wait for the device;
+ *   ps_status, ps_stats, mf_train_sse                          return a value to the host: wait for `stream`;
+ *   ps_push, kge_sgd_step, kge_sgd_epoch, mf_train_sse         scratch of the library grows with the largest
+ *       call so far: a call that outgrows it waits for the work that uses the old scratch, frees it and
+ *       allocates (the push's scratch: waits for the device; the step's own: for `stream`); calls of a size
+ *       seen before do not wait.  kge_sgd_step / kge_sgd_epoch with loss_host_out also wait for `stream` to hand back the loss;
+ *   mf_sgd_epoch     the first epoch after mf_load_ratings allocates a small per-block plan; an epoch whose
+ *       schedule differs from the previous call's waits for `stream` before it replaces the schedule on the
+ *       device (and allocates if it is longer); repeated epochs with one schedule do neither;
+ *   mf_sgd_epoch_handoff   allocates its state on first use, and always waits for `stream` at its end: it
+ *       returns the order of the epoch to the host;
+ *   ps_set_option(PS_OPT_LOCATION_CACHES)   waits for the device, frees and allocates the caches.
+ * ps_pull, ps_localize, ps_owner and ps_push_noalloc neither wait nor allocate.
  *
  * Errors.  Host-visible mistakes (null pointers, sizes, worker ids, a bad
  * schedule) are reported by the call itself and nothing is changed.  A key

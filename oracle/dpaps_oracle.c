@@ -319,7 +319,7 @@ int orc_mf_block_ratings(int64_t m, int64_t n, int64_t nnz, const int32_t *rows,
  * has which block changes from subepoch to subepoch).  tasks[t] = (worker, row
  * block, column block); stratum s holds tasks[stratum_ptr[s] .. stratum_ptr[s+1]).
  * Per subepoch: every task localizes the keys of its two factor blocks (Sec.
- * 2.3: "move parameters of a block to the node that accesses them"), then
+ * 2.3: the parameters of a block are relocated to the node that will work on the block), then
  * processes its entries one by one with pull / SGD step / push, then all
  * workers meet at a barrier (Appendix A).  Within a subepoch every access must
  * be local (Sec. 4.1); anything else is reported as ORC_EREMOTE. */

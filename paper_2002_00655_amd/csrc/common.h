@@ -158,6 +158,7 @@ struct SgdArgs {
     // an epoch with hand-over of column blocks instead of barriers (k_mf_sgd_handoff only)
     uint32_t *col_state;        // d_col words: visits << 1 | held
     int32_t *sched;             // per worker and step: column block, visits before
+    uint32_t take_spins;        // looks for a free column block after which a worker gives up (PS_ESTALL)
 };
 
 // mf_sgd_chunk.hip: the kernel that processes a column's entries in groups (see there)

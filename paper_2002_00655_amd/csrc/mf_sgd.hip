@@ -359,7 +359,7 @@ static int launch_sgd(dpaps_ps *ps, const SgdArgs &a, int ntasks, int threads, s
 // Sec. 4.6): nothing is relocated and nothing stays with the worker.  One wavefront per task walks its block in
 // stored order; every entry is a pull of its two keys from the store, the step, and a push that reads the
 // stored values again and adds the update terms (in_place = 1: the worker updates the two rows where they are,
-// without the second read - "working directly on the data store", Sec. 4.4).  Every access is counted as
+// without the second read - the variant of Sec. 4.4 in which workers operate on the server's own copy).  Every access is counted as
 // local or remote by the owner map as it stands, with the messages a remote one costs (request to the home
 // node, forward if the key lives elsewhere, reply; the two keys of a call share messages to one destination,
 // Sec. 3.7).

@@ -44,6 +44,8 @@
 #include "common.h"
 #include "mf_device.h"
 
+#include <algorithm>
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -984,7 +986,7 @@ __device__ __forceinline__ int handoff_take(const SgdArgs &a, const uint32_t *to
         __builtin_amdgcn_s_sleep(8);
         if ((spins & 63u) == 0u) {
             if (rl_i(__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), 0) != 0) return -1;
-            if (spins > (1u << 21)) { atomicExch(a.err, PS_ESTALL); return -1; }
+            if (spins > a.take_spins) { atomicExch(a.err, PS_ESTALL); return -1; }
         }
     }
 }
@@ -1173,6 +1175,12 @@ static int plan_teams(dpaps_ps *ps, SgdArgs &a, int waves, hipStream_t st) {
 // One launch for a whole epoch: `workers` workgroups of 16 wavefronts, worker w on row block w (see k_mf_sgd_handoff).
 int dpaps_launch_sgd_handoff(dpaps_ps *ps, const SgdArgs &a_in, int workers, hipStream_t st) {
     SgdArgs a = a_in;
+    // A worker without a block looks again about every microsecond.  While it waits, the blocks it still needs are
+    // being worked on by others, and in the worst case it is the last to get each of them: the bound on its looks
+    // covers the whole epoch at a generous microsecond per entry (2 million looks at least) - it is there for
+    // inconsistent tables, not to time out a slow epoch.
+    const int64_t looks = std::max<int64_t>((int64_t)1 << 21, 8 * ps->mf.nnz);
+    a.take_spins = (uint32_t)std::min<int64_t>(looks, 0x7FFFFFFF);
     const int rc = plan_teams(ps, a, 16, st);
     if (rc) return rc;
     switch ((a.L + 15) / 16) {

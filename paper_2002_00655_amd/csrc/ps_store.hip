@@ -759,7 +759,14 @@ int dpaps_take_error(dpaps_ps *ps, hipStream_t st) {
     if (e != 0) {
         PS_HIP(ps, hipMemsetAsync(ps->err, 0, sizeof(int32_t), st));
         PS_HIP(ps, hipStreamSynchronize(st));
-        ps->last_error = "a key or index was out of range in an earlier call";
+        switch (e) {
+        case PS_EKEY: ps->last_error = "a key or index was out of range in an earlier call"; break;
+        case PS_EREMOTE: ps->last_error = "an SGD task touched a parameter that is not allocated to its worker"; break;
+        case PS_ESTALL: ps->last_error = "a kernel gave up a wait that did not end (inconsistent layout tables, or more workgroups than the device runs at once)"; break;
+        case PS_ELAYOUT: ps->last_error = "the ratings are not laid out block by block as mf_load_ratings requires"; break;
+        case PS_ELIMIT: ps->last_error = "the ratings exceed a limit of the layout (rows with several entries per block, or entries per row or column in a block)"; break;
+        default: ps->last_error = "a kernel of an earlier call reported an error"; break;
+        }
     }
     return e;
 }

@@ -19,6 +19,18 @@ from paper_2002_00655_amd import workloads as wl
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "mf_step_3x3.txt")
 
 
+def test_golden_file_is_what_its_generator_writes():
+    """The expected values of the hand-computed example come from exact fractions (tests/golden/make_mf_step_3x3.py,
+    which imports nothing of the oracle or the library)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("make_mf_step_3x3", os.path.join(os.path.dirname(GOLDEN), "make_mf_step_3x3.py"))
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    stored = [l.strip() for l in open(GOLDEN)]
+    for line in gen.lines():
+        assert line in stored, line
+
+
 def _install(orc, W0, H0):
     """Initial factors go in through push onto the zeroed store (0 + x = x exactly)."""
     m, n = W0.shape[0], H0.shape[0]
