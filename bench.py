@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # counters read for a plain 1 GiB copy; summaries under profiles/).  Only valid for the kernel sources they were
 # taken with and for the default settings of the workload: bytes read, bytes written.
 KERNEL_SOURCES = ("mf_sgd_chunk.hip", "mf_sgd.hip", "mf_device.h", "common.h")
-TRAFFIC = {"kernel_sha256_16": "52bfc29f50eadfe0",
-           "bytes_per_launch": {"large": (143_686_477.0, 122_989_105.0), "wide": (1_324_750_711.0, 953_170_690.0)}}
+TRAFFIC = {"kernel_sha256_16": "9e67f1d175fd2620",
+           "bytes_per_launch": {"large": (147_027_414.0, 125_866_524.0), "wide": (1_324_690_933.0, 953_166_649.0)}}
 
 # block boundaries per workload: a column of a block weighs this many entries on top of its own (see --col-cost)
 COL_COST = {"wide": 3.0}
