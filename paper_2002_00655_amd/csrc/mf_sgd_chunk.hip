@@ -48,6 +48,7 @@
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define CH 15                    // entries per group (the 16th row of X is the column's row)
 #define AUX_SC1 16               // cache policy of a buffer access: agent scope
@@ -109,6 +110,7 @@ __device__ __forceinline__ void solve_first() { __asm__ volatile("s_nop 4"); }
 
 // NT = number of 16-component tiles of a factor row (rank <= 16 NT); A4: the rank is a multiple of 4,
 // so every row starts on a 16-byte boundary and is read in 16-byte pieces
+// (otherwise in 8-byte pieces where the rank is even, in 4-byte pieces where it is odd)
 // AGENT_H: the column factors and the owner map are read and written with agent-scope accesses, which the caches
 // of a compute die pass through to memory, so that the workgroup that takes the column block next - on any die -
 // reads what this one wrote, without a write-back or an invalidation of whole caches (the row factors need none
@@ -136,6 +138,7 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
     const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
     const int n16_ = lane & 15, hi_ = lane >> 4;
     const int L = L_;
+    const bool even_rank = (L & 1) == 0;     // (only looked at where the rank is no multiple of 4: rows then start on 8-byte boundaries)
     const bool tail = lane + 64 * (NV - 1) < L;
     const int hwaves = a.heavy_waves;                                  // wavefronts 0 .. hwaves-1 take the heavy runs
     float *stg = lds_f + (size_t)wave * 16 * RS;                       // this wavefront's X: 16 rows (heavy wavefronts only)
@@ -286,6 +289,15 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                     if constexpr (A4) {
                         // may run past the row's end (into the next row, or past the buffer's end)
                         xp[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)goff + 64 * j, 0, 0));
+                    } else if (even_rank) {
+                        // rows start on 8-byte boundaries: two pieces of two components (both exist or neither)
+#pragma unroll
+                        for (int q = 0; q < 4; q += 2) {
+                            const u32x2 pr = __builtin_amdgcn_raw_buffer_load_b64(
+                                wbuf, (16 * j + 4 * hi + q < L ? (int)goff : (int)wspan) + 64 * j + 4 * q, 0, 0);
+                            const uint32_t p0 = pr[0], p1 = pr[1];
+                            xp[j][q] = __uint_as_float(p0); xp[j][q + 1] = __uint_as_float(p1);
+                        }
                     } else {
 #pragma unroll
                         for (int q = 0; q < 4; ++q)
@@ -577,10 +589,18 @@ __device__ __forceinline__ void sgd_block(const SgdArgs &a, float *lds_f, const 
                         // has been seen to pick element 0 every time)
                         const float r0 = acc[0], r1 = acc[1], r2 = acc[2], r3 = acc[3];
                         const float rr[4] = {r0, r1, r2, r3};
+                        if (even_rank) {
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(rr[q]), wbuf,
-                                                                  (int)(16 * tile + 4 * hi + q < L ? dst : wspan) + 64 * tile + 4 * q, 0, 0);
+                            for (int q = 0; q < 4; q += 2) {
+                                const u32x2 pr = {__float_as_uint(rr[q]), __float_as_uint(rr[q + 1])};
+                                __builtin_amdgcn_raw_buffer_store_b64(pr, wbuf, (int)(16 * tile + 4 * hi + q < L ? dst : wspan) + 64 * tile + 4 * q, 0, 0);
+                            }
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(rr[q]), wbuf,
+                                                                      (int)(16 * tile + 4 * hi + q < L ? dst : wspan) + 64 * tile + 4 * q, 0, 0);
+                        }
                     }
                 }
                 // ---- hand the rows on: the stores must have completed before the tickets move ---------
